@@ -1,0 +1,139 @@
+"""Pins for the oracle's pruning rule (Sec. 4.1, Sec. 4.5): closed forms, brute force, the
+paper's worked-example counts.  CPU only."""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import prism_oracle as O
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def test_cv_closed_form():
+    # {1,2,3,4}: mean 2.5, population variance 1.25
+    assert abs(O.coefficient_of_variation([1, 2, 3, 4]) - math.sqrt(1.25) / 2.5) < 1e-15
+    assert abs(O.coefficient_of_variation([1, 2, 3, 4]) - 0.4472135955) < 1e-9
+    assert abs(O.coefficient_of_variation([-1, -2, -3, -4]) - 0.4472135955) < 1e-9   # absolute value
+
+
+def test_gate_branches():
+    assert O.gate_open([1, 2, 3, 4], 0.44) and not O.gate_open([1, 2, 3, 4], 0.45)
+    assert not O.gate_open([2.5, 2.5, 2.5], 0.0)             # no dispersion: nothing to separate
+    assert O.gate_open([-1.0, 1.0], 100.0)                   # mean 0, std > 0: CV is infinite
+    assert O.gate_open([1, 2, 3, 4], 0.0)
+
+
+def test_rank_order_ties_prefer_lower_index():
+    assert list(O.rank_order([1.0, 3.0, 3.0, 2.0, 3.0])) == [1, 2, 4, 3, 0]
+
+
+def _sse(groups):
+    return sum(sum((x - sum(g) / len(g)) ** 2 for x in g) for g in groups if g)
+
+
+def _splits_to_groups(x, splits):
+    b = [0] + list(splits) + [len(x)]
+    return [list(x[b[i]:b[i + 1]]) for i in range(len(b) - 1)]
+
+
+@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("k", [2, 3, 4])
+def test_kmeans_matches_brute_force_over_contiguous_splits(seed, k):
+    r = np.random.default_rng(seed)
+    n = int(r.integers(k, 13))
+    x = np.sort(r.normal(size=n) * (1 + 3 * (r.random(n) > 0.5)))[::-1]
+    best = min(itertools.combinations(range(1, n), k - 1), key=lambda s: (round(_sse(_splits_to_groups(x, s)), 12), s))
+    got = O.kmeans_1d_splits(x, k)
+    assert abs(_sse(_splits_to_groups(x, got)) - _sse(_splits_to_groups(x, best))) < 1e-10
+    assert tuple(got) == best
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_contiguous_optimum_is_the_global_kmeans_optimum(seed):
+    """All k^n labelings for n <= 8: no non-contiguous clustering has a lower SSE."""
+    r = np.random.default_rng(100 + seed)
+    n, k = 8, 3
+    x = np.sort(r.normal(size=n))[::-1]
+    best = math.inf
+    for lab in itertools.product(range(k), repeat=n):
+        if len(set(lab)) < k:
+            continue
+        best = min(best, _sse([[x[i] for i in range(n) if lab[i] == c] for c in range(k)]))
+    got = _sse(_splits_to_groups(x, O.kmeans_1d_splits(x, k)))
+    assert abs(got - best) < 1e-12
+
+
+def test_kmeans_two_blobs_split_at_the_gap_and_tie_rule():
+    x = np.array([10.2, 10.1, 9.9, 9.8, 1.2, 1.0, 0.9])
+    assert O.kmeans_1d_splits(x, 2) == [4]
+    # {2 | 1 0} and {2 1 | 0} have the same SSE: smallest split position wins
+    assert O.kmeans_1d_splits(np.array([2.0, 1.0, 0.0]), 2) == [1]
+    assert O.kmeans_1d_splits(np.array([5.0, 4.0, 3.0]), 3) == [1, 2]
+    assert O.kmeans_1d_splits(np.array([5.0, 4.0, 3.0]), 1) == []
+
+
+def test_kmeans_agrees_with_library_lloyd_on_separated_data():
+    """Special case where an iterative library K-Means reaches the optimum: three far-apart blobs."""
+    from sklearn.cluster import KMeans
+    r = np.random.default_rng(7)
+    x = np.concatenate([r.normal(8, .3, 5), r.normal(0, .3, 9), r.normal(-7, .3, 6)])
+    x = np.sort(x)[::-1]
+    lab = KMeans(3, n_init=10, random_state=0).fit(x[:, None]).labels_
+    lib_splits = [i for i in range(1, len(x)) if lab[i] != lab[i - 1]]
+    assert O.kmeans_1d_splits(x, 3) == lib_splits == [5, 14]
+
+
+def _golden_events():
+    out = []
+    for line in open(os.path.join(GOLDEN, "working_example_sec4_5.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, k, tau, scores, counts, gate, term = [f.strip() for f in line.split("|")]
+        out.append((name, int(k), float(tau), [float(s) for s in scores.split()],
+                    [int(c) for c in counts.split()], bool(int(gate)), bool(int(term))))
+    return out
+
+
+@pytest.mark.parametrize("ev", _golden_events(), ids=lambda e: e[0])
+def test_paper_worked_example_counts(ev):
+    name, K_rem, tau, scores, (n_sel, n_def, n_drop), gate, term = ev
+    r = O.route(scores, K_rem, 3, tau)
+    assert r.gate == gate
+    assert int((r.fate == O.SELECTED).sum()) == n_sel
+    assert int((r.fate == O.DEFERRED).sum()) == n_def
+    assert int((r.fate == O.DROPPED).sum()) == n_drop
+    assert (r.terminate and r.pruned) == term
+    # drop-only keeps selected + deferred, three-way keeps only deferred
+    assert int(O.keep_mask(r, O.MODE_DROP_ONLY).sum()) == n_sel + n_def
+    assert int(O.keep_mask(r, O.MODE_THREE_WAY).sum()) == n_def
+
+
+def test_route_fates_follow_cluster_means_and_rank():
+    s = [0.1, 5.0, 0.2, 9.0, 5.1, 0.0, 4.9]
+    r = O.route(s, 2, 3, 0.0)                    # rank 2 is 5.1 -> boundary = {5.1, 5.0, 4.9}
+    assert list(r.fate) == [O.DROPPED, O.DEFERRED, O.DROPPED, O.SELECTED, O.DEFERRED, O.DROPPED, O.DEFERRED]
+    assert list(r.cluster) == [2, 1, 2, 0, 1, 2, 1]
+    r = O.route(s, 1, 3, 0.0)                    # rank 1 is in the top cluster: nothing is selected
+    assert (r.fate == O.SELECTED).sum() == 0 and (r.fate == O.DEFERRED).sum() == 1
+    r = O.route(s, 5, 3, 0.0)                    # boundary is the lowest cluster: nothing dropped
+    assert (r.fate == O.DROPPED).sum() == 0 and (r.fate == O.SELECTED).sum() == 4
+
+
+def test_route_degenerate_cases():
+    assert not O.route([1.0, 2.0, 3.0], 3, 3, 0.0).pruned          # n_live <= K: nothing may be dropped
+    assert not O.route([4.0, 4.0, 4.0, 4.0], 2, 3, 0.0).pruned     # a single distinct score
+    r = O.route([4.0, 4.0, 1.0, 1.0, 1.0], 1, 3, 0.0)              # two distinct scores -> two clusters
+    assert r.pruned and r.n_clusters == 2 and list(r.fate) == [1, 1, 0, 0, 0]
+    # a planted mistake must be caught: K-th rank is 1-indexed (K = 2 of [9 | 5 5 | 1]) -> 9 selected
+    assert list(O.route([9.0, 5.0, 5.1, 1.0], 2, 3, 0.0).fate) == [O.SELECTED, O.DEFERRED, O.DEFERRED, O.DROPPED]
+
+
+def test_gamma_formula():
+    a = [1, 2, 3, 4]
+    assert O.goodman_kruskal_gamma(a, [10, 20, 30, 40]) == 1.0
+    assert O.goodman_kruskal_gamma(a, [4, 3, 2, 1]) == -1.0
+    # pairs: 6; swapping the two middle ones reverses exactly one pair -> (5 - 1) / 6
+    assert abs(O.goodman_kruskal_gamma(a, [1, 3, 2, 4]) - 4 / 6) < 1e-15
