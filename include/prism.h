@@ -1,0 +1,203 @@
+/*
+ * prism.h - C ABI of the MI355X (gfx950) monolithic-forwarding reranker library.
+ *
+ * The library selects the top-K of N candidate documents for a query (paper Sec. 2.1,
+ * problem statement) with ONE batched forward of a decoder-only cross-encoder over all
+ * (query, candidate) sequences (Sec. 3.3, monolithic forwarding) and progressive cluster
+ * pruning between layers (Sec. 4.1).  Every step runs in HIP kernels; the host side only
+ * sequences launches and reads back the per-checkpoint keep mask.
+ *
+ * Conventions
+ *   - Plain C types only.  Every pointer is tagged [host] or [device] below.
+ *   - Matrices are row-major [out_features, in_features]; a projection is y = x W^T.
+ *   - dtype: PRISM_DTYPE_FP32 or PRISM_DTYPE_BF16 is the storage type of all weights and
+ *     the operand type of the layer GEMMs.  The residual stream is fp32 in both modes.
+ *   - All entry points return PRISM_OK (0) or a negative PRISM_E* code; nothing throws,
+ *     aborts or exits; outputs are untouched on error.  prism_last_error() gives detail.
+ *   - A context is single-caller.  Different contexts may run concurrently.
+ */
+#ifndef PRISM_H_
+#define PRISM_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PRISM_OK            0
+#define PRISM_EINVAL       (-1)  /* null / negative / zero-length input, token id out of range, K <= 0 */
+#define PRISM_ECAP         (-2)  /* pool does not fit under hbm_cap_bytes even with chunking */
+#define PRISM_EHIP         (-3)  /* a HIP call failed; see prism_last_error() */
+#define PRISM_ENOMEM       (-4)  /* device or host allocation failed */
+#define PRISM_EUNSUPPORTED (-5)  /* shape not supported by the kernels of the chosen dtype */
+
+#define PRISM_DTYPE_FP32 0
+#define PRISM_DTYPE_BF16 1
+
+#define PRISM_MODE_DROP_ONLY  0  /* Sec. 7: only hopeless candidates are pruned; survivors reach full depth */
+#define PRISM_MODE_THREE_WAY  1  /* Sec. 4.1: selected leave early, deferred continue, early termination */
+#define PRISM_MODE_NO_PRUNING 2  /* plain full-depth forward of every candidate */
+
+#define PRISM_MAX_CANDS    4096  /* candidates per call */
+#define PRISM_MAX_CLUSTERS 8
+#define PRISM_MAX_SEQ      8192  /* tokens per (query + candidate) sequence */
+
+/* fates written to prism_report.ev_fate (Sec. 4.1) */
+#define PRISM_FATE_NOT_LIVE (-1)
+#define PRISM_FATE_DROPPED    0
+#define PRISM_FATE_DEFERRED   1
+#define PRISM_FATE_SELECTED   2
+
+typedef struct prism_ctx prism_ctx;
+
+/* Architecture of the reranker (decoder-only, causal; Sec. 2.1).  Sizes in elements. */
+typedef struct {
+  int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+  float   rms_eps, rope_base;
+  int32_t dtype;    /* PRISM_DTYPE_* */
+  int32_t qk_norm;  /* 1: per-head RMSNorm on q and k (over head_dim) before RoPE */
+} prism_model;
+
+/* One transformer layer.  attn_norm, ffn_norm: [hidden]; wq: [n_q_heads*head_dim, hidden];
+ * wk, wv: [n_kv_heads*head_dim, hidden]; q_norm, k_norm: [head_dim] (ignored if !qk_norm);
+ * wo: [hidden, n_q_heads*head_dim]; w_gate, w_up: [ffn, hidden]; w_down: [hidden, ffn]. */
+typedef struct {
+  const void *attn_norm, *wq, *wk, *wv, *q_norm, *k_norm, *wo, *ffn_norm, *w_gate, *w_up, *w_down;
+} prism_layer_weights;
+
+typedef struct {
+  const void *embed;                  /* [device] [vocab, hidden] */
+  const prism_layer_weights *layers;  /* [host] array of n_layers structs; the tensor pointers inside are
+                                         [device] if layer_residency == 0, [pinned host] if 1 */
+  const void *final_norm;             /* [device] [hidden] */
+  const void *w_yes, *w_no;           /* [device] [hidden] each (a tied head points into embed rows) */
+  int32_t layer_residency;            /* 0: device; 1: pinned host, streamed one layer ahead (Sec. 4.2) */
+} prism_weights;
+
+typedef struct {
+  const int32_t *checkpoint_layers;   /* [host] 1-indexed: the check runs on the output of layer l, before l+1 */
+  int32_t n_checkpoints;
+  float   cv_threshold;               /* dispersion threshold tau (Sec. 4.1); gate opens iff std > tau*|mean| */
+  int32_t n_clusters;                 /* k of the K-Means step, 2..PRISM_MAX_CLUSTERS; 0 -> 3 */
+  int32_t mode;                       /* PRISM_MODE_* */
+  int32_t chunk_cands;                /* Sec. 4.3 chunked execution: candidates per chunk; 0 = whole pool */
+  int64_t hbm_cap_bytes;              /* cap on library-owned device memory; 0 = unlimited */
+  void   *stream;                     /* hipStream_t of the caller, or NULL for a library-owned stream */
+} prism_options;
+
+/* Optional per-call record.  The caller allocates every array ([host]); an "event" is one
+ * scoring of the live set: each evaluated checkpoint plus the final scoring.  Rows of
+ * ev_scores / ev_fate are indexed by ORIGINAL candidate index. */
+typedef struct {
+  int32_t  cap_events;      /* in: capacity of the ev_* arrays, in events (n_checkpoints + 1 suffices) */
+  int32_t  n_cands;         /* in: row length of ev_scores / ev_fate (>= n_cands of the call) */
+  int32_t  n_events;        /* out */
+  int32_t *ev_layer;        /* out [cap_events] layer whose output was scored (n_layers = final) */
+  int32_t *ev_n_before;     /* out [cap_events] live candidates scored */
+  int32_t *ev_n_after;      /* out [cap_events] live candidates that continue */
+  int32_t *ev_tokens_after; /* out [cap_events] live tokens that continue */
+  int32_t *ev_gate;         /* out [cap_events] 1 if the dispersion gate fired */
+  int32_t *ev_n_clusters;   /* out [cap_events] clusters used (0 if no clustering ran) */
+  double  *ev_mean;         /* out [cap_events] mean of the live scores */
+  double  *ev_std;          /* out [cap_events] population std of the live scores */
+  float   *ev_scores;       /* out [cap_events * n_cands]; NaN where the candidate was not live */
+  int8_t  *ev_fate;         /* out [cap_events * n_cands]; PRISM_FATE_* */
+  double   ms_total;        /* out: GPU time of the call, first launch to last (HIP events) */
+  double   ms_layers;       /* out: GPU time inside transformer layers */
+  double   ms_checks;       /* out: GPU time in scoring + pruning + compaction */
+  int64_t  token_layers;    /* out: sum over executed layers of live tokens */
+  int64_t  peak_hbm_bytes;  /* out: library-owned device memory at its peak */
+  int64_t  bytes_streamed;  /* out: host->device weight bytes copied during the call */
+  int32_t  layers_run;      /* out */
+} prism_report;
+
+/* Build a context.  Device-resident layer weights are repacked once into library-owned HBM
+ * (fused [wq;wk;wv] and [w_gate;w_up] operands); pinned-host layer weights are borrowed and
+ * read asynchronously by every prism_select, so they must stay mapped and unmodified until
+ * prism_destroy.  embed, final_norm, w_yes, w_no are borrowed in place.  The option arrays
+ * are copied. */
+int prism_create(const prism_model *model, const prism_weights *weights, const prism_options *options,
+                 prism_ctx **out_ctx);
+
+/* Top-K selection (Sec. 2.1).  All pointers [host].  Sequence c is query ++ cand_tokens[c], positions
+ * restart at 0 for every sequence.  out_idx / out_scores hold >= K entries; *out_count = min(K, n_cands).
+ * Order: best first, ties by lower candidate index.  Synchronous: returns after the results are on the
+ * host.  K >= n_cands disables pruning.  report may be NULL. */
+int prism_select(prism_ctx *ctx, const int32_t *query_tokens, int32_t query_len,
+                 const int32_t *const *cand_tokens, const int32_t *cand_lens, int32_t n_cands,
+                 int32_t K, int32_t *out_idx, float *out_scores, int32_t *out_count,
+                 prism_report *report);
+
+/* Teacher forcing for parity tests: masks [host] is [n_events][n_cands] of 0/1 by ORIGINAL candidate index
+ * (copied); at the e-th evaluated checkpoint the library still scores and routes, but keeps exactly the
+ * candidates with mask 1 among the live ones.  NULL clears it. */
+int prism_set_forced_keep(prism_ctx *ctx, const int8_t *masks, int32_t n_events, int32_t n_cands);
+
+void prism_destroy(prism_ctx *ctx);
+const char *prism_strerror(int code);
+const char *prism_last_error(void);   /* thread-local detail of the last failure */
+
+/* ------------------------------------------------------------------------------------------------
+ * Kernel-level entry points: one call per step of the path, on caller-owned [device] buffers, on the
+ * given hipStream_t (NULL = default stream).  They launch exactly the kernels prism_select uses and
+ * return without synchronising unless stated.  Used by the parity tests and micro-benchmarks.
+ * ------------------------------------------------------------------------------------------------ */
+
+/* Pack + embed (Sec. 4.5: the forward begins at the embedding layer): X[t,:] = table[tokens[t],:] as fp32. */
+int prism_op_embed(const int32_t *tokens, int32_t T, const void *table, int32_t hidden, int32_t dtype,
+                   float *X, void *stream);
+
+/* RMSNorm of the fp32 residual into the GEMM operand type: out[t,:] = X[t,:]/sqrt(mean(X[t,:]^2)+eps)*gain. */
+int prism_op_rmsnorm(const float *X, const void *gain, int32_t T, int32_t hidden, float eps, int32_t dtype,
+                     void *out, void *stream);
+
+#define PRISM_EPI_STORE    0  /* C[M,N] (operand dtype) = A W^T */
+#define PRISM_EPI_RESIDUAL 1  /* X[M,N] (fp32) += A W^T */
+#define PRISM_EPI_SWIGLU   2  /* W is [2F,K] = [W_gate; W_up]; S[M,F] (operand dtype) = silu(A Wg^T) * (A Wu^T) */
+/* Layer contraction (Sec. 2.2: latency is dominated by the matrix multiplications of the blocks).
+ * A [M,K], W [N,K] in dtype; N is the row count of W (2F for SWIGLU). */
+int prism_op_gemm(int32_t dtype, int32_t epilogue, const void *A, const void *W, void *out,
+                  int32_t M, int32_t N, int32_t K, void *stream);
+
+/* Per-head RMSNorm (optional, over head_dim, gains q_gain / k_gain [head_dim]) then rotate-half RoPE
+ * (pair i with i + head_dim/2, angle pos * rope_base^(-2i/head_dim)) on the q and k parts of the fused
+ * projection QKV [T, (nq+2nkv)*hd], in place.  pos[t] [device] is the position of token t in its
+ * sequence, 0 <= pos[t] < max_pos <= PRISM_MAX_SEQ.  Synchronises the stream before returning. */
+int prism_op_qknorm_rope(int32_t dtype, void *QKV, const int32_t *pos, int32_t max_pos, const void *q_gain,
+                         const void *k_gain, int32_t T, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                         float eps, float rope_base, int32_t qk_norm, void *stream);
+
+/* Causal GQA attention within each sequence (no token attends across sequences; Sec. 2.2).
+ * QKV [T, (nq+2nkv)*hd] [device] with RoPE already applied; cu_seqlens [n_seqs+1] [host]: token offsets of
+ * the sequences inside QKV; out [T, nq*hd] [device] in dtype.  Synchronises the stream before returning. */
+int prism_op_attention(int32_t dtype, const void *QKV, const int32_t *cu_seqlens_host, int32_t n_seqs,
+                       int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, void *out, void *stream);
+
+/* Intermediate scorer (Sec. 4.1): for each sequence c, the last token's state through the final RMSNorm and
+ * the yes/no head: scores[c] = z . w_yes - z . w_no.  last_row[c] = row of that token in X. */
+int prism_op_score(const float *X, const int32_t *last_row, int32_t n_seqs, int32_t hidden,
+                   const void *final_norm, const void *w_yes, const void *w_no, int32_t dtype, float eps,
+                   float *scores, void *stream);
+
+/* One pruning check (Sec. 4.1): dispersion gate, exact 1-D K-Means, boundary-cluster routing.
+ * scores [n] fp32 in, fate [n] int8 out (PRISM_FATE_*), stats [4] double out = {mean, std, gate, n_clusters}.
+ * With n <= K_rem, a closed gate or a single distinct score every fate is DEFERRED.  All pointers [device].
+ * Synchronises the stream before returning. */
+int prism_op_route(const float *scores, int32_t n, int32_t K_rem, int32_t n_clusters, float tau,
+                   int8_t *fate, double *stats, void *stream);
+
+/* Stream compaction of the packed residual (Sec. 4.1: continue only on the remaining candidates):
+ * rows [src_start[c], src_start[c]+len[c]) of X_src go to rows starting at dst_start[c] of X_dst for
+ * each of the n_keep kept sequences; the arrays are [device]; X_dst must not alias X_src. */
+int prism_op_compact(const float *X_src, float *X_dst, const int32_t *src_start, const int32_t *dst_start,
+                     const int32_t *len, int32_t n_keep, int32_t hidden, void *stream);
+
+/* Final top-K (Sec. 2.1): ranks n scores (descending, ties by lower position) and writes the first K
+ * positions and scores. */
+int prism_op_topk(const float *scores, int32_t n, int32_t K, int32_t *out_pos, float *out_scores, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PRISM_H_ */

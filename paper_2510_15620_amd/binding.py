@@ -1,0 +1,266 @@
+"""ctypes binding of libprism.so: argument marshalling only - every step of the path runs in the
+library's HIP kernels.  Function names follow include/prism.h.  PyTorch tensors are used as
+device-memory handles (data_ptr) and for the caller's stream."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libprism.so")
+
+OK, EINVAL, ECAP, EHIP, ENOMEM, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
+DTYPE_FP32, DTYPE_BF16 = 0, 1
+MODE_DROP_ONLY, MODE_THREE_WAY, MODE_NO_PRUNING = 0, 1, 2
+EPI_STORE, EPI_RESIDUAL, EPI_SWIGLU = 0, 1, 2
+FATE_NOT_LIVE, FATE_DROPPED, FATE_DEFERRED, FATE_SELECTED = -1, 0, 1, 2
+MAX_CANDS, MAX_CLUSTERS, MAX_SEQ = 4096, 8, 8192
+
+EXPORTS = ["prism_create", "prism_select", "prism_set_forced_keep", "prism_destroy", "prism_strerror",
+           "prism_last_error", "prism_op_embed", "prism_op_rmsnorm", "prism_op_gemm", "prism_op_qknorm_rope",
+           "prism_op_attention", "prism_op_score", "prism_op_route", "prism_op_compact", "prism_op_topk"]
+
+
+class PrismError(RuntimeError):
+    def __init__(self, code: int, detail: str):
+        super().__init__(f"prism error {code}: {detail}")
+        self.code = code
+
+
+class prism_model(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn", "vocab")] + \
+               [("rms_eps", C.c_float), ("rope_base", C.c_float), ("dtype", C.c_int32), ("qk_norm", C.c_int32)]
+
+
+LAYER_FIELDS = ("attn_norm", "wq", "wk", "wv", "q_norm", "k_norm", "wo", "ffn_norm", "w_gate", "w_up", "w_down")
+
+
+class prism_layer_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in LAYER_FIELDS]
+
+
+class prism_weights(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("layers", C.POINTER(prism_layer_weights)), ("final_norm", C.c_void_p),
+                ("w_yes", C.c_void_p), ("w_no", C.c_void_p), ("layer_residency", C.c_int32)]
+
+
+class prism_options(C.Structure):
+    _fields_ = [("checkpoint_layers", C.POINTER(C.c_int32)), ("n_checkpoints", C.c_int32), ("cv_threshold", C.c_float),
+                ("n_clusters", C.c_int32), ("mode", C.c_int32), ("chunk_cands", C.c_int32), ("hbm_cap_bytes", C.c_int64),
+                ("stream", C.c_void_p)]
+
+
+class prism_report(C.Structure):
+    _fields_ = [("cap_events", C.c_int32), ("n_cands", C.c_int32), ("n_events", C.c_int32),
+                ("ev_layer", C.POINTER(C.c_int32)), ("ev_n_before", C.POINTER(C.c_int32)),
+                ("ev_n_after", C.POINTER(C.c_int32)), ("ev_tokens_after", C.POINTER(C.c_int32)),
+                ("ev_gate", C.POINTER(C.c_int32)), ("ev_n_clusters", C.POINTER(C.c_int32)),
+                ("ev_mean", C.POINTER(C.c_double)), ("ev_std", C.POINTER(C.c_double)),
+                ("ev_scores", C.POINTER(C.c_float)), ("ev_fate", C.POINTER(C.c_int8)),
+                ("ms_total", C.c_double), ("ms_layers", C.c_double), ("ms_checks", C.c_double),
+                ("token_layers", C.c_int64), ("peak_hbm_bytes", C.c_int64), ("bytes_streamed", C.c_int64),
+                ("layers_run", C.c_int32)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The HIP library.  There is no fallback: a missing library is an error."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise PrismError(EHIP, f"{LIB_PATH} is not built; run `python -m paper_2510_15620_amd.build`")
+        _lib = C.CDLL(LIB_PATH)
+        _lib.prism_strerror.restype = C.c_char_p
+        _lib.prism_last_error.restype = C.c_char_p
+        _lib.prism_destroy.restype = None
+        vp, i32, f32 = C.c_void_p, C.c_int32, C.c_float
+        _lib.prism_create.argtypes = [C.POINTER(prism_model), C.POINTER(prism_weights), C.POINTER(prism_options), C.POINTER(vp)]
+        _lib.prism_select.argtypes = [vp, C.POINTER(i32), i32, C.POINTER(C.POINTER(i32)), C.POINTER(i32), i32, i32,
+                                      C.POINTER(i32), C.POINTER(f32), C.POINTER(i32), C.POINTER(prism_report)]
+        _lib.prism_set_forced_keep.argtypes = [vp, C.POINTER(C.c_int8), i32, i32]
+        _lib.prism_destroy.argtypes = [vp]
+        _lib.prism_strerror.argtypes = [i32]
+        _lib.prism_op_embed.argtypes = [vp, i32, vp, i32, i32, vp, vp]
+        _lib.prism_op_rmsnorm.argtypes = [vp, vp, i32, i32, f32, i32, vp, vp]
+        _lib.prism_op_gemm.argtypes = [i32, i32, vp, vp, vp, i32, i32, i32, vp]
+        _lib.prism_op_qknorm_rope.argtypes = [i32, vp, vp, i32, vp, vp, i32, i32, i32, i32, f32, f32, i32, vp]
+        _lib.prism_op_attention.argtypes = [i32, vp, C.POINTER(i32), i32, i32, i32, i32, vp, vp]
+        _lib.prism_op_score.argtypes = [vp, vp, i32, i32, vp, vp, vp, i32, f32, vp, vp]
+        _lib.prism_op_route.argtypes = [vp, i32, i32, i32, f32, vp, vp, vp]
+        _lib.prism_op_compact.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp]
+        _lib.prism_op_topk.argtypes = [vp, i32, i32, vp, vp, vp]
+    return _lib
+
+
+def _check(rc: int):
+    if rc != OK:
+        l = lib()
+        raise PrismError(rc, f"{l.prism_strerror(rc).decode()}: {l.prism_last_error().decode()}")
+
+
+def _ptr(t) -> int:
+    return 0 if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _i32_array(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+@dataclass
+class Report:
+    layer: np.ndarray
+    n_before: np.ndarray
+    n_after: np.ndarray
+    tokens_after: np.ndarray
+    gate: np.ndarray
+    n_clusters: np.ndarray
+    mean: np.ndarray
+    std: np.ndarray
+    scores: np.ndarray          # [n_events, n_cands], NaN where not live
+    fate: np.ndarray            # [n_events, n_cands]
+    ms_total: float
+    ms_layers: float
+    ms_checks: float
+    token_layers: int
+    peak_hbm_bytes: int
+    bytes_streamed: int
+    layers_run: int
+
+
+class Prism:
+    """prism_create / prism_select / prism_set_forced_keep / prism_destroy."""
+
+    def __init__(self, model, weights, *, checkpoints: Sequence[int] = (), cv_threshold: float = 0.0, n_clusters: int = 3,
+                 mode: int = MODE_DROP_ONLY, chunk_cands: int = 0, hbm_cap_bytes: int = 0, stream_weights: bool = False,
+                 stream: Optional[int] = None):
+        """model: object with n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, rms_eps, rope_base,
+        qk_norm, dtype ("fp32" | "bf16").  weights: object with embed, final_norm, w_yes, w_no (device tensors) and
+        layers: list of dicts of tensors (device, or pinned host when stream_weights)."""
+        self._ctx = C.c_void_p()
+        m = prism_model(model.n_layers, model.hidden, model.n_q_heads, model.n_kv_heads, model.head_dim, model.ffn,
+                        model.vocab, model.rms_eps, model.rope_base, DTYPE_FP32 if model.dtype == "fp32" else DTYPE_BF16,
+                        int(model.qk_norm))
+        layers = (prism_layer_weights * model.n_layers)()
+        for l, lw in enumerate(weights.layers):
+            for n in LAYER_FIELDS:
+                setattr(layers[l], n, _ptr(lw[n]))
+        self._keep = (weights, layers)      # borrowed by the library for the context's lifetime
+        w = prism_weights(_ptr(weights.embed), layers, _ptr(weights.final_norm), _ptr(weights.w_yes), _ptr(weights.w_no),
+                          1 if stream_weights else 0)
+        ck, ckp = _i32_array(list(checkpoints))
+        o = prism_options(ckp, len(ck), cv_threshold, n_clusters, mode, chunk_cands, hbm_cap_bytes,
+                          _stream() if stream is None else stream)
+        self.n_checkpoints = len(ck)
+        _check(lib().prism_create(C.byref(m), C.byref(w), C.byref(o), C.byref(self._ctx)))
+
+    def select(self, query_tokens, cand_tokens: Sequence, K: int, report: bool = True):
+        q, qp = _i32_array(query_tokens)
+        cands = [np.ascontiguousarray(c, dtype=np.int32) for c in cand_tokens]
+        n = len(cands)
+        cptrs = (C.POINTER(C.c_int32) * max(n, 1))(*[c.ctypes.data_as(C.POINTER(C.c_int32)) for c in cands])
+        lens, lp = _i32_array([len(c) for c in cands])
+        kk = max(K, 1)
+        out_idx = np.full(kk, -1, np.int32)
+        out_scores = np.full(kk, np.nan, np.float32)
+        count = C.c_int32(0)
+        rep = None
+        if report:
+            cap = self.n_checkpoints + 1
+            arrs = {k: np.zeros(cap, np.int32) for k in ("layer", "n_before", "n_after", "tokens_after", "gate", "n_clusters")}
+            arrs["mean"], arrs["std"] = np.zeros(cap, np.float64), np.zeros(cap, np.float64)
+            arrs["scores"] = np.zeros((cap, max(n, 1)), np.float32)
+            arrs["fate"] = np.zeros((cap, max(n, 1)), np.int8)
+            P = lambda a, t: a.ctypes.data_as(C.POINTER(t))
+            rep = prism_report(cap, max(n, 1), 0, P(arrs["layer"], C.c_int32), P(arrs["n_before"], C.c_int32),
+                               P(arrs["n_after"], C.c_int32), P(arrs["tokens_after"], C.c_int32), P(arrs["gate"], C.c_int32),
+                               P(arrs["n_clusters"], C.c_int32), P(arrs["mean"], C.c_double), P(arrs["std"], C.c_double),
+                               P(arrs["scores"], C.c_float), P(arrs["fate"], C.c_int8))
+        _check(lib().prism_select(self._ctx, qp, len(q), cptrs, lp, n, K, out_idx.ctypes.data_as(C.POINTER(C.c_int32)),
+                                  out_scores.ctypes.data_as(C.POINTER(C.c_float)), C.byref(count),
+                                  C.byref(rep) if rep is not None else None))
+        k = count.value
+        r = None
+        if rep is not None:
+            e = rep.n_events
+            r = Report(arrs["layer"][:e], arrs["n_before"][:e], arrs["n_after"][:e], arrs["tokens_after"][:e],
+                       arrs["gate"][:e].astype(bool), arrs["n_clusters"][:e], arrs["mean"][:e], arrs["std"][:e],
+                       arrs["scores"][:e], arrs["fate"][:e], rep.ms_total, rep.ms_layers, rep.ms_checks,
+                       rep.token_layers, rep.peak_hbm_bytes, rep.bytes_streamed, rep.layers_run)
+        return out_idx[:k].copy(), out_scores[:k].copy(), r
+
+    def set_forced_keep(self, masks: Optional[np.ndarray]):
+        if masks is None:
+            _check(lib().prism_set_forced_keep(self._ctx, None, 0, 0))
+            return
+        m = np.ascontiguousarray(masks, dtype=np.int8)
+        _check(lib().prism_set_forced_keep(self._ctx, m.ctypes.data_as(C.POINTER(C.c_int8)), m.shape[0], m.shape[1]))
+
+    def destroy(self):
+        if self._ctx:
+            lib().prism_destroy(self._ctx)
+            self._ctx = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+# ---- kernel-level entry points (device tensors in, device tensors out) ---------------------------------------------
+
+def _dt(t) -> int:
+    import torch
+    return DTYPE_FP32 if t.dtype == torch.float32 else DTYPE_BF16
+
+
+def op_embed(tokens, table, X):
+    _check(lib().prism_op_embed(_ptr(tokens), tokens.numel(), _ptr(table), table.shape[1], _dt(table), _ptr(X), _stream()))
+
+
+def op_rmsnorm(X, gain, eps, out):
+    _check(lib().prism_op_rmsnorm(_ptr(X), _ptr(gain), X.shape[0], X.shape[1], eps, _dt(gain), _ptr(out), _stream()))
+
+
+def op_gemm(epilogue, A, W, out):
+    _check(lib().prism_op_gemm(_dt(A), epilogue, _ptr(A), _ptr(W), _ptr(out), A.shape[0], W.shape[0], A.shape[1], _stream()))
+
+
+def op_qknorm_rope(QKV, pos, max_pos, q_gain, k_gain, nq, nkv, hd, eps, base, qk_norm):
+    _check(lib().prism_op_qknorm_rope(_dt(QKV), _ptr(QKV), _ptr(pos), max_pos, _ptr(q_gain), _ptr(k_gain), QKV.shape[0],
+                                      nq, nkv, hd, eps, base, int(qk_norm), _stream()))
+
+
+def op_attention(QKV, cu_seqlens, nq, nkv, hd, out):
+    cu, cup = _i32_array(cu_seqlens)
+    _check(lib().prism_op_attention(_dt(QKV), _ptr(QKV), cup, len(cu) - 1, nq, nkv, hd, _ptr(out), _stream()))
+
+
+def op_score(X, last_row, final_norm, w_yes, w_no, eps, scores):
+    _check(lib().prism_op_score(_ptr(X), _ptr(last_row), last_row.numel(), X.shape[1], _ptr(final_norm), _ptr(w_yes),
+                                _ptr(w_no), _dt(final_norm), eps, _ptr(scores), _stream()))
+
+
+def op_route(scores, K_rem, n_clusters, tau, fate, stats):
+    _check(lib().prism_op_route(_ptr(scores), scores.numel(), K_rem, n_clusters, tau, _ptr(fate), _ptr(stats), _stream()))
+
+
+def op_compact(X_src, X_dst, src_start, dst_start, length):
+    _check(lib().prism_op_compact(_ptr(X_src), _ptr(X_dst), _ptr(src_start), _ptr(dst_start), _ptr(length),
+                                  length.numel(), X_src.shape[1], _stream()))
+
+
+def op_topk(scores, K, out_pos, out_scores):
+    _check(lib().prism_op_topk(_ptr(scores), scores.numel(), K, _ptr(out_pos), _ptr(out_scores), _stream()))

@@ -1,0 +1,97 @@
+// Shared declarations of the HIP library: error plumbing, element types, kernel launchers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "prism.h"
+
+namespace prism {
+
+// ---- error plumbing --------------------------------------------------------------------------
+void set_error(const char *fmt, ...);
+int hip_fail(hipError_t e, const char *what, const char *file, int line);
+
+#define PRISM_HIP(call)                                                        \
+  do {                                                                         \
+    hipError_t e_ = (call);                                                    \
+    if (e_ != hipSuccess) return ::prism::hip_fail(e_, #call, __FILE__, __LINE__); \
+  } while (0)
+
+#define PRISM_REQUIRE(cond, code, ...)                                         \
+  do {                                                                         \
+    if (!(cond)) { ::prism::set_error(__VA_ARGS__); return (code); }           \
+  } while (0)
+
+#define PRISM_TRY(call)                                                        \
+  do { int rc_ = (call); if (rc_ != PRISM_OK) return rc_; } while (0)
+
+// ---- element types ---------------------------------------------------------------------------
+typedef __bf16 bf16;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16 v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }  // round-to-nearest-even
+
+static inline size_t dtype_size(int dtype) { return dtype == PRISM_DTYPE_FP32 ? 4 : 2; }
+static inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+static inline int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// ---- launchers (each validates shapes, launches on `s`, never synchronises) -------------------
+int launch_embed(const int32_t *tokens, int T, const void *table, int hidden, int dtype, float *X, hipStream_t s);
+int launch_rmsnorm(const float *X, const void *gain, int T, int hidden, float eps, int dtype, void *out, hipStream_t s);
+int launch_gemm_fp32(int epilogue, const float *A, const float *W, void *out, int M, int N, int K, hipStream_t s);
+int launch_gemm_bf16(int epilogue, const bf16 *A, const bf16 *W, void *out, int M, int N, int K, hipStream_t s);
+bool gemm_bf16_supported(int epilogue, int N, int K);
+
+// cos/sin table for RoPE: tab[pos * (hd/2) + i] = (cos, sin)(pos * base^(-2i/hd)), evaluated in fp64
+int launch_rope_table(float2 *tab, int n_pos, int head_dim, float rope_base, hipStream_t s);
+int launch_qknorm_rope(int dtype, void *QKV, const int32_t *pos, const void *q_gain, const void *k_gain, int T,
+                       int nq, int nkv, int hd, float eps, int qk_norm, const float2 *rope_tab, hipStream_t s);
+int launch_v_transpose(const bf16 *QKV, int T, int nq, int nkv, int hd, bf16 *Vt, const int32_t *vt_col,
+                       int64_t vt_stride, hipStream_t s);
+
+// generic fp32 attention: one workgroup per (token, q head); pos[t] = position of t in its sequence
+int launch_attention_fp32(const float *QKV, const int32_t *pos, int T, int nq, int nkv, int hd, float *out,
+                          hipStream_t s);
+// MFMA attention (hd == 128).  tiles: per work item {first token row of the sequence, sequence length,
+// first query of the tile, column of the sequence's first key in Vt}; see attn_bf16.hip.
+struct AttnTile { int32_t seq_row0, seq_len, q0, vt_col0; };
+int launch_attention_bf16(const bf16 *QKV, const bf16 *Vt, int64_t vt_stride, const AttnTile *tiles, int n_tiles,
+                          int T, int nq, int nkv, int hd, bf16 *out, hipStream_t s);
+bool attention_bf16_supported(int nq, int nkv, int hd);
+static const int kAttnBQ = 64;   // query rows per attention work item
+
+int launch_score(const float *X, const int32_t *last_row, int n, int hidden, const void *final_norm,
+                 const void *w_yes, const void *w_no, int dtype, float eps, float *scores, hipStream_t s);
+size_t route_workspace_bytes(int n, int k);
+int launch_route(const float *scores, int n, int K_rem, int n_clusters, float tau, int8_t *fate, double *stats,
+                 void *workspace, hipStream_t s);
+int launch_compact(const float *Xs, float *Xd, const int32_t *src_start, const int32_t *dst_start,
+                   const int32_t *len, int n_keep, int hidden, hipStream_t s);
+int launch_topk(const float *scores, int n, int K, int32_t *out_pos, float *out_scores, hipStream_t s);
+// same, restricted to the entries whose tag equals `want` (tag may be null: all entries)
+int launch_topk_masked(const float *scores, const int8_t *tag, int want, int n, int K, int32_t *out_pos,
+                       float *out_scores, hipStream_t s);
+int launch_fill_zero(void *p, size_t bytes, hipStream_t s);
+
+}  // namespace prism

@@ -1,0 +1,304 @@
+// Bandwidth- and latency-bound steps of the path: embedding gather, RMSNorm, q/k norm + RoPE,
+// V transposition, the intermediate scorer, compaction and the final top-K.
+#include "common.h"
+
+namespace prism {
+
+// ------------------------------------------------------------------------------------------------
+// Pack + embed: X[t,:] = table[tokens[t],:]            (paper Sec. 4.5: forwarding begins at the embedding)
+// One workgroup per token row; HBM-bound (T*H*4 B written).
+template <typename T>
+__global__ __launch_bounds__(256) void embed_kernel(const int32_t *__restrict__ tokens, const T *__restrict__ table,
+                                                    int hidden, float *__restrict__ X) {
+  const int64_t t = blockIdx.x;
+  const T *src = table + (int64_t)tokens[t] * hidden;
+  float *dst = X + t * hidden;
+  for (int i = threadIdx.x * 4; i < hidden; i += blockDim.x * 4) {
+    if (i + 3 < hidden) {
+      float4 v = make_float4(to_f32(src[i]), to_f32(src[i + 1]), to_f32(src[i + 2]), to_f32(src[i + 3]));
+      *reinterpret_cast<float4 *>(dst + i) = v;
+    } else {
+      for (int j = i; j < hidden; ++j) dst[j] = to_f32(src[j]);
+    }
+  }
+}
+
+int launch_embed(const int32_t *tokens, int T, const void *table, int hidden, int dtype, float *X, hipStream_t s) {
+  PRISM_REQUIRE(tokens && table && X && T >= 0 && hidden > 0 && hidden % 4 == 0, PRISM_EINVAL, "embed: bad arguments");
+  if (T == 0) return PRISM_OK;
+  if (dtype == PRISM_DTYPE_FP32)
+    embed_kernel<float><<<T, 256, 0, s>>>(tokens, (const float *)table, hidden, X);
+  else
+    embed_kernel<bf16><<<T, 256, 0, s>>>(tokens, (const bf16 *)table, hidden, X);
+  PRISM_HIP(hipGetLastError());
+  return PRISM_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// RMSNorm of the fp32 residual into the GEMM operand type.  One workgroup per row; the row is read
+// twice (the second read hits L2).  HBM-bound: T*H*(4 + sizeof(T)) bytes.
+__device__ __forceinline__ float block_sum_256(float v, float *red) {
+  v = wave_sum(v);
+  const int w = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __syncthreads();
+  float t = red[0] + red[1] + red[2] + red[3];
+  __syncthreads();
+  return t;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float *__restrict__ X, const T *__restrict__ gain,
+                                                      int hidden, float eps, T *__restrict__ out) {
+  __shared__ float red[4];
+  const float *x = X + (int64_t)blockIdx.x * hidden;
+  T *o = out + (int64_t)blockIdx.x * hidden;
+  float ss = 0.f;
+  for (int i = threadIdx.x * 4; i < hidden; i += 1024) {
+    float4 v = *reinterpret_cast<const float4 *>(x + i);
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  ss = block_sum_256(ss, red);
+  const float r = 1.0f / sqrtf(ss / (float)hidden + eps);
+  for (int i = threadIdx.x * 4; i < hidden; i += 1024) {
+    float4 v = *reinterpret_cast<const float4 *>(x + i);
+    o[i] = from_f32<T>(v.x * r * to_f32(gain[i]));
+    o[i + 1] = from_f32<T>(v.y * r * to_f32(gain[i + 1]));
+    o[i + 2] = from_f32<T>(v.z * r * to_f32(gain[i + 2]));
+    o[i + 3] = from_f32<T>(v.w * r * to_f32(gain[i + 3]));
+  }
+}
+
+int launch_rmsnorm(const float *X, const void *gain, int T, int hidden, float eps, int dtype, void *out, hipStream_t s) {
+  PRISM_REQUIRE(X && gain && out && T >= 0 && hidden > 0 && hidden % 4 == 0, PRISM_EINVAL, "rmsnorm: bad arguments");
+  if (T == 0) return PRISM_OK;
+  if (dtype == PRISM_DTYPE_FP32)
+    rmsnorm_kernel<float><<<T, 256, 0, s>>>(X, (const float *)gain, hidden, eps, (float *)out);
+  else
+    rmsnorm_kernel<bf16><<<T, 256, 0, s>>>(X, (const bf16 *)gain, hidden, eps, (bf16 *)out);
+  PRISM_HIP(hipGetLastError());
+  return PRISM_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// RoPE table, evaluated in fp64 and rounded once: tab[pos][i] = (cos, sin)(pos * base^(-2 i / hd)).
+__global__ void rope_table_kernel(float2 *tab, int n_pos, int half, double log2_base) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n_pos * half) return;
+  const int pos = idx / half, i = idx % half;
+  const double theta = exp2(-(double)i / (double)half * log2_base);
+  const double a = (double)pos * theta;
+  tab[idx] = make_float2((float)cos(a), (float)sin(a));
+}
+
+int launch_rope_table(float2 *tab, int n_pos, int head_dim, float rope_base, hipStream_t s) {
+  PRISM_REQUIRE(tab && n_pos > 0 && head_dim > 0 && head_dim % 2 == 0 && rope_base > 0, PRISM_EINVAL, "rope table: bad arguments");
+  const int half = head_dim / 2, n = n_pos * half;
+  rope_table_kernel<<<cdiv(n, 256), 256, 0, s>>>(tab, n_pos, half, log2((double)rope_base));
+  PRISM_HIP(hipGetLastError());
+  return PRISM_OK;
+}
+
+// Per-head RMSNorm (optional) then rotate-half RoPE on q and k, in place in the fused projection
+// QKV [T, (nq + 2 nkv) * hd].  One wavefront per (token, head); lane i owns pairs (i, i + hd/2),
+// (i + 64, i + 64 + hd/2), ...   HBM-bound: reads and writes the q and k columns once.
+template <typename T>
+__global__ __launch_bounds__(256) void qknorm_rope_kernel(T *__restrict__ QKV, const int32_t *__restrict__ pos,
+                                                          const T *__restrict__ q_gain, const T *__restrict__ k_gain,
+                                                          int n_tok, int nq, int nkv, int hd, float eps, int qk_norm,
+                                                          const float2 *__restrict__ rope_tab) {
+  const int heads = nq + nkv;
+  const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (item >= (int64_t)n_tok * heads) return;
+  const int t = (int)(item / heads), h = (int)(item % heads);
+  const int lane = threadIdx.x & 63, half = hd / 2;
+  T *x = QKV + (int64_t)t * (nq + 2 * nkv) * hd + (int64_t)h * hd;
+  const T *g = h < nq ? q_gain : k_gain;
+  const float2 *tab = rope_tab + (int64_t)pos[t] * half;
+  float ss = 0.f;
+  for (int i = lane; i < half; i += 64) {
+    const float a = to_f32(x[i]), b = to_f32(x[i + half]);
+    ss += a * a + b * b;
+  }
+  float r = 1.f;
+  if (qk_norm) {
+    ss = wave_sum(ss);
+    r = 1.0f / sqrtf(ss / (float)hd + eps);
+  }
+  for (int i = lane; i < half; i += 64) {
+    float a = to_f32(x[i]), b = to_f32(x[i + half]);
+    if (qk_norm) {
+      a = a * r * to_f32(g[i]);
+      b = b * r * to_f32(g[i + half]);
+    }
+    const float2 cs = tab[i];
+    x[i] = from_f32<T>(a * cs.x - b * cs.y);
+    x[i + half] = from_f32<T>(b * cs.x + a * cs.y);
+  }
+}
+
+int launch_qknorm_rope(int dtype, void *QKV, const int32_t *pos, const void *q_gain, const void *k_gain, int T,
+                       int nq, int nkv, int hd, float eps, int qk_norm, const float2 *rope_tab, hipStream_t s) {
+  PRISM_REQUIRE(QKV && pos && rope_tab && T >= 0 && nq > 0 && nkv > 0 && hd > 0 && hd % 2 == 0, PRISM_EINVAL,
+                "qknorm_rope: bad arguments");
+  PRISM_REQUIRE(!qk_norm || (q_gain && k_gain), PRISM_EINVAL, "qknorm_rope: gains missing");
+  if (T == 0) return PRISM_OK;
+  const int64_t items = (int64_t)T * (nq + nkv);
+  const int grid = cdiv(items, 4);
+  if (dtype == PRISM_DTYPE_FP32)
+    qknorm_rope_kernel<float><<<grid, 256, 0, s>>>((float *)QKV, pos, (const float *)q_gain, (const float *)k_gain, T,
+                                                    nq, nkv, hd, eps, qk_norm, rope_tab);
+  else
+    qknorm_rope_kernel<bf16><<<grid, 256, 0, s>>>((bf16 *)QKV, pos, (const bf16 *)q_gain, (const bf16 *)k_gain, T, nq,
+                                                   nkv, hd, eps, qk_norm, rope_tab);
+  PRISM_HIP(hipGetLastError());
+  return PRISM_OK;
+}
+
+// V part of QKV [T, ...] -> Vt [nkv][hd][vt_stride], column vt_col[t]: the PV contraction runs over
+// keys, so the MFMA operand wants keys contiguous.  Tile of 64 tokens x hd through LDS.
+__global__ __launch_bounds__(256) void v_transpose_kernel(const bf16 *__restrict__ QKV, int n_tok, int nq, int nkv,
+                                                          int hd, bf16 *__restrict__ Vt,
+                                                          const int32_t *__restrict__ vt_col, int64_t vt_stride) {
+  __shared__ bf16 tile[64][128 + 2];
+  const int t0 = blockIdx.x * 64, h = blockIdx.y;
+  const int row_elems = (nq + 2 * nkv) * hd;
+  const bf16 *src = QKV + (int64_t)(nq + nkv + h) * hd;
+  for (int idx = threadIdx.x; idx < 64 * hd; idx += 256) {
+    const int r = idx / hd, d = idx % hd;
+    if (t0 + r < n_tok) tile[r][d] = src[(int64_t)(t0 + r) * row_elems + d];
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < 64 * hd; idx += 256) {
+    const int d = idx / 64, r = idx % 64;
+    if (t0 + r < n_tok) Vt[((int64_t)h * hd + d) * vt_stride + vt_col[t0 + r]] = tile[r][d];
+  }
+}
+
+int launch_v_transpose(const bf16 *QKV, int T, int nq, int nkv, int hd, bf16 *Vt, const int32_t *vt_col,
+                       int64_t vt_stride, hipStream_t s) {
+  PRISM_REQUIRE(QKV && Vt && vt_col && T >= 0 && hd > 0 && hd <= 128, PRISM_EINVAL, "v_transpose: bad arguments");
+  if (T == 0) return PRISM_OK;
+  v_transpose_kernel<<<dim3(cdiv(T, 64), nkv), 256, 0, s>>>(QKV, T, nq, nkv, hd, Vt, vt_col, vt_stride);
+  PRISM_HIP(hipGetLastError());
+  return PRISM_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Intermediate scorer (Sec. 4.1): last-token state -> final RMSNorm -> yes/no head rows.
+// One workgroup per live candidate; reads H floats; latency-bound.
+template <typename T>
+__global__ __launch_bounds__(256) void score_kernel(const float *__restrict__ X, const int32_t *__restrict__ last_row,
+                                                    int hidden, const T *__restrict__ gain, const T *__restrict__ w_yes,
+                                                    const T *__restrict__ w_no, float eps, float *__restrict__ scores) {
+  __shared__ float red[4];
+  const float *x = X + (int64_t)last_row[blockIdx.x] * hidden;
+  float ss = 0.f, dy = 0.f, dn = 0.f;
+  for (int i = threadIdx.x; i < hidden; i += 256) {
+    const float v = x[i];
+    ss += v * v;
+    const float z = v * to_f32(gain[i]);
+    dy += z * to_f32(w_yes[i]);
+    dn += z * to_f32(w_no[i]);
+  }
+  ss = block_sum_256(ss, red);
+  dy = block_sum_256(dy, red);
+  dn = block_sum_256(dn, red);
+  if (threadIdx.x == 0) {
+    const float r = 1.0f / sqrtf(ss / (float)hidden + eps);
+    scores[blockIdx.x] = dy * r - dn * r;
+  }
+}
+
+int launch_score(const float *X, const int32_t *last_row, int n, int hidden, const void *final_norm,
+                 const void *w_yes, const void *w_no, int dtype, float eps, float *scores, hipStream_t s) {
+  PRISM_REQUIRE(X && last_row && final_norm && w_yes && w_no && scores && n >= 0 && hidden > 0, PRISM_EINVAL,
+                "score: bad arguments");
+  if (n == 0) return PRISM_OK;
+  if (dtype == PRISM_DTYPE_FP32)
+    score_kernel<float><<<n, 256, 0, s>>>(X, last_row, hidden, (const float *)final_norm, (const float *)w_yes,
+                                           (const float *)w_no, eps, scores);
+  else
+    score_kernel<bf16><<<n, 256, 0, s>>>(X, last_row, hidden, (const bf16 *)final_norm, (const bf16 *)w_yes,
+                                          (const bf16 *)w_no, eps, scores);
+  PRISM_HIP(hipGetLastError());
+  return PRISM_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Compaction (Sec. 4.1: continue only on the remaining candidates): each kept sequence's rows move
+// to their new offset in a second buffer, order preserved.  HBM-bound: 2 * T' * H * 4 bytes.
+__global__ __launch_bounds__(256) void compact_kernel(const float *__restrict__ Xs, float *__restrict__ Xd,
+                                                      const int32_t *__restrict__ src_start,
+                                                      const int32_t *__restrict__ dst_start,
+                                                      const int32_t *__restrict__ len, int hidden) {
+  const int c = blockIdx.x;
+  const int n = len[c], h4 = hidden / 4;
+  const float4 *src = reinterpret_cast<const float4 *>(Xs + (int64_t)src_start[c] * hidden);
+  float4 *dst = reinterpret_cast<float4 *>(Xd + (int64_t)dst_start[c] * hidden);
+  for (int r = blockIdx.y; r < n; r += gridDim.y)
+    for (int i = threadIdx.x; i < h4; i += 256) dst[(int64_t)r * h4 + i] = src[(int64_t)r * h4 + i];
+}
+
+int launch_compact(const float *Xs, float *Xd, const int32_t *src_start, const int32_t *dst_start,
+                   const int32_t *len, int n_keep, int hidden, hipStream_t s) {
+  PRISM_REQUIRE(Xs && Xd && Xs != Xd && src_start && dst_start && len && n_keep >= 0 && hidden % 4 == 0, PRISM_EINVAL,
+                "compact: bad arguments");
+  if (n_keep == 0) return PRISM_OK;
+  compact_kernel<<<dim3(n_keep, 32), 256, 0, s>>>(Xs, Xd, src_start, dst_start, len, hidden);
+  PRISM_HIP(hipGetLastError());
+  return PRISM_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Final top-K (Sec. 2.1): rank by counting (score descending, lower position first on ties).
+__global__ __launch_bounds__(1024) void topk_kernel(const float *__restrict__ scores, const int8_t *__restrict__ tag,
+                                                    int want, int n, int K, int32_t *__restrict__ out_pos,
+                                                    float *__restrict__ out_scores) {
+  // entries whose tag differs from `want` do not take part (tag == nullptr: all take part)
+  for (int i = threadIdx.x; i < n; i += blockDim.x) {
+    if (tag && tag[i] != want) continue;
+    const float si = scores[i];
+    int rank = 0;
+    for (int j = 0; j < n; ++j) {
+      if (tag && tag[j] != want) continue;
+      const float sj = scores[j];
+      rank += (sj > si) || (sj == si && j < i);
+    }
+    if (rank < K) {
+      out_pos[rank] = i;
+      out_scores[rank] = si;
+    }
+  }
+}
+
+int launch_topk_masked(const float *scores, const int8_t *tag, int want, int n, int K, int32_t *out_pos,
+                       float *out_scores, hipStream_t s) {
+  PRISM_REQUIRE(scores && out_pos && out_scores && n >= 0 && K >= 0, PRISM_EINVAL, "topk: bad arguments");
+  if (n == 0 || K == 0) return PRISM_OK;
+  topk_kernel<<<1, 1024, 0, s>>>(scores, tag, want, n, K, out_pos, out_scores);
+  PRISM_HIP(hipGetLastError());
+  return PRISM_OK;
+}
+
+int launch_topk(const float *scores, int n, int K, int32_t *out_pos, float *out_scores, hipStream_t s) {
+  return launch_topk_masked(scores, nullptr, 0, n, K, out_pos, out_scores, s);
+}
+
+__global__ void fill_zero_kernel(uint4 *p, size_t n16) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
+}
+
+int launch_fill_zero(void *p, size_t bytes, hipStream_t s) {
+  PRISM_REQUIRE(p && bytes % 16 == 0, PRISM_EINVAL, "fill_zero: bad arguments");
+  if (bytes == 0) return PRISM_OK;
+  const size_t n16 = bytes / 16;
+  const int grid = (int)((n16 + 255) / 256 < 4096 ? (n16 + 255) / 256 : 4096);
+  fill_zero_kernel<<<grid, 256, 0, s>>>((uint4 *)p, n16);
+  PRISM_HIP(hipGetLastError());
+  return PRISM_OK;
+}
+
+}  // namespace prism

@@ -1,0 +1,812 @@
+// Host orchestrator and C ABI: the layer loop of monolithic forwarding (paper Sec. 3.3), the pruning
+// checkpoints between layers (Sec. 3.4, 4.1), chunked execution within a layer (Sec. 4.3) and
+// overlapped layer streaming from pinned host memory on a side stream (Sec. 4.2).
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <limits>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "common.h"
+
+namespace prism {
+
+// ------------------------------------------------------------------------------------------------ errors
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+int hip_fail(hipError_t e, const char *what, const char *file, int line) {
+  set_error("HIP error %d (%s) in %s at %s:%d", (int)e, hipGetErrorString(e), what, file, line);
+  return e == hipErrorOutOfMemory ? PRISM_ENOMEM : PRISM_EHIP;
+}
+
+// ------------------------------------------------------------------------------------------------ layer layout
+// One layer's operands in one contiguous device buffer, so that a streamed layer is a handful of
+// copies into a slot and the fused operands [wq;wk;wv] and [w_gate;w_up] come for free.
+struct LayerLayout {
+  size_t attn_norm, wqkv, wk, wv, q_norm, k_norm, wo, ffn_norm, wgu, wu, wd, bytes;
+};
+
+static LayerLayout make_layout(const prism_model &m) {
+  const size_t e = dtype_size(m.dtype);
+  const size_t H = m.hidden, Dq = (size_t)m.n_q_heads * m.head_dim, Dkv = (size_t)m.n_kv_heads * m.head_dim, F = m.ffn;
+  LayerLayout L;
+  size_t o = 0;
+  auto take = [&](size_t elems) { size_t at = o; o = (size_t)round_up(o + elems * e, 256); return at; };
+  L.attn_norm = take(H);
+  L.wqkv = take((Dq + 2 * Dkv) * H);
+  L.wk = L.wqkv + Dq * H * e;
+  L.wv = L.wk + Dkv * H * e;
+  L.q_norm = take(m.head_dim);
+  L.k_norm = take(m.head_dim);
+  L.wo = take(H * Dq);
+  L.ffn_norm = take(H);
+  L.wgu = take(2 * F * H);
+  L.wu = L.wgu + F * H * e;
+  L.wd = take(H * F);
+  L.bytes = o;
+  return L;
+}
+
+struct CopyItem { size_t dst_off; const void *src; size_t bytes; };
+
+static void layer_copy_items(const prism_model &m, const LayerLayout &L, const prism_layer_weights &w,
+                             std::vector<CopyItem> &items) {
+  const size_t e = dtype_size(m.dtype);
+  const size_t H = m.hidden, Dq = (size_t)m.n_q_heads * m.head_dim, Dkv = (size_t)m.n_kv_heads * m.head_dim, F = m.ffn;
+  items.clear();
+  items.push_back({L.attn_norm, w.attn_norm, H * e});
+  items.push_back({L.wqkv, w.wq, Dq * H * e});
+  items.push_back({L.wk, w.wk, Dkv * H * e});
+  items.push_back({L.wv, w.wv, Dkv * H * e});
+  if (m.qk_norm) {
+    items.push_back({L.q_norm, w.q_norm, (size_t)m.head_dim * e});
+    items.push_back({L.k_norm, w.k_norm, (size_t)m.head_dim * e});
+  }
+  items.push_back({L.wo, w.wo, H * Dq * e});
+  items.push_back({L.ffn_norm, w.ffn_norm, H * e});
+  items.push_back({L.wgu, w.w_gate, F * H * e});
+  items.push_back({L.wu, w.w_up, F * H * e});
+  items.push_back({L.wd, w.w_down, H * F * e});
+}
+
+}  // namespace prism
+
+using namespace prism;
+
+// ------------------------------------------------------------------------------------------------ context
+struct prism_ctx {
+  prism_model m;
+  prism_options opt;
+  std::vector<int32_t> checkpoints;
+  LayerLayout lay;
+  const void *embed = nullptr, *final_norm = nullptr, *w_yes = nullptr, *w_no = nullptr;
+  bool streamed = false;
+  std::vector<prism_layer_weights> host_layers;   // pinned-host tensors when streamed
+  std::vector<char *> layer_buf;                  // n_layers slots (resident) or 2 (streamed)
+  hipStream_t stream = nullptr, copy_stream = nullptr;
+  bool own_stream = false;
+  hipEvent_t ev_ready[2] = {nullptr, nullptr}, ev_free[2] = {nullptr, nullptr};
+  hipEvent_t ev_t[4] = {nullptr, nullptr, nullptr, nullptr};
+  std::vector<hipEvent_t> ev_layer;               // 2 per layer, for the report
+  float2 *rope_tab = nullptr;
+
+  // scratch, grown on demand
+  float *X[2] = {nullptr, nullptr};
+  int64_t x_cap[2] = {0, 0};                      // tokens
+  char *Xn = nullptr, *QKV = nullptr, *Vt = nullptr, *AO = nullptr, *S = nullptr;
+  int64_t chunk_cap = 0, vt_cap = 0;              // tokens / V^T columns
+  int32_t *d_meta = nullptr; int64_t meta_cap = 0;   // int32 words
+  int32_t *h_meta = nullptr; int64_t h_meta_cap = 0; // pinned staging
+  float *d_scores = nullptr; int8_t *d_fate = nullptr; double *d_stats = nullptr; void *route_ws = nullptr;
+  int32_t *d_top_pos = nullptr; float *d_top_scores = nullptr;
+  char *h_res = nullptr;                          // pinned: scores, fate, stats, topk
+  std::vector<int8_t> forced; int forced_events = 0, forced_cands = 0;
+  int64_t bytes_now = 0, bytes_peak = 0;
+};
+
+namespace prism {
+
+static int dev_alloc(prism_ctx *c, void **p, size_t bytes) {
+  bytes = (size_t)round_up(bytes ? bytes : 256, 256);
+  if (c->opt.hbm_cap_bytes > 0 && c->bytes_now + (int64_t)bytes > c->opt.hbm_cap_bytes) {
+    set_error("device memory cap: %lld bytes in use + %zu requested exceeds hbm_cap_bytes = %lld",
+              (long long)c->bytes_now, bytes, (long long)c->opt.hbm_cap_bytes);
+    return PRISM_ECAP;
+  }
+  hipError_t e = hipMalloc(p, bytes);
+  if (e != hipSuccess) { *p = nullptr; return hip_fail(e, "hipMalloc", __FILE__, __LINE__); }
+  c->bytes_now += bytes;
+  c->bytes_peak = std::max(c->bytes_peak, c->bytes_now);
+  return PRISM_OK;
+}
+
+static void dev_free(prism_ctx *c, void *p, size_t bytes) {
+  if (!p) return;
+  (void)hipFree(p);
+  c->bytes_now -= (int64_t)round_up(bytes ? bytes : 256, 256);
+}
+
+template <typename T>
+static int grow(prism_ctx *c, T **p, int64_t *cap, int64_t need, size_t unit) {
+  if (need <= *cap) return PRISM_OK;
+  if (*p) { PRISM_HIP(hipStreamSynchronize(c->stream)); dev_free(c, *p, (size_t)*cap * unit); *p = nullptr; *cap = 0; }
+  void *q = nullptr;
+  PRISM_TRY(dev_alloc(c, &q, (size_t)need * unit));
+  *p = (T *)q;
+  *cap = need;
+  return PRISM_OK;
+}
+
+static int validate_model(const prism_model *m) {
+  PRISM_REQUIRE(m->n_layers > 0 && m->hidden > 0 && m->n_q_heads > 0 && m->n_kv_heads > 0 && m->head_dim > 0 &&
+                    m->ffn > 0 && m->vocab > 0,
+                PRISM_EINVAL, "model: sizes must be positive");
+  PRISM_REQUIRE(m->n_q_heads % m->n_kv_heads == 0, PRISM_EINVAL, "model: n_q_heads must be a multiple of n_kv_heads");
+  PRISM_REQUIRE(m->head_dim % 2 == 0 && m->hidden % 4 == 0, PRISM_EINVAL, "model: head_dim must be even, hidden a multiple of 4");
+  PRISM_REQUIRE(m->dtype == PRISM_DTYPE_FP32 || m->dtype == PRISM_DTYPE_BF16, PRISM_EINVAL, "model: unknown dtype %d", m->dtype);
+  PRISM_REQUIRE(m->rms_eps >= 0.f && m->rope_base > 0.f, PRISM_EINVAL, "model: rms_eps / rope_base out of range");
+  if (m->dtype == PRISM_DTYPE_BF16) {
+    const int Dq = m->n_q_heads * m->head_dim, Dkv = m->n_kv_heads * m->head_dim;
+    PRISM_REQUIRE(attention_bf16_supported(m->n_q_heads, m->n_kv_heads, m->head_dim), PRISM_EUNSUPPORTED,
+                  "bf16 mode needs head_dim 128 and 1, 2, 4 or 8 query heads per KV head");
+    PRISM_REQUIRE(gemm_bf16_supported(PRISM_EPI_STORE, Dq + 2 * Dkv, m->hidden) &&
+                      gemm_bf16_supported(PRISM_EPI_RESIDUAL, m->hidden, Dq) &&
+                      gemm_bf16_supported(PRISM_EPI_SWIGLU, 2 * m->ffn, m->hidden) &&
+                      gemm_bf16_supported(PRISM_EPI_RESIDUAL, m->hidden, m->ffn),
+                  PRISM_EUNSUPPORTED, "bf16 mode needs hidden, n_q_heads*head_dim and ffn to be multiples of 64");
+    PRISM_REQUIRE(m->hidden % 8 == 0 && m->ffn % 8 == 0, PRISM_EUNSUPPORTED, "bf16 mode: rows must be 16-byte aligned");
+  }
+  return PRISM_OK;
+}
+
+static int issue_layer_copy(prism_ctx *c, int layer, int slot, hipStream_t s, hipMemcpyKind kind, int64_t *bytes) {
+  std::vector<CopyItem> items;
+  layer_copy_items(c->m, c->lay, c->host_layers[layer], items);
+  for (const CopyItem &it : items) {
+    PRISM_HIP(hipMemcpyAsync(c->layer_buf[slot] + it.dst_off, it.src, it.bytes, kind, s));
+    if (bytes) *bytes += (int64_t)it.bytes;
+  }
+  return PRISM_OK;
+}
+
+}  // namespace prism
+
+// ------------------------------------------------------------------------------------------------ create / destroy
+extern "C" int prism_create(const prism_model *model, const prism_weights *weights, const prism_options *options,
+                            prism_ctx **out_ctx) {
+  PRISM_REQUIRE(model && weights && options && out_ctx, PRISM_EINVAL, "prism_create: null argument");
+  PRISM_TRY(validate_model(model));
+  PRISM_REQUIRE(weights->embed && weights->layers && weights->final_norm && weights->w_yes && weights->w_no,
+                PRISM_EINVAL, "prism_create: null weight pointer");
+  PRISM_REQUIRE(weights->layer_residency == 0 || weights->layer_residency == 1, PRISM_EINVAL, "prism_create: layer_residency");
+  PRISM_REQUIRE(options->n_checkpoints >= 0 && (options->n_checkpoints == 0 || options->checkpoint_layers),
+                PRISM_EINVAL, "prism_create: checkpoint list");
+  PRISM_REQUIRE(options->mode >= 0 && options->mode <= 2, PRISM_EINVAL, "prism_create: mode %d", options->mode);
+  PRISM_REQUIRE(options->cv_threshold >= 0.f, PRISM_EINVAL, "prism_create: cv_threshold must be >= 0");
+  PRISM_REQUIRE(options->n_clusters == 0 || (options->n_clusters >= 2 && options->n_clusters <= PRISM_MAX_CLUSTERS),
+                PRISM_EINVAL, "prism_create: n_clusters %d outside 2..%d", options->n_clusters, PRISM_MAX_CLUSTERS);
+  PRISM_REQUIRE(options->chunk_cands >= 0 && options->hbm_cap_bytes >= 0, PRISM_EINVAL, "prism_create: negative option");
+  for (int l = 0; l < model->n_layers; ++l) {
+    const prism_layer_weights &w = weights->layers[l];
+    PRISM_REQUIRE(w.attn_norm && w.wq && w.wk && w.wv && w.wo && w.ffn_norm && w.w_gate && w.w_up && w.w_down &&
+                      (!model->qk_norm || (w.q_norm && w.k_norm)),
+                  PRISM_EINVAL, "prism_create: null tensor in layer %d", l);
+  }
+  for (int i = 0; i < options->n_checkpoints; ++i)
+    PRISM_REQUIRE(options->checkpoint_layers[i] >= 1 && options->checkpoint_layers[i] <= model->n_layers, PRISM_EINVAL,
+                  "prism_create: checkpoint layer %d outside 1..%d", options->checkpoint_layers[i], model->n_layers);
+
+  prism_ctx *c = new (std::nothrow) prism_ctx();
+  PRISM_REQUIRE(c, PRISM_ENOMEM, "prism_create: out of host memory");
+  c->m = *model;
+  c->opt = *options;
+  if (c->opt.n_clusters == 0) c->opt.n_clusters = 3;
+  c->checkpoints.assign(options->checkpoint_layers, options->checkpoint_layers + options->n_checkpoints);
+  std::sort(c->checkpoints.begin(), c->checkpoints.end());
+  c->checkpoints.erase(std::unique(c->checkpoints.begin(), c->checkpoints.end()), c->checkpoints.end());
+  c->opt.checkpoint_layers = nullptr;
+  c->lay = make_layout(*model);
+  c->embed = weights->embed; c->final_norm = weights->final_norm; c->w_yes = weights->w_yes; c->w_no = weights->w_no;
+  c->streamed = weights->layer_residency == 1;
+  c->host_layers.assign(weights->layers, weights->layers + model->n_layers);
+
+  auto fail = [&](int rc) { prism_destroy(c); return rc; };
+#define CREATE_TRY(x) do { int rc__ = (x); if (rc__ != PRISM_OK) return fail(rc__); } while (0)
+#define CREATE_HIP(x) do { hipError_t e__ = (x); if (e__ != hipSuccess) return fail(hip_fail(e__, #x, __FILE__, __LINE__)); } while (0)
+  if (options->stream) c->stream = (hipStream_t)options->stream;
+  else { CREATE_HIP(hipStreamCreateWithFlags(&c->stream, hipStreamNonBlocking)); c->own_stream = true; }
+  CREATE_HIP(hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking));
+  for (int i = 0; i < 2; ++i) {
+    CREATE_HIP(hipEventCreateWithFlags(&c->ev_ready[i], hipEventDisableTiming));
+    CREATE_HIP(hipEventCreateWithFlags(&c->ev_free[i], hipEventDisableTiming));
+  }
+  for (int i = 0; i < 4; ++i) CREATE_HIP(hipEventCreate(&c->ev_t[i]));
+
+  const int n_slots = c->streamed ? std::min(2, model->n_layers) : model->n_layers;
+  c->layer_buf.assign(n_slots, nullptr);
+  for (int s = 0; s < n_slots; ++s) CREATE_TRY(dev_alloc(c, (void **)&c->layer_buf[s], c->lay.bytes));
+  if (!c->streamed) {
+    for (int l = 0; l < model->n_layers; ++l) CREATE_TRY(issue_layer_copy(c, l, l, c->stream, hipMemcpyDeviceToDevice, nullptr));
+  }
+  CREATE_TRY(dev_alloc(c, (void **)&c->rope_tab, (size_t)PRISM_MAX_SEQ * (model->head_dim / 2) * sizeof(float2)));
+  CREATE_TRY(launch_rope_table(c->rope_tab, PRISM_MAX_SEQ, model->head_dim, model->rope_base, c->stream));
+  CREATE_TRY(dev_alloc(c, (void **)&c->d_scores, PRISM_MAX_CANDS * sizeof(float)));
+  CREATE_TRY(dev_alloc(c, (void **)&c->d_fate, PRISM_MAX_CANDS));
+  CREATE_TRY(dev_alloc(c, (void **)&c->d_stats, 4 * sizeof(double)));
+  CREATE_TRY(dev_alloc(c, &c->route_ws, route_workspace_bytes(PRISM_MAX_CANDS, PRISM_MAX_CLUSTERS)));
+  CREATE_TRY(dev_alloc(c, (void **)&c->d_top_pos, PRISM_MAX_CANDS * sizeof(int32_t)));
+  CREATE_TRY(dev_alloc(c, (void **)&c->d_top_scores, PRISM_MAX_CANDS * sizeof(float)));
+  CREATE_HIP(hipHostMalloc((void **)&c->h_res, PRISM_MAX_CANDS * 16 + 256, hipHostMallocDefault));
+  CREATE_HIP(hipStreamSynchronize(c->stream));
+#undef CREATE_TRY
+#undef CREATE_HIP
+  *out_ctx = c;
+  return PRISM_OK;
+}
+
+extern "C" void prism_destroy(prism_ctx *c) {
+  if (!c) return;
+  if (c->stream) (void)hipStreamSynchronize(c->stream);
+  if (c->copy_stream) (void)hipStreamSynchronize(c->copy_stream);
+  for (char *p : c->layer_buf) if (p) (void)hipFree(p);
+  void *ptrs[] = {c->rope_tab, c->X[0], c->X[1], c->Xn, c->QKV, c->Vt, c->AO, c->S, c->d_meta, c->d_scores, c->d_fate,
+                  c->d_stats, c->route_ws, c->d_top_pos, c->d_top_scores};
+  for (void *p : ptrs) if (p) (void)hipFree(p);
+  if (c->h_meta) (void)hipHostFree(c->h_meta);
+  if (c->h_res) (void)hipHostFree(c->h_res);
+  for (int i = 0; i < 2; ++i) {
+    if (c->ev_ready[i]) (void)hipEventDestroy(c->ev_ready[i]);
+    if (c->ev_free[i]) (void)hipEventDestroy(c->ev_free[i]);
+  }
+  for (int i = 0; i < 4; ++i) if (c->ev_t[i]) (void)hipEventDestroy(c->ev_t[i]);
+  for (hipEvent_t e : c->ev_layer) if (e) (void)hipEventDestroy(e);
+  if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
+  if (c->own_stream && c->stream) (void)hipStreamDestroy(c->stream);
+  delete c;
+}
+
+extern "C" int prism_set_forced_keep(prism_ctx *c, const int8_t *masks, int32_t n_events, int32_t n_cands) {
+  PRISM_REQUIRE(c, PRISM_EINVAL, "prism_set_forced_keep: null context");
+  if (!masks) { c->forced.clear(); c->forced_events = c->forced_cands = 0; return PRISM_OK; }
+  PRISM_REQUIRE(n_events > 0 && n_cands > 0, PRISM_EINVAL, "prism_set_forced_keep: sizes must be positive");
+  c->forced.assign(masks, masks + (size_t)n_events * n_cands);
+  c->forced_events = n_events;
+  c->forced_cands = n_cands;
+  return PRISM_OK;
+}
+
+extern "C" const char *prism_strerror(int code) {
+  switch (code) {
+    case PRISM_OK: return "ok";
+    case PRISM_EINVAL: return "invalid argument";
+    case PRISM_ECAP: return "pool does not fit under the device-memory cap";
+    case PRISM_EHIP: return "HIP runtime error";
+    case PRISM_ENOMEM: return "out of memory";
+    case PRISM_EUNSUPPORTED: return "shape not supported by the kernels of this dtype";
+    default: return "unknown error code";
+  }
+}
+
+extern "C" const char *prism_last_error(void) { return g_err; }
+
+// ------------------------------------------------------------------------------------------------ select
+namespace prism {
+
+struct Chunk { int c0, c1; int64_t r0, r1; int tile0, n_tiles; int64_t vt_cols; };
+
+// Per-call host state: the live set and the metadata derived from it.
+struct Plan {
+  std::vector<int> live;           // original candidate indices, batch order
+  std::vector<int> len;            // sequence length per live candidate
+  std::vector<int64_t> row0;       // first row per live candidate
+  int64_t T = 0;
+  std::vector<Chunk> chunks;
+  std::vector<AttnTile> tiles;
+  int64_t max_chunk_tokens = 0, max_vt_cols = 0;
+};
+
+static void build_plan(const prism_ctx *c, Plan &p) {
+  const int n = (int)p.live.size();
+  p.row0.resize(n);
+  int64_t r = 0;
+  for (int i = 0; i < n; ++i) { p.row0[i] = r; r += p.len[i]; }
+  p.T = r;
+  p.chunks.clear();
+  p.tiles.clear();
+  p.max_chunk_tokens = p.max_vt_cols = 0;
+  const int step = c->opt.chunk_cands > 0 ? c->opt.chunk_cands : std::max(n, 1);
+  const bool mfma = c->m.dtype == PRISM_DTYPE_BF16;
+  const int bq = mfma ? 32 * (8 / (c->m.n_q_heads / c->m.n_kv_heads)) : 0;
+  for (int c0 = 0; c0 < n; c0 += step) {
+    Chunk ch;
+    ch.c0 = c0; ch.c1 = std::min(n, c0 + step);
+    ch.r0 = p.row0[c0]; ch.r1 = ch.c1 < n ? p.row0[ch.c1] : p.T;
+    ch.tile0 = (int)p.tiles.size();
+    int64_t col = 0;
+    if (mfma) {
+      for (int i = ch.c0; i < ch.c1; ++i) {
+        for (int q0 = 0; q0 < p.len[i]; q0 += bq)
+          p.tiles.push_back({(int32_t)(p.row0[i] - ch.r0), p.len[i], q0, (int32_t)col});
+        col += round_up(p.len[i], 64);
+      }
+      // heavy (late) query blocks first: they loop over the most keys
+      std::stable_sort(p.tiles.begin() + ch.tile0, p.tiles.end(),
+                       [](const AttnTile &a, const AttnTile &b) { return a.q0 > b.q0; });
+    }
+    ch.n_tiles = (int)p.tiles.size() - ch.tile0;
+    ch.vt_cols = col;
+    p.chunks.push_back(ch);
+    p.max_chunk_tokens = std::max(p.max_chunk_tokens, ch.r1 - ch.r0);
+    p.max_vt_cols = std::max(p.max_vt_cols, col);
+  }
+}
+
+// meta buffer (int32 words): [pos T][vtcol T][lastrow n][src n][dst n][len n][tiles 4*n_tiles][tokens T]
+struct MetaOff { int64_t pos, vtcol, lastrow, src, dst, len, tiles, tokens, words; };
+
+static MetaOff meta_offsets(int64_t T, int n, int64_t n_tiles) {
+  MetaOff o;
+  int64_t w = 0;
+  auto take = [&](int64_t k) { int64_t at = w; w = round_up(w + k, 64); return at; };
+  o.pos = take(T); o.vtcol = take(T); o.lastrow = take(n); o.src = take(n); o.dst = take(n); o.len = take(n);
+  o.tiles = take(4 * n_tiles); o.tokens = take(T);
+  o.words = w;
+  return o;
+}
+
+static int ensure_scratch(prism_ctx *c, const Plan &p, bool need_second_x, int n_cands, int64_t max_tiles) {
+  const prism_model &m = c->m;
+  const size_t e = dtype_size(m.dtype);
+  const int64_t Dq = (int64_t)m.n_q_heads * m.head_dim, Dkv = (int64_t)m.n_kv_heads * m.head_dim;
+  PRISM_TRY(grow(c, &c->X[0], &c->x_cap[0], p.T, (size_t)m.hidden * 4));
+  if (need_second_x) PRISM_TRY(grow(c, &c->X[1], &c->x_cap[1], p.T, (size_t)m.hidden * 4));
+  if (p.max_chunk_tokens > c->chunk_cap) {
+    PRISM_HIP(hipStreamSynchronize(c->stream));
+    const int64_t old = c->chunk_cap, cap = p.max_chunk_tokens;
+    dev_free(c, c->Xn, (size_t)old * m.hidden * e); dev_free(c, c->QKV, (size_t)old * (Dq + 2 * Dkv) * e);
+    dev_free(c, c->AO, (size_t)old * Dq * e); dev_free(c, c->S, (size_t)old * m.ffn * e);
+    c->Xn = c->QKV = c->AO = c->S = nullptr; c->chunk_cap = 0;
+    PRISM_TRY(dev_alloc(c, (void **)&c->Xn, (size_t)cap * m.hidden * e));
+    PRISM_TRY(dev_alloc(c, (void **)&c->QKV, (size_t)cap * (Dq + 2 * Dkv) * e));
+    PRISM_TRY(dev_alloc(c, (void **)&c->AO, (size_t)cap * Dq * e));
+    PRISM_TRY(dev_alloc(c, (void **)&c->S, (size_t)cap * m.ffn * e));
+    c->chunk_cap = cap;
+  }
+  if (m.dtype == PRISM_DTYPE_BF16 && p.max_vt_cols > c->vt_cap) {
+    const int64_t old = c->vt_cap;
+    PRISM_TRY(grow(c, &c->Vt, &c->vt_cap, p.max_vt_cols, (size_t)Dkv * 2));
+    (void)old;
+    // pad columns are multiplied by exact zeros; they only have to be finite
+    PRISM_TRY(launch_fill_zero(c->Vt, (size_t)round_up((size_t)c->vt_cap * Dkv * 2, 256), c->stream));
+  }
+  const MetaOff mo = meta_offsets(p.T, n_cands, max_tiles);
+  PRISM_TRY(grow(c, &c->d_meta, &c->meta_cap, mo.words, 4));
+  if (mo.words > c->h_meta_cap) {
+    if (c->h_meta) { PRISM_HIP(hipStreamSynchronize(c->stream)); (void)hipHostFree(c->h_meta); c->h_meta = nullptr; }
+    PRISM_HIP(hipHostMalloc((void **)&c->h_meta, (size_t)mo.words * 4, hipHostMallocDefault));
+    c->h_meta_cap = mo.words;
+  }
+  return PRISM_OK;
+}
+
+// Writes pos / vtcol / lastrow / tiles for the current live set into the pinned staging buffer and
+// uploads them.  The staging buffer is only rewritten after a stream synchronisation.
+static int upload_meta(prism_ctx *c, const Plan &p, const MetaOff &mo, bool with_tokens) {
+  int32_t *h = c->h_meta;
+  const int n = (int)p.live.size();
+  for (const Chunk &ch : p.chunks) {
+    int64_t col = 0;
+    for (int i = ch.c0; i < ch.c1; ++i) {
+      int32_t *pos = h + mo.pos + p.row0[i], *vc = h + mo.vtcol + p.row0[i];
+      for (int t = 0; t < p.len[i]; ++t) { pos[t] = t; vc[t] = (int32_t)(col + t); }
+      col += round_up(p.len[i], 64);
+    }
+  }
+  for (int i = 0; i < n; ++i) h[mo.lastrow + i] = (int32_t)(p.row0[i] + p.len[i] - 1);
+  if (!p.tiles.empty()) memcpy(h + mo.tiles, p.tiles.data(), p.tiles.size() * sizeof(AttnTile));
+  // one copy for [pos .. tiles], a second for the tokens (first upload only)
+  PRISM_HIP(hipMemcpyAsync(c->d_meta, h, (size_t)mo.tokens * 4, hipMemcpyHostToDevice, c->stream));
+  if (with_tokens)
+    PRISM_HIP(hipMemcpyAsync(c->d_meta + mo.tokens, h + mo.tokens, (size_t)p.T * 4, hipMemcpyHostToDevice, c->stream));
+  return PRISM_OK;
+}
+
+static int run_layer(prism_ctx *c, const Plan &p, const MetaOff &mo, float *X, const char *wbuf) {
+  const prism_model &m = c->m;
+  const LayerLayout &L = c->lay;
+  const int H = m.hidden, Dq = m.n_q_heads * m.head_dim, Dkv = m.n_kv_heads * m.head_dim, F = m.ffn;
+  hipStream_t s = c->stream;
+  const bool bf = m.dtype == PRISM_DTYPE_BF16;
+  for (const Chunk &ch : p.chunks) {
+    const int Tc = (int)(ch.r1 - ch.r0);
+    float *Xc = X + ch.r0 * H;
+    const int32_t *pos = c->d_meta + mo.pos + ch.r0;
+    PRISM_TRY(launch_rmsnorm(Xc, wbuf + L.attn_norm, Tc, H, m.rms_eps, m.dtype, c->Xn, s));
+    if (bf) {
+      PRISM_TRY(launch_gemm_bf16(PRISM_EPI_STORE, (const bf16 *)c->Xn, (const bf16 *)(wbuf + L.wqkv), c->QKV, Tc, Dq + 2 * Dkv, H, s));
+      PRISM_TRY(launch_qknorm_rope(m.dtype, c->QKV, pos, wbuf + L.q_norm, wbuf + L.k_norm, Tc, m.n_q_heads, m.n_kv_heads,
+                                   m.head_dim, m.rms_eps, m.qk_norm, c->rope_tab, s));
+      PRISM_TRY(launch_v_transpose((const bf16 *)c->QKV, Tc, m.n_q_heads, m.n_kv_heads, m.head_dim, (bf16 *)c->Vt,
+                                   c->d_meta + mo.vtcol + ch.r0, c->vt_cap, s));
+      PRISM_TRY(launch_attention_bf16((const bf16 *)c->QKV, (const bf16 *)c->Vt, c->vt_cap,
+                                      (const AttnTile *)(c->d_meta + mo.tiles) + ch.tile0, ch.n_tiles, Tc, m.n_q_heads,
+                                      m.n_kv_heads, m.head_dim, (bf16 *)c->AO, s));
+      PRISM_TRY(launch_gemm_bf16(PRISM_EPI_RESIDUAL, (const bf16 *)c->AO, (const bf16 *)(wbuf + L.wo), Xc, Tc, H, Dq, s));
+      PRISM_TRY(launch_rmsnorm(Xc, wbuf + L.ffn_norm, Tc, H, m.rms_eps, m.dtype, c->Xn, s));
+      PRISM_TRY(launch_gemm_bf16(PRISM_EPI_SWIGLU, (const bf16 *)c->Xn, (const bf16 *)(wbuf + L.wgu), c->S, Tc, 2 * F, H, s));
+      PRISM_TRY(launch_gemm_bf16(PRISM_EPI_RESIDUAL, (const bf16 *)c->S, (const bf16 *)(wbuf + L.wd), Xc, Tc, H, F, s));
+    } else {
+      PRISM_TRY(launch_gemm_fp32(PRISM_EPI_STORE, (const float *)c->Xn, (const float *)(wbuf + L.wqkv), c->QKV, Tc, Dq + 2 * Dkv, H, s));
+      PRISM_TRY(launch_qknorm_rope(m.dtype, c->QKV, pos, wbuf + L.q_norm, wbuf + L.k_norm, Tc, m.n_q_heads, m.n_kv_heads,
+                                   m.head_dim, m.rms_eps, m.qk_norm, c->rope_tab, s));
+      PRISM_TRY(launch_attention_fp32((const float *)c->QKV, pos, Tc, m.n_q_heads, m.n_kv_heads, m.head_dim, (float *)c->AO, s));
+      PRISM_TRY(launch_gemm_fp32(PRISM_EPI_RESIDUAL, (const float *)c->AO, (const float *)(wbuf + L.wo), Xc, Tc, H, Dq, s));
+      PRISM_TRY(launch_rmsnorm(Xc, wbuf + L.ffn_norm, Tc, H, m.rms_eps, m.dtype, c->Xn, s));
+      PRISM_TRY(launch_gemm_fp32(PRISM_EPI_SWIGLU, (const float *)c->Xn, (const float *)(wbuf + L.wgu), c->S, Tc, 2 * F, H, s));
+      PRISM_TRY(launch_gemm_fp32(PRISM_EPI_RESIDUAL, (const float *)c->S, (const float *)(wbuf + L.wd), Xc, Tc, H, F, s));
+    }
+  }
+  return PRISM_OK;
+}
+
+}  // namespace prism
+
+extern "C" int prism_select(prism_ctx *c, const int32_t *query_tokens, int32_t query_len,
+                            const int32_t *const *cand_tokens, const int32_t *cand_lens, int32_t n_cands, int32_t K,
+                            int32_t *out_idx, float *out_scores, int32_t *out_count, prism_report *rep) {
+  PRISM_REQUIRE(c && query_tokens && cand_tokens && cand_lens && out_idx && out_scores && out_count, PRISM_EINVAL,
+                "prism_select: null argument");
+  PRISM_REQUIRE(query_len > 0 && n_cands > 0 && K > 0, PRISM_EINVAL, "prism_select: query_len, n_cands and K must be positive");
+  PRISM_REQUIRE(n_cands <= PRISM_MAX_CANDS, PRISM_EINVAL, "prism_select: more than %d candidates", PRISM_MAX_CANDS);
+  const prism_model &m = c->m;
+  for (int t = 0; t < query_len; ++t)
+    PRISM_REQUIRE(query_tokens[t] >= 0 && query_tokens[t] < m.vocab, PRISM_EINVAL, "prism_select: query token %d out of range", t);
+  Plan p;
+  p.live.resize(n_cands);
+  p.len.resize(n_cands);
+  for (int i = 0; i < n_cands; ++i) {
+    PRISM_REQUIRE(cand_lens[i] > 0 && cand_tokens[i], PRISM_EINVAL, "prism_select: candidate %d is empty", i);
+    PRISM_REQUIRE((int64_t)query_len + cand_lens[i] <= PRISM_MAX_SEQ, PRISM_EINVAL,
+                  "prism_select: sequence %d longer than %d tokens", i, PRISM_MAX_SEQ);
+    for (int t = 0; t < cand_lens[i]; ++t)
+      PRISM_REQUIRE(cand_tokens[i][t] >= 0 && cand_tokens[i][t] < m.vocab, PRISM_EINVAL,
+                    "prism_select: token %d of candidate %d out of range", t, i);
+    p.live[i] = i;
+    p.len[i] = query_len + cand_lens[i];
+  }
+  if (rep) {
+    PRISM_REQUIRE(rep->cap_events > 0 && rep->n_cands >= n_cands && rep->ev_layer && rep->ev_n_before && rep->ev_n_after &&
+                      rep->ev_tokens_after && rep->ev_gate && rep->ev_n_clusters && rep->ev_mean && rep->ev_std &&
+                      rep->ev_scores && rep->ev_fate,
+                  PRISM_EINVAL, "prism_select: report arrays missing or too small");
+  }
+  const int Kc = std::min(K, n_cands);
+  const int mode = K >= n_cands ? PRISM_MODE_NO_PRUNING : c->opt.mode;
+  build_plan(c, p);
+  PRISM_REQUIRE(p.T < (int64_t)1 << 30, PRISM_EINVAL, "prism_select: pool of %lld tokens is too large", (long long)p.T);
+  const bool may_prune = mode != PRISM_MODE_NO_PRUNING && !c->checkpoints.empty();
+  const int64_t max_tiles = (int64_t)p.tiles.size();   // the live set only shrinks
+  PRISM_TRY(ensure_scratch(c, p, may_prune, n_cands, max_tiles));
+  const MetaOff mo = meta_offsets(p.T, n_cands, max_tiles);
+  hipStream_t s = c->stream;
+
+  // tokens, packed: sequence i = query ++ candidate i
+  {
+    int32_t *tok = c->h_meta + mo.tokens;
+    for (int i = 0; i < n_cands; ++i) {
+      memcpy(tok + p.row0[i], query_tokens, (size_t)query_len * 4);
+      memcpy(tok + p.row0[i] + query_len, cand_tokens[i], (size_t)cand_lens[i] * 4);
+    }
+  }
+  const bool timed = rep != nullptr;
+  if (timed && (int)c->ev_layer.size() < 2 * m.n_layers) {
+    const size_t old = c->ev_layer.size();
+    c->ev_layer.resize(2 * m.n_layers, nullptr);
+    for (size_t i = old; i < c->ev_layer.size(); ++i) PRISM_HIP(hipEventCreate(&c->ev_layer[i]));
+  }
+  if (timed) PRISM_HIP(hipEventRecord(c->ev_t[0], s));
+  PRISM_TRY(upload_meta(c, p, mo, true));
+  int cur = 0;
+  PRISM_TRY(launch_embed(c->d_meta + mo.tokens, (int)p.T, c->embed, m.hidden, m.dtype, c->X[cur], s));
+
+  int64_t bytes_streamed = 0, token_layers = 0;
+  if (c->streamed) {
+    // Sec. 4.2: two buffers; layer l computes from slot l % 2 while layer l + 1 arrives in the other
+    for (int l = 0; l < std::min(2, m.n_layers); ++l) {
+      PRISM_TRY(issue_layer_copy(c, l, l, c->copy_stream, hipMemcpyHostToDevice, &bytes_streamed));
+      PRISM_HIP(hipEventRecord(c->ev_ready[l], c->copy_stream));
+    }
+  }
+
+  std::vector<int> early_idx;          // three-way mode: candidates selected before the end, in output order
+  std::vector<float> early_scores;
+  int K_rem = Kc, n_events = 0, n_forced_seen = 0, layers_run = 0;
+  bool terminated = false;
+  std::vector<int> final_idx;
+  std::vector<float> final_scores;
+  size_t next_ckpt = 0;
+  double ms_checks = 0.0;
+  float *h_scores = (float *)c->h_res;
+  int8_t *h_fate = (int8_t *)(c->h_res + PRISM_MAX_CANDS * 4);
+  double *h_stats = (double *)(c->h_res + PRISM_MAX_CANDS * 5);
+  int32_t *h_top_pos = (int32_t *)(c->h_res + PRISM_MAX_CANDS * 5 + 64);
+  float *h_top_scores = (float *)(c->h_res + PRISM_MAX_CANDS * 9 + 64);
+
+  auto record_event = [&](int layer, int n_before, const std::vector<int> &live_before, bool gate, int n_clusters,
+                          double mean, double sd, const int8_t *fate /* may be null */, const std::vector<char> *keep) {
+    if (!rep || n_events >= rep->cap_events) { ++n_events; return; }
+    const int e = n_events++;
+    rep->ev_layer[e] = layer; rep->ev_n_before[e] = n_before; rep->ev_gate[e] = gate; rep->ev_n_clusters[e] = n_clusters;
+    rep->ev_mean[e] = mean; rep->ev_std[e] = sd;
+    float *sc = rep->ev_scores + (size_t)e * rep->n_cands;
+    int8_t *ft = rep->ev_fate + (size_t)e * rep->n_cands;
+    for (int i = 0; i < rep->n_cands; ++i) { sc[i] = std::numeric_limits<float>::quiet_NaN(); ft[i] = PRISM_FATE_NOT_LIVE; }
+    int n_after = 0; int64_t tok_after = 0;
+    for (int i = 0; i < n_before; ++i) {
+      sc[live_before[i]] = h_scores[i];
+      ft[live_before[i]] = fate ? fate[i] : (int8_t)PRISM_FATE_DEFERRED;
+      if (!keep || (*keep)[i]) { ++n_after; tok_after += p.len[i]; }
+    }
+    rep->ev_n_after[e] = n_after; rep->ev_tokens_after[e] = (int32_t)tok_after;
+  };
+
+  for (int l = 0; l < m.n_layers && !terminated; ++l) {
+    const int slot = c->streamed ? l % 2 : l;
+    if (c->streamed) PRISM_HIP(hipStreamWaitEvent(s, c->ev_ready[slot], 0));
+    if (timed) PRISM_HIP(hipEventRecord(c->ev_layer[2 * l], s));
+    PRISM_TRY(run_layer(c, p, mo, c->X[cur], c->layer_buf[slot]));
+    if (timed) PRISM_HIP(hipEventRecord(c->ev_layer[2 * l + 1], s));
+    token_layers += p.T;
+    layers_run = l + 1;
+    if (c->streamed && l + 2 < m.n_layers) {
+      PRISM_HIP(hipEventRecord(c->ev_free[slot], s));
+      PRISM_HIP(hipStreamWaitEvent(c->copy_stream, c->ev_free[slot], 0));
+      PRISM_TRY(issue_layer_copy(c, l + 2, slot, c->copy_stream, hipMemcpyHostToDevice, &bytes_streamed));
+      PRISM_HIP(hipEventRecord(c->ev_ready[slot], c->copy_stream));
+    }
+    while (next_ckpt < c->checkpoints.size() && c->checkpoints[next_ckpt] < l + 1) ++next_ckpt;
+    const bool is_ckpt = next_ckpt < c->checkpoints.size() && c->checkpoints[next_ckpt] == l + 1;
+    const int n_live = (int)p.live.size();
+    if (!is_ckpt || l + 1 >= m.n_layers || !may_prune || n_live <= K_rem) continue;
+
+    // ---- pruning check on the output of layer l + 1, before layer l + 2 runs (Sec. 3.4, 4.1)
+    if (timed) PRISM_HIP(hipEventRecord(c->ev_t[2], s));
+    PRISM_TRY(launch_score(c->X[cur], c->d_meta + mo.lastrow, n_live, m.hidden, c->final_norm, c->w_yes, c->w_no, m.dtype,
+                           m.rms_eps, c->d_scores, s));
+    PRISM_TRY(launch_route(c->d_scores, n_live, K_rem, c->opt.n_clusters, c->opt.cv_threshold, c->d_fate, c->d_stats,
+                           c->route_ws, s));
+    PRISM_HIP(hipMemcpyAsync(h_scores, c->d_scores, (size_t)n_live * 4, hipMemcpyDeviceToHost, s));
+    PRISM_HIP(hipMemcpyAsync(h_fate, c->d_fate, (size_t)n_live, hipMemcpyDeviceToHost, s));
+    PRISM_HIP(hipMemcpyAsync(h_stats, c->d_stats, 4 * sizeof(double), hipMemcpyDeviceToHost, s));
+    PRISM_HIP(hipStreamSynchronize(s));
+    const bool gate = h_stats[2] != 0.0;
+    const int n_clu = (int)h_stats[3];
+    std::vector<char> keep(n_live, 1);
+    int n_sel = 0, n_def = 0;
+    for (int i = 0; i < n_live; ++i) {
+      n_sel += h_fate[i] == PRISM_FATE_SELECTED;
+      n_def += h_fate[i] == PRISM_FATE_DEFERRED;
+      if (n_clu > 0) keep[i] = mode == PRISM_MODE_DROP_ONLY ? h_fate[i] != PRISM_FATE_DROPPED : h_fate[i] == PRISM_FATE_DEFERRED;
+    }
+    if (!c->forced.empty() && n_forced_seen < c->forced_events && mode == PRISM_MODE_DROP_ONLY) {
+      const int8_t *fm = c->forced.data() + (size_t)n_forced_seen * c->forced_cands;
+      for (int i = 0; i < n_live; ++i) keep[i] = p.live[i] < c->forced_cands ? fm[p.live[i]] != 0 : 1;
+    }
+    ++n_forced_seen;
+    const std::vector<int> live_before = p.live;
+    record_event(l + 1, n_live, live_before, gate, n_clu, h_stats[0], h_stats[1], h_fate, &keep);
+    if (mode == PRISM_MODE_THREE_WAY && n_clu > 0) {
+      if (n_sel > 0) {
+        // selected candidates leave with their exit-time score, best first
+        PRISM_TRY(launch_topk_masked(c->d_scores, c->d_fate, PRISM_FATE_SELECTED, n_live, n_sel, c->d_top_pos, c->d_top_scores, s));
+        PRISM_HIP(hipMemcpyAsync(h_top_pos, c->d_top_pos, (size_t)n_sel * 4, hipMemcpyDeviceToHost, s));
+        PRISM_HIP(hipMemcpyAsync(h_top_scores, c->d_top_scores, (size_t)n_sel * 4, hipMemcpyDeviceToHost, s));
+        PRISM_HIP(hipStreamSynchronize(s));
+        for (int i = 0; i < n_sel; ++i) { early_idx.push_back(p.live[h_top_pos[i]]); early_scores.push_back(h_top_scores[i]); }
+        K_rem -= n_sel;
+      }
+      if (n_def == K_rem) {
+        // Sec. 4.1: the deferred set fills the remaining slots exactly -> the forward stops here
+        PRISM_TRY(launch_topk_masked(c->d_scores, c->d_fate, PRISM_FATE_DEFERRED, n_live, n_def, c->d_top_pos, c->d_top_scores, s));
+        PRISM_HIP(hipMemcpyAsync(h_top_pos, c->d_top_pos, (size_t)n_def * 4, hipMemcpyDeviceToHost, s));
+        PRISM_HIP(hipMemcpyAsync(h_top_scores, c->d_top_scores, (size_t)n_def * 4, hipMemcpyDeviceToHost, s));
+        PRISM_HIP(hipStreamSynchronize(s));
+        for (int i = 0; i < n_def; ++i) { final_idx.push_back(p.live[h_top_pos[i]]); final_scores.push_back(h_top_scores[i]); }
+        terminated = true;
+      }
+    }
+    int n_keep = 0;
+    for (int i = 0; i < n_live; ++i) n_keep += keep[i];
+    if (n_keep < n_live && !terminated) {
+      // ---- compaction: kept sequences move to the other X buffer, order preserved; metadata is rebuilt
+      int32_t *h = c->h_meta;
+      Plan q;
+      int64_t dst = 0;
+      int k = 0;
+      for (int i = 0; i < n_live; ++i) {
+        if (!keep[i]) continue;
+        h[mo.src + k] = (int32_t)p.row0[i]; h[mo.dst + k] = (int32_t)dst; h[mo.len + k] = p.len[i];
+        q.live.push_back(p.live[i]); q.len.push_back(p.len[i]);
+        dst += p.len[i]; ++k;
+      }
+      build_plan(c, q);
+      PRISM_TRY(upload_meta(c, q, mo, false));   // also carries src/dst/len, which sit between lastrow and tiles
+      PRISM_TRY(launch_compact(c->X[cur], c->X[cur ^ 1], c->d_meta + mo.src, c->d_meta + mo.dst, c->d_meta + mo.len, n_keep,
+                               m.hidden, s));
+      cur ^= 1;
+      p = q;
+    }
+    if (timed) {
+      PRISM_HIP(hipEventRecord(c->ev_t[3], s));
+      PRISM_HIP(hipEventSynchronize(c->ev_t[3]));
+      float ms = 0.f;
+      PRISM_HIP(hipEventElapsedTime(&ms, c->ev_t[2], c->ev_t[3]));
+      ms_checks += ms;
+    }
+  }
+
+  if (!terminated) {
+    // ---- final scoring and top-K (Sec. 2.1)
+    const int n_live = (int)p.live.size();
+    const int k_out = std::min(K_rem, n_live);
+    PRISM_TRY(launch_score(c->X[cur], c->d_meta + mo.lastrow, n_live, m.hidden, c->final_norm, c->w_yes, c->w_no, m.dtype,
+                           m.rms_eps, c->d_scores, s));
+    PRISM_TRY(launch_topk(c->d_scores, n_live, k_out, c->d_top_pos, c->d_top_scores, s));
+    PRISM_HIP(hipMemcpyAsync(h_scores, c->d_scores, (size_t)n_live * 4, hipMemcpyDeviceToHost, s));
+    PRISM_HIP(hipMemcpyAsync(h_top_pos, c->d_top_pos, (size_t)k_out * 4, hipMemcpyDeviceToHost, s));
+    PRISM_HIP(hipMemcpyAsync(h_top_scores, c->d_top_scores, (size_t)k_out * 4, hipMemcpyDeviceToHost, s));
+    if (timed) PRISM_HIP(hipEventRecord(c->ev_t[1], s));
+    PRISM_HIP(hipStreamSynchronize(s));
+    for (int i = 0; i < k_out; ++i) { final_idx.push_back(p.live[h_top_pos[i]]); final_scores.push_back(h_top_scores[i]); }
+    record_event(m.n_layers, n_live, p.live, false, 0, 0.0, 0.0, nullptr, nullptr);
+  } else {
+    if (timed) PRISM_HIP(hipEventRecord(c->ev_t[1], s));
+    PRISM_HIP(hipStreamSynchronize(s));
+  }
+  if (c->streamed) PRISM_HIP(hipStreamSynchronize(c->copy_stream));
+
+  int n_out = 0;
+  for (size_t i = 0; i < early_idx.size() && n_out < Kc; ++i, ++n_out) { out_idx[n_out] = early_idx[i]; out_scores[n_out] = early_scores[i]; }
+  for (size_t i = 0; i < final_idx.size() && n_out < Kc; ++i, ++n_out) { out_idx[n_out] = final_idx[i]; out_scores[n_out] = final_scores[i]; }
+  *out_count = n_out;
+  if (rep) {
+    rep->n_events = std::min(n_events, rep->cap_events);
+    float ms = 0.f;
+    PRISM_HIP(hipEventElapsedTime(&ms, c->ev_t[0], c->ev_t[1]));
+    rep->ms_total = ms;
+    double ml = 0.0;
+    for (int l = 0; l < layers_run; ++l) {
+      PRISM_HIP(hipEventElapsedTime(&ms, c->ev_layer[2 * l], c->ev_layer[2 * l + 1]));
+      ml += ms;
+    }
+    rep->ms_layers = ml;
+    rep->ms_checks = ms_checks;
+    rep->token_layers = token_layers;
+    rep->peak_hbm_bytes = c->bytes_peak;
+    rep->bytes_streamed = bytes_streamed;
+    rep->layers_run = layers_run;
+  }
+  return PRISM_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ kernel-level entry points
+namespace prism {
+
+struct TmpDev {            // stream-ordered temporary: freed after the stream has drained
+  void *p = nullptr;
+  int alloc(size_t bytes) { hipError_t e = hipMalloc(&p, bytes ? bytes : 256); return e == hipSuccess ? PRISM_OK : hip_fail(e, "hipMalloc", __FILE__, __LINE__); }
+  ~TmpDev() { if (p) (void)hipFree(p); }
+};
+
+}  // namespace prism
+
+extern "C" int prism_op_embed(const int32_t *tokens, int32_t T, const void *table, int32_t hidden, int32_t dtype, float *X,
+                              void *stream) {
+  return launch_embed(tokens, T, table, hidden, dtype, X, (hipStream_t)stream);
+}
+
+extern "C" int prism_op_rmsnorm(const float *X, const void *gain, int32_t T, int32_t hidden, float eps, int32_t dtype,
+                                void *out, void *stream) {
+  return launch_rmsnorm(X, gain, T, hidden, eps, dtype, out, (hipStream_t)stream);
+}
+
+extern "C" int prism_op_gemm(int32_t dtype, int32_t epilogue, const void *A, const void *W, void *out, int32_t M, int32_t N,
+                             int32_t K, void *stream) {
+  PRISM_REQUIRE(epilogue >= PRISM_EPI_STORE && epilogue <= PRISM_EPI_SWIGLU, PRISM_EINVAL, "gemm: unknown epilogue %d", epilogue);
+  if (dtype == PRISM_DTYPE_FP32) return launch_gemm_fp32(epilogue, (const float *)A, (const float *)W, out, M, N, K, (hipStream_t)stream);
+  PRISM_REQUIRE(dtype == PRISM_DTYPE_BF16, PRISM_EINVAL, "gemm: unknown dtype %d", dtype);
+  return launch_gemm_bf16(epilogue, (const bf16 *)A, (const bf16 *)W, out, M, N, K, (hipStream_t)stream);
+}
+
+extern "C" int prism_op_qknorm_rope(int32_t dtype, void *QKV, const int32_t *pos, int32_t max_pos, const void *q_gain,
+                                    const void *k_gain, int32_t T, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                    float eps, float rope_base, int32_t qk_norm, void *stream) {
+  PRISM_REQUIRE(max_pos > 0 && max_pos <= PRISM_MAX_SEQ && head_dim > 0 && head_dim % 2 == 0, PRISM_EINVAL, "qknorm_rope: max_pos / head_dim");
+  hipStream_t s = (hipStream_t)stream;
+  TmpDev tab;
+  PRISM_TRY(tab.alloc((size_t)max_pos * (head_dim / 2) * sizeof(float2)));
+  PRISM_TRY(launch_rope_table((float2 *)tab.p, max_pos, head_dim, rope_base, s));
+  PRISM_TRY(launch_qknorm_rope(dtype, QKV, pos, q_gain, k_gain, T, n_q_heads, n_kv_heads, head_dim, eps, qk_norm,
+                               (const float2 *)tab.p, s));
+  PRISM_HIP(hipStreamSynchronize(s));   // the table is freed on return
+  return PRISM_OK;
+}
+
+extern "C" int prism_op_attention(int32_t dtype, const void *QKV, const int32_t *cu, int32_t n_seqs, int32_t nq, int32_t nkv,
+                                  int32_t hd, void *out, void *stream) {
+  PRISM_REQUIRE(QKV && cu && out && n_seqs >= 0 && nq > 0 && nkv > 0 && nq % nkv == 0, PRISM_EINVAL, "attention: bad arguments");
+  hipStream_t s = (hipStream_t)stream;
+  if (n_seqs == 0) return PRISM_OK;
+  const int T = cu[n_seqs];
+  for (int i = 0; i < n_seqs; ++i)
+    PRISM_REQUIRE(cu[i + 1] > cu[i] && cu[i + 1] - cu[i] <= PRISM_MAX_SEQ, PRISM_EINVAL, "attention: sequence %d has bad length", i);
+  std::vector<int32_t> pos(T), vtcol(T);
+  std::vector<AttnTile> tiles;
+  int64_t col = 0;
+  const bool bf = dtype == PRISM_DTYPE_BF16;
+  PRISM_REQUIRE(!bf || attention_bf16_supported(nq, nkv, hd), PRISM_EUNSUPPORTED, "attention bf16: unsupported head shape");
+  const int bq = bf ? 32 * (8 / (nq / nkv)) : 1;
+  for (int i = 0; i < n_seqs; ++i) {
+    const int L = cu[i + 1] - cu[i];
+    for (int t = 0; t < L; ++t) { pos[cu[i] + t] = t; vtcol[cu[i] + t] = (int32_t)(col + t); }
+    if (bf) for (int q0 = 0; q0 < L; q0 += bq) tiles.push_back({cu[i], L, q0, (int32_t)col});
+    col += round_up(L, 64);
+  }
+  TmpDev d_pos, d_vtcol, d_tiles, d_vt;
+  PRISM_TRY(d_pos.alloc((size_t)T * 4));
+  PRISM_HIP(hipMemcpyAsync(d_pos.p, pos.data(), (size_t)T * 4, hipMemcpyHostToDevice, s));
+  if (!bf) {
+    PRISM_TRY(launch_attention_fp32((const float *)QKV, (const int32_t *)d_pos.p, T, nq, nkv, hd, (float *)out, s));
+  } else {
+    PRISM_TRY(d_vtcol.alloc((size_t)T * 4));
+    PRISM_TRY(d_tiles.alloc(tiles.size() * sizeof(AttnTile)));
+    const size_t vt_bytes = (size_t)round_up((size_t)col * nkv * hd * 2, 256);
+    PRISM_TRY(d_vt.alloc(vt_bytes));
+    PRISM_HIP(hipMemcpyAsync(d_vtcol.p, vtcol.data(), (size_t)T * 4, hipMemcpyHostToDevice, s));
+    PRISM_HIP(hipMemcpyAsync(d_tiles.p, tiles.data(), tiles.size() * sizeof(AttnTile), hipMemcpyHostToDevice, s));
+    PRISM_TRY(launch_fill_zero(d_vt.p, vt_bytes, s));
+    PRISM_TRY(launch_v_transpose((const bf16 *)QKV, T, nq, nkv, hd, (bf16 *)d_vt.p, (const int32_t *)d_vtcol.p, col, s));
+    PRISM_TRY(launch_attention_bf16((const bf16 *)QKV, (const bf16 *)d_vt.p, col, (const AttnTile *)d_tiles.p, (int)tiles.size(),
+                                    T, nq, nkv, hd, (bf16 *)out, s));
+  }
+  PRISM_HIP(hipStreamSynchronize(s));   // temporaries and host vectors are released on return
+  return PRISM_OK;
+}
+
+extern "C" int prism_op_score(const float *X, const int32_t *last_row, int32_t n_seqs, int32_t hidden, const void *final_norm,
+                              const void *w_yes, const void *w_no, int32_t dtype, float eps, float *scores, void *stream) {
+  return launch_score(X, last_row, n_seqs, hidden, final_norm, w_yes, w_no, dtype, eps, scores, (hipStream_t)stream);
+}
+
+extern "C" int prism_op_route(const float *scores, int32_t n, int32_t K_rem, int32_t n_clusters, float tau, int8_t *fate,
+                              double *stats, void *stream) {
+  PRISM_REQUIRE(n >= 1 && n <= PRISM_MAX_CANDS && n_clusters >= 2 && n_clusters <= PRISM_MAX_CLUSTERS, PRISM_EINVAL,
+                "route: n = %d or n_clusters = %d out of range", n, n_clusters);
+  hipStream_t s = (hipStream_t)stream;
+  TmpDev ws;
+  PRISM_TRY(ws.alloc(route_workspace_bytes(n, n_clusters)));
+  PRISM_TRY(launch_route(scores, n, K_rem, n_clusters, tau, fate, stats, ws.p, s));
+  PRISM_HIP(hipStreamSynchronize(s));
+  return PRISM_OK;
+}
+
+extern "C" int prism_op_compact(const float *X_src, float *X_dst, const int32_t *src_start, const int32_t *dst_start,
+                                const int32_t *len, int32_t n_keep, int32_t hidden, void *stream) {
+  return launch_compact(X_src, X_dst, src_start, dst_start, len, n_keep, hidden, (hipStream_t)stream);
+}
+
+extern "C" int prism_op_topk(const float *scores, int32_t n, int32_t K, int32_t *out_pos, float *out_scores, void *stream) {
+  PRISM_REQUIRE(n <= PRISM_MAX_CANDS && K <= n, PRISM_EINVAL, "topk: n = %d, K = %d", n, K);
+  return launch_topk(scores, n, K, out_pos, out_scores, (hipStream_t)stream);
+}

@@ -1,0 +1,51 @@
+"""The C-ABI library loads and exports every symbol include/prism.h declares (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2510_15620_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    src = open(os.path.join(ROOT, "include", "prism.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(prism_[a-z_0-9]+)\s*\(", src)))
+
+
+@pytest.fixture(scope="module")
+def built():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2510_15620_amd import build
+        build.build(verbose=False)
+    return ctypes.CDLL(binding.LIB_PATH)
+
+
+def test_every_declared_symbol_is_exported(built):
+    names = _declared()
+    assert "prism_select" in names and "prism_create" in names and len(names) >= 15
+    for n in names:
+        assert hasattr(built, n), n
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_struct_layouts_match_the_header():
+    # sizes implied by the header's field lists (natural alignment, LP64)
+    assert ctypes.sizeof(binding.prism_model) == 11 * 4
+    assert ctypes.sizeof(binding.prism_layer_weights) == 11 * 8
+    assert ctypes.sizeof(binding.prism_weights) == 6 * 8
+    assert ctypes.sizeof(binding.prism_options) == 8 + 4 * 6 + 8 + 8
+    assert ctypes.sizeof(binding.prism_report) == 3 * 4 + 4 + 10 * 8 + 3 * 8 + 3 * 8 + 8
+
+
+def test_strerror_and_argument_errors_without_a_gpu(built):
+    built.prism_strerror.restype = ctypes.c_char_p
+    assert built.prism_strerror(0) == b"ok"
+    assert b"invalid" in built.prism_strerror(-1)
+    # null arguments are rejected before any HIP call
+    assert built.prism_create(None, None, None, None) == binding.EINVAL
+    assert built.prism_select(None, None, 0, None, None, 0, 0, None, None, None, None) == binding.EINVAL
+    built.prism_destroy(None)
