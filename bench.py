@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of the monolithic-forwarding hot path on one MI355X.
+
+One "step" is one prism_select over the whole synthetic workload (pack + embed, every layer over the
+live candidates, every pruning checkpoint, compaction, final top-K).  Weights and the context are
+resident in HBM before the timed region; the tokens are handed over as host arrays, as the C ABI
+defines (a few hundred KB).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4_8b]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
+KIND_NAMES = ["gemm_qkv", "gemm_o", "gemm_gate_up_swiglu", "gemm_down", "attention", "elementwise"]
+
+
+def cpu_baseline(w, wt_dev, q, cands, token_layers_job: int, n_cands: int):
+    """The oracle as it stands, timed on a bounded sample: ONE candidate through the first two layers
+    plus one scoring, extrapolated by token-layers to the job the GPU ran (same pruning schedule)."""
+    import numpy as np
+    from oracle import prism_oracle as O
+    from tests.helpers import oracle_model, to_f64
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    n_layers = min(2, w.model.n_layers)
+    c = int(np.argmin([abs(len(x) - np.median([len(y) for y in cands])) for x in cands]))
+    ow = {"embed": None, "final_norm": to_f64(wt_dev.final_norm), "w_yes": to_f64(wt_dev.w_yes), "w_no": to_f64(wt_dev.w_no),
+          "layers": [{k: to_f64(v) for k, v in wt_dev.layers[l].items()} for l in range(n_layers)]}
+    toks = np.concatenate([q, cands[c]])
+    emb_rows = to_f64(wt_dev.embed[toks.tolist()])
+    om = oracle_model(w.model)
+    t0 = time.perf_counter()
+    X = emb_rows
+    for l in range(n_layers):
+        X = O.layer_forward(X, ow["layers"][l], om)
+    O.head_score(X[-1], ow["final_norm"], ow["w_yes"], ow["w_no"], om.rms_eps)
+    dt = time.perf_counter() - t0
+    sample_token_layers = len(toks) * n_layers
+    job_seconds = dt * token_layers_job / sample_token_layers
+    return {"value": n_cands / job_seconds, "unit": "candidates/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"fp64 numpy oracle, candidate {c} ({len(toks)} tokens) through layers 1-{n_layers} + one scoring: "
+                      f"{dt:.2f} s, scaled by token-layers ({token_layers_job} in the pruned job / {sample_token_layers} in the sample)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="cfg4_8b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-unpruned", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 (the path shards by candidate, see DESIGN.md)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2510_15620_amd import binding as B
+    from paper_2510_15620_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    w = W.WORKLOADS[args.workload]
+    m = w.model
+    t_gen = time.perf_counter()
+    if w.stream_weights:
+        dev = W.make_weights(w, "cuda")
+        host_layers = [{k: v.to("cpu").pin_memory() for k, v in l.items()} for l in dev.layers]
+        wt = W.Weights(dev.embed, host_layers, dev.final_norm)
+        wt_for_oracle = dev
+    else:
+        wt = wt_for_oracle = W.make_weights(w, "cuda")
+    q, cands = W.make_tokens(w)
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t_gen
+    opts = dict(checkpoints=w.checkpoints, cv_threshold=w.cv_threshold, n_clusters=w.n_clusters, chunk_cands=w.chunk_cands,
+                hbm_cap_bytes=w.hbm_cap_bytes, stream_weights=w.stream_weights)
+    p = B.Prism(m, wt, **opts)
+
+    for _ in range(args.warmup):
+        p.select(q, cands, w.K, report=False)
+    torch.cuda.synchronize()
+    reps = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        idx, scores, rep = p.select(q, cands, w.K, report=True)      # synchronous: results are on the host
+        reps.append(rep)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall / args.steps * 1e3
+    rep = reps[-1]
+
+    unpruned_ms = None
+    if not args.no_unpruned:
+        p0 = B.Prism(m, wt, **{**opts, "mode": B.MODE_NO_PRUNING})
+        p0.select(q, cands, w.K, report=False)
+        t1 = time.perf_counter()
+        p0.select(q, cands, w.K, report=False)
+        unpruned_ms = (time.perf_counter() - t1) * 1e3
+        p0.destroy()
+
+    # per-kernel-kind totals over the timed steps (HIP events around each launch on the compute stream)
+    kinds = {}
+    for k, name in enumerate(KIND_NAMES):
+        ms = sum(r.kind_ms[k] for r in reps)
+        fl = sum(r.kind_flops[k] for r in reps)
+        n = sum(r.kind_launches[k] for r in reps)
+        kinds[name] = {"launches": n, "ms": round(ms, 3), "tflops": round(fl / ms / 1e9, 1) if ms > 0 and fl > 0 else None}
+    dom = 2        # the gate/up GEMM with the SwiGLU epilogue carries more than half of all flops
+    dom_ms = sum(r.kind_ms[dom] for r in reps)
+    dom_fl = sum(r.kind_flops[dom] for r in reps)
+    dom_n = sum(r.kind_launches[dom] for r in reps)
+    achieved = dom_fl / dom_ms / 1e9
+    roofline = {"bound": "mfma", "kernel": "gemm_bf16_kernel<256,256,2,4,SWIGLU>", "achieved": round(achieved, 1),
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "flops_per_launch": dom_fl / dom_n, "avg_launch_ms": round(dom_ms / dom_n, 4), "launches": dom_n}
+    gemm_ms = sum(r.kind_ms[k] for r in reps for k in range(4))
+    gemm_fl = sum(r.kind_flops[k] for r in reps for k in range(4))
+    attn_ms = sum(r.kind_ms[4] for r in reps)
+    attn_fl = sum(r.kind_flops[4] for r in reps)
+
+    out = {
+        "metric": "candidates/sec + top-K latency (ms), 8B-shaped reranker, 100 cands x 1024 tok"
+                  if args.workload == "cfg4_8b" else f"candidates/sec + top-K latency (ms), {args.workload}",
+        "value": round(w.n_cands / (ms_per_step / 1e3), 2), "unit": "candidates/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if m.dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: {m.n_layers} layers, hidden {m.hidden}, {m.n_q_heads}/{m.n_kv_heads} heads x {m.head_dim}, "
+                               f"ffn {m.ffn}, vocab {m.vocab}; query {w.query_len} tok, {w.n_cands} candidates, "
+                               f"{int(sum(len(c) + len(q) for c in cands))} tokens in all; K={w.K}; "
+                               f"checkpoints after layers {w.checkpoints}; k={w.n_clusters} clusters, tau={w.cv_threshold}, drop-only",
+                   "n_cands": w.n_cands, "K": w.K, "seed": w.seed, "chunk_cands": w.chunk_cands, "stream_weights": w.stream_weights},
+        "topk_latency_ms": round(ms_per_step, 3),
+        "unpruned_latency_ms": None if unpruned_ms is None else round(unpruned_ms, 3),
+        "gpu_ms": {"total": round(rep.ms_total, 3), "layers": round(rep.ms_layers, 3), "checks": round(rep.ms_checks, 3)},
+        "survivors": {"layer": rep.layer.tolist(), "n_before": rep.n_before.tolist(), "n_after": rep.n_after.tolist()},
+        "token_layers": int(rep.token_layers), "peak_hbm_bytes": int(rep.peak_hbm_bytes), "bytes_streamed": int(rep.bytes_streamed),
+        "topk": idx.tolist(),
+        "kernels": kinds,
+        "mfma_utilisation": {"layer_gemms": round(gemm_fl / gemm_ms / 1e9 / PEAK_BF16_TFLOPS, 4) if gemm_ms else None,
+                             "attention": round(attn_fl / attn_ms / 1e9 / PEAK_BF16_TFLOPS, 4) if attn_ms else None},
+        "roofline": roofline,
+        "weights_gen_s": round(t_gen, 1),
+    }
+    if w.stream_weights and rep.ms_total > 0:
+        out["stream_GBps"] = round(rep.bytes_streamed / rep.ms_total / 1e6, 1)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, wt_for_oracle, q, cands, int(rep.token_layers), w.n_cands)
+    p.destroy()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -42,6 +42,7 @@ extern "C" {
 #define PRISM_MAX_CANDS    4096  /* candidates per call */
 #define PRISM_MAX_CLUSTERS 8
 #define PRISM_MAX_SEQ      8192  /* tokens per (query + candidate) sequence */
+#define PRISM_N_KINDS      6     /* kernel kinds timed in prism_report */
 
 /* fates written to prism_report.ev_fate (Sec. 4.1) */
 #define PRISM_FATE_NOT_LIVE (-1)
@@ -110,6 +111,14 @@ typedef struct {
   int64_t  peak_hbm_bytes;  /* out: library-owned device memory at its peak */
   int64_t  bytes_streamed;  /* out: host->device weight bytes copied during the call */
   int32_t  layers_run;      /* out */
+  /* out: per-kernel-kind totals over the call, from HIP events around each launch on the compute stream.
+   * kinds: 0 fused QKV GEMM, 1 O-projection GEMM, 2 gate/up GEMM with SwiGLU, 3 down GEMM, 4 attention,
+   * 5 the elementwise steps of a layer (RMSNorm, q/k norm + RoPE, V transposition).
+   * kind_flops is the ALGORITHMIC work: 2*M*N*K per GEMM (live tokens only), 2*nq*hd*L*(L+1) per sequence
+   * of attention (causal triangle only); 0 for kind 5. */
+  int32_t  kind_launches[PRISM_N_KINDS];
+  double   kind_ms[PRISM_N_KINDS];
+  double   kind_flops[PRISM_N_KINDS];
 } prism_report;
 
 /* Build a context.  Device-resident layer weights are repacked once into library-owned HBM

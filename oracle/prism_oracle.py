@@ -26,7 +26,16 @@ Readings taken where the paper is silent (each is also listed in the design note
     positions in rank order; with fewer distinct scores than clusters the number
     of clusters is reduced, with one distinct score nothing is pruned;
   * ranking: score descending, ties by lower original index;
-  * number of clusters: an option, default 3.
+  * number of clusters: an option, default 3;
+  * operand precision: Model.operand = "exact" keeps every value in fp64.  "bf16" / "f16" round the
+    operands of the matrix-core contractions to that type (round-to-nearest-even): the normalised
+    GEMM inputs, q and k after RoPE, v, the attention output and the SwiGLU output - the weights are
+    already of that type.  Accumulation, softmax (including the probabilities), norms and the
+    residual stream stay in fp64.  This is the arithmetic a 16-bit-operand forward defines, whatever
+    its blocking; it is not a model of any particular kernel.  On the 4B/8B-shaped workloads the
+    rounded forward differs from the exact one by up to ~5e-2 in score (measured), more than the
+    2e-2 parity tolerance, so the 16-bit device modes are compared with the oracle in the same
+    operand precision and the distance to the exact oracle is reported beside it.
 
 Parity status: the numeric score values on the synthetic workloads are "parity
 unpinned" by the paper (it prints no scores and ships no weights); they are
@@ -93,6 +102,20 @@ def silu(x: np.ndarray) -> np.ndarray:
     return x / (1.0 + np.exp(-x))
 
 
+def round_operand(x: np.ndarray, kind: str) -> np.ndarray:
+    """Value of x after rounding to the operand type (round-to-nearest-even), returned as fp64."""
+    if kind == "exact":
+        return x
+    if kind == "f16":
+        return np.asarray(x, F64).astype(np.float16).astype(F64)
+    if kind == "bf16":
+        f = np.ascontiguousarray(np.asarray(x, F64).astype(np.float32))
+        u = f.view(np.uint32).astype(np.uint64)
+        u = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16) << 16          # nearest, ties to even, on the top 16 bits
+        return u.astype(np.uint32).view(np.float32).reshape(f.shape).astype(F64)
+    raise ValueError(kind)
+
+
 @dataclass
 class Model:
     n_layers: int
@@ -105,28 +128,31 @@ class Model:
     rms_eps: float = 1e-6
     rope_base: float = 1e6
     qk_norm: bool = True
+    operand: str = "exact"          # "exact" | "bf16" | "f16": precision of the contraction operands
 
 
 def attention_block(X: np.ndarray, lw: Dict[str, np.ndarray], m: Model) -> np.ndarray:
     """X + Attn(RMSNorm(X)) W_o^T for one sequence X [L, hidden]; positions 0..L-1."""
     L = X.shape[0]
-    xn = rmsnorm(X, lw["attn_norm"], m.rms_eps)
+    rnd = lambda t: round_operand(t, m.operand)
+    xn = rnd(rmsnorm(X, lw["attn_norm"], m.rms_eps))
     q = (xn @ lw["wq"].T).reshape(L, m.n_q_heads, m.head_dim)
     k = (xn @ lw["wk"].T).reshape(L, m.n_kv_heads, m.head_dim)
-    v = (xn @ lw["wv"].T).reshape(L, m.n_kv_heads, m.head_dim)
+    v = rnd((xn @ lw["wv"].T).reshape(L, m.n_kv_heads, m.head_dim))
     if m.qk_norm:
         q = rmsnorm(q, lw["q_norm"], m.rms_eps)
         k = rmsnorm(k, lw["k_norm"], m.rms_eps)
     pos = np.arange(L)
-    q, k = rope(q, pos, m.rope_base), rope(k, pos, m.rope_base)
-    a = causal_gqa_attention(q, k, v).reshape(L, m.n_q_heads * m.head_dim)
+    q, k = rnd(rope(q, pos, m.rope_base)), rnd(rope(k, pos, m.rope_base))
+    a = rnd(causal_gqa_attention(q, k, v).reshape(L, m.n_q_heads * m.head_dim))
     return X + a @ lw["wo"].T
 
 
 def ffn_block(X: np.ndarray, lw: Dict[str, np.ndarray], m: Model) -> np.ndarray:
     """X + (silu(Xn W_g^T) * (Xn W_u^T)) W_d^T with Xn = RMSNorm(X)."""
-    xn = rmsnorm(X, lw["ffn_norm"], m.rms_eps)
-    return X + (silu(xn @ lw["w_gate"].T) * (xn @ lw["w_up"].T)) @ lw["w_down"].T
+    xn = round_operand(rmsnorm(X, lw["ffn_norm"], m.rms_eps), m.operand)
+    act = round_operand(silu(xn @ lw["w_gate"].T) * (xn @ lw["w_up"].T), m.operand)
+    return X + act @ lw["w_down"].T
 
 
 def layer_forward(X: np.ndarray, lw: Dict[str, np.ndarray], m: Model) -> np.ndarray:

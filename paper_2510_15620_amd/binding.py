@@ -63,7 +63,8 @@ class prism_report(C.Structure):
                 ("ev_scores", C.POINTER(C.c_float)), ("ev_fate", C.POINTER(C.c_int8)),
                 ("ms_total", C.c_double), ("ms_layers", C.c_double), ("ms_checks", C.c_double),
                 ("token_layers", C.c_int64), ("peak_hbm_bytes", C.c_int64), ("bytes_streamed", C.c_int64),
-                ("layers_run", C.c_int32)]
+                ("layers_run", C.c_int32), ("kind_launches", C.c_int32 * 6), ("kind_ms", C.c_double * 6),
+                ("kind_flops", C.c_double * 6)]
 
 
 _lib = None
@@ -137,6 +138,9 @@ class Report:
     peak_hbm_bytes: int
     bytes_streamed: int
     layers_run: int
+    kind_launches: List[int] = field(default_factory=list)   # QKV, O, gate/up, down GEMMs, attention, elementwise
+    kind_ms: List[float] = field(default_factory=list)
+    kind_flops: List[float] = field(default_factory=list)
 
 
 class Prism:
@@ -197,7 +201,8 @@ class Prism:
             r = Report(arrs["layer"][:e], arrs["n_before"][:e], arrs["n_after"][:e], arrs["tokens_after"][:e],
                        arrs["gate"][:e].astype(bool), arrs["n_clusters"][:e], arrs["mean"][:e], arrs["std"][:e],
                        arrs["scores"][:e], arrs["fate"][:e], rep.ms_total, rep.ms_layers, rep.ms_checks,
-                       rep.token_layers, rep.peak_hbm_bytes, rep.bytes_streamed, rep.layers_run)
+                       rep.token_layers, rep.peak_hbm_bytes, rep.bytes_streamed, rep.layers_run,
+                       list(rep.kind_launches), list(rep.kind_ms), list(rep.kind_flops))
         return out_idx[:k].copy(), out_scores[:k].copy(), r
 
     def set_forced_keep(self, masks: Optional[np.ndarray]):

@@ -99,6 +99,11 @@ struct prism_ctx {
   hipEvent_t ev_ready[2] = {nullptr, nullptr}, ev_free[2] = {nullptr, nullptr};
   hipEvent_t ev_t[4] = {nullptr, nullptr, nullptr, nullptr};
   std::vector<hipEvent_t> ev_layer;               // 2 per layer, for the report
+  // per-launch spans for the report: events come from a pool that only grows
+  struct Span { int kind; hipEvent_t a, b; double flops; };
+  std::vector<hipEvent_t> ev_pool; size_t ev_used = 0;
+  std::vector<Span> spans;
+  bool profiling = false;
   float2 *rope_tab = nullptr;
 
   // scratch, grown on demand
@@ -271,6 +276,7 @@ extern "C" void prism_destroy(prism_ctx *c) {
   }
   for (int i = 0; i < 4; ++i) if (c->ev_t[i]) (void)hipEventDestroy(c->ev_t[i]);
   for (hipEvent_t e : c->ev_layer) if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : c->ev_pool) if (e) (void)hipEventDestroy(e);
   if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
   if (c->own_stream && c->stream) (void)hipStreamDestroy(c->stream);
   delete c;
@@ -422,40 +428,69 @@ static int upload_meta(prism_ctx *c, const Plan &p, const MetaOff &mo, bool with
   return PRISM_OK;
 }
 
+static int span_event(prism_ctx *c, hipEvent_t *e) {
+  if (c->ev_used == c->ev_pool.size()) {
+    hipEvent_t n = nullptr;
+    PRISM_HIP(hipEventCreate(&n));
+    c->ev_pool.push_back(n);
+  }
+  *e = c->ev_pool[c->ev_used++];
+  PRISM_HIP(hipEventRecord(*e, c->stream));
+  return PRISM_OK;
+}
+
+// Times the launches issued by `body` as one span of the given kind (only when a report was asked for).
+template <typename Fn>
+static int timed_span(prism_ctx *c, int kind, double flops, Fn body) {
+  if (!c->profiling) return body();
+  prism_ctx::Span sp{kind, nullptr, nullptr, flops};
+  PRISM_TRY(span_event(c, &sp.a));
+  PRISM_TRY(body());
+  PRISM_TRY(span_event(c, &sp.b));
+  c->spans.push_back(sp);
+  return PRISM_OK;
+}
+
 static int run_layer(prism_ctx *c, const Plan &p, const MetaOff &mo, float *X, const char *wbuf) {
   const prism_model &m = c->m;
   const LayerLayout &L = c->lay;
   const int H = m.hidden, Dq = m.n_q_heads * m.head_dim, Dkv = m.n_kv_heads * m.head_dim, F = m.ffn;
   hipStream_t s = c->stream;
   const bool bf = m.dtype == PRISM_DTYPE_BF16;
+  auto gemm = [&](int epi, const void *A, const void *W, void *out, int M, int N, int K) {
+    return bf ? launch_gemm_bf16(epi, (const bf16 *)A, (const bf16 *)W, out, M, N, K, s)
+              : launch_gemm_fp32(epi, (const float *)A, (const float *)W, out, M, N, K, s);
+  };
   for (const Chunk &ch : p.chunks) {
     const int Tc = (int)(ch.r1 - ch.r0);
     float *Xc = X + ch.r0 * H;
     const int32_t *pos = c->d_meta + mo.pos + ch.r0;
-    PRISM_TRY(launch_rmsnorm(Xc, wbuf + L.attn_norm, Tc, H, m.rms_eps, m.dtype, c->Xn, s));
-    if (bf) {
-      PRISM_TRY(launch_gemm_bf16(PRISM_EPI_STORE, (const bf16 *)c->Xn, (const bf16 *)(wbuf + L.wqkv), c->QKV, Tc, Dq + 2 * Dkv, H, s));
+    double attn_flops = 0.0;
+    for (int i = ch.c0; i < ch.c1; ++i) attn_flops += 2.0 * m.n_q_heads * m.head_dim * (double)p.len[i] * (p.len[i] + 1.0);
+    const double tk = 2.0 * Tc;
+    // ---- attention block: X += Attn(RMSNorm(X)) Wo^T
+    PRISM_TRY(timed_span(c, 5, 0.0, [&] { return launch_rmsnorm(Xc, wbuf + L.attn_norm, Tc, H, m.rms_eps, m.dtype, c->Xn, s); }));
+    PRISM_TRY(timed_span(c, 0, tk * (Dq + 2 * Dkv) * H, [&] { return gemm(PRISM_EPI_STORE, c->Xn, wbuf + L.wqkv, c->QKV, Tc, Dq + 2 * Dkv, H); }));
+    PRISM_TRY(timed_span(c, 5, 0.0, [&] {
       PRISM_TRY(launch_qknorm_rope(m.dtype, c->QKV, pos, wbuf + L.q_norm, wbuf + L.k_norm, Tc, m.n_q_heads, m.n_kv_heads,
                                    m.head_dim, m.rms_eps, m.qk_norm, c->rope_tab, s));
-      PRISM_TRY(launch_v_transpose((const bf16 *)c->QKV, Tc, m.n_q_heads, m.n_kv_heads, m.head_dim, (bf16 *)c->Vt,
-                                   c->d_meta + mo.vtcol + ch.r0, c->vt_cap, s));
-      PRISM_TRY(launch_attention_bf16((const bf16 *)c->QKV, (const bf16 *)c->Vt, c->vt_cap,
-                                      (const AttnTile *)(c->d_meta + mo.tiles) + ch.tile0, ch.n_tiles, Tc, m.n_q_heads,
-                                      m.n_kv_heads, m.head_dim, (bf16 *)c->AO, s));
-      PRISM_TRY(launch_gemm_bf16(PRISM_EPI_RESIDUAL, (const bf16 *)c->AO, (const bf16 *)(wbuf + L.wo), Xc, Tc, H, Dq, s));
-      PRISM_TRY(launch_rmsnorm(Xc, wbuf + L.ffn_norm, Tc, H, m.rms_eps, m.dtype, c->Xn, s));
-      PRISM_TRY(launch_gemm_bf16(PRISM_EPI_SWIGLU, (const bf16 *)c->Xn, (const bf16 *)(wbuf + L.wgu), c->S, Tc, 2 * F, H, s));
-      PRISM_TRY(launch_gemm_bf16(PRISM_EPI_RESIDUAL, (const bf16 *)c->S, (const bf16 *)(wbuf + L.wd), Xc, Tc, H, F, s));
-    } else {
-      PRISM_TRY(launch_gemm_fp32(PRISM_EPI_STORE, (const float *)c->Xn, (const float *)(wbuf + L.wqkv), c->QKV, Tc, Dq + 2 * Dkv, H, s));
-      PRISM_TRY(launch_qknorm_rope(m.dtype, c->QKV, pos, wbuf + L.q_norm, wbuf + L.k_norm, Tc, m.n_q_heads, m.n_kv_heads,
-                                   m.head_dim, m.rms_eps, m.qk_norm, c->rope_tab, s));
-      PRISM_TRY(launch_attention_fp32((const float *)c->QKV, pos, Tc, m.n_q_heads, m.n_kv_heads, m.head_dim, (float *)c->AO, s));
-      PRISM_TRY(launch_gemm_fp32(PRISM_EPI_RESIDUAL, (const float *)c->AO, (const float *)(wbuf + L.wo), Xc, Tc, H, Dq, s));
-      PRISM_TRY(launch_rmsnorm(Xc, wbuf + L.ffn_norm, Tc, H, m.rms_eps, m.dtype, c->Xn, s));
-      PRISM_TRY(launch_gemm_fp32(PRISM_EPI_SWIGLU, (const float *)c->Xn, (const float *)(wbuf + L.wgu), c->S, Tc, 2 * F, H, s));
-      PRISM_TRY(launch_gemm_fp32(PRISM_EPI_RESIDUAL, (const float *)c->S, (const float *)(wbuf + L.wd), Xc, Tc, H, F, s));
-    }
+      if (bf)
+        PRISM_TRY(launch_v_transpose((const bf16 *)c->QKV, Tc, m.n_q_heads, m.n_kv_heads, m.head_dim, (bf16 *)c->Vt,
+                                     c->d_meta + mo.vtcol + ch.r0, c->vt_cap, s));
+      return (int)PRISM_OK;
+    }));
+    PRISM_TRY(timed_span(c, 4, attn_flops, [&] {
+      if (bf)
+        return launch_attention_bf16((const bf16 *)c->QKV, (const bf16 *)c->Vt, c->vt_cap,
+                                     (const AttnTile *)(c->d_meta + mo.tiles) + ch.tile0, ch.n_tiles, Tc, m.n_q_heads,
+                                     m.n_kv_heads, m.head_dim, (bf16 *)c->AO, s);
+      return launch_attention_fp32((const float *)c->QKV, pos, Tc, m.n_q_heads, m.n_kv_heads, m.head_dim, (float *)c->AO, s);
+    }));
+    PRISM_TRY(timed_span(c, 1, tk * H * Dq, [&] { return gemm(PRISM_EPI_RESIDUAL, c->AO, wbuf + L.wo, Xc, Tc, H, Dq); }));
+    // ---- FFN block: X += (silu(Xn Wg^T) * (Xn Wu^T)) Wd^T
+    PRISM_TRY(timed_span(c, 5, 0.0, [&] { return launch_rmsnorm(Xc, wbuf + L.ffn_norm, Tc, H, m.rms_eps, m.dtype, c->Xn, s); }));
+    PRISM_TRY(timed_span(c, 2, tk * 2 * F * H, [&] { return gemm(PRISM_EPI_SWIGLU, c->Xn, wbuf + L.wgu, c->S, Tc, 2 * F, H); }));
+    PRISM_TRY(timed_span(c, 3, tk * H * F, [&] { return gemm(PRISM_EPI_RESIDUAL, c->S, wbuf + L.wd, Xc, Tc, H, F); }));
   }
   return PRISM_OK;
 }
@@ -510,6 +545,9 @@ extern "C" int prism_select(prism_ctx *c, const int32_t *query_tokens, int32_t q
     }
   }
   const bool timed = rep != nullptr;
+  c->profiling = timed;
+  c->spans.clear();
+  c->ev_used = 0;
   if (timed && (int)c->ev_layer.size() < 2 * m.n_layers) {
     const size_t old = c->ev_layer.size();
     c->ev_layer.resize(2 * m.n_layers, nullptr);
@@ -696,6 +734,13 @@ extern "C" int prism_select(prism_ctx *c, const int32_t *query_tokens, int32_t q
     rep->peak_hbm_bytes = c->bytes_peak;
     rep->bytes_streamed = bytes_streamed;
     rep->layers_run = layers_run;
+    for (int k = 0; k < PRISM_N_KINDS; ++k) { rep->kind_launches[k] = 0; rep->kind_ms[k] = 0.0; rep->kind_flops[k] = 0.0; }
+    for (const prism_ctx::Span &sp : c->spans) {
+      PRISM_HIP(hipEventElapsedTime(&ms, sp.a, sp.b));
+      rep->kind_launches[sp.kind] += 1;
+      rep->kind_ms[sp.kind] += ms;
+      rep->kind_flops[sp.kind] += sp.flops;
+    }
   }
   return PRISM_OK;
 }

@@ -132,6 +132,11 @@ class Workload:
     stream_weights: bool = False
     hbm_cap_bytes: int = 0
     seed: int = 0
+    weights_name: str = ""    # stream name of the weight tensors; "" = the workload's own name
+
+    @property
+    def wname(self) -> str:
+        return self.weights_name or self.name
 
 
 def _every(n_layers, stride):
@@ -154,7 +159,8 @@ WORKLOADS: Dict[str, Workload] = {
     # BASELINE configs[4]: 8B-shaped, weights streamed from pinned host memory, chunks of 64
     "cfg5_8b_stream": Workload("cfg5_8b_stream", ModelShape(36, 4096, 32, 8, 128, 12288, 151936),
                                64, 500, ("lognormal", 400.0, 0.6, 32, 2048), 20, _every(36, 4),
-                               chunk_cands=64, stream_weights=True, hbm_cap_bytes=24 * 10**9),
+                               chunk_cands=64, stream_weights=True, hbm_cap_bytes=24 * 10**9,
+                               weights_name="cfg4_8b"),       # "8B-shaped reranker as in the previous config"
     # small cases for element-by-element parity (not BASELINE configs)
     "mini_bf16": Workload("mini_bf16", ModelShape(4, 512, 8, 2, 128, 1408, 2048),
                           24, 13, ("uniform", 20, 300), 4, [1, 2, 3]),
@@ -209,7 +215,7 @@ def make_layer(w: Workload, layer: int, device="cpu") -> Dict[str, torch.Tensor]
     out = {}
     for name, shape in layer_tensor_shapes(w.model).items():
         mean = 1.0 if len(shape) == 1 else 0.0
-        out[name] = gaussian(w.seed, f"{w.name}/L{layer}/{name}", shape, mean, 0.02, dt, device)
+        out[name] = gaussian(w.seed, f"{w.wname}/L{layer}/{name}", shape, mean, 0.02, dt, device)
     return out
 
 
@@ -234,7 +240,7 @@ def make_weights(w: Workload, device="cpu", layers: Optional[List[int]] = None) 
     """All tensors of the model (or only the listed layers; others are left out as None)."""
     dt = torch_dtype(w.model)
     m = w.model
-    embed = gaussian(w.seed, w.name + "/embed", (m.vocab, m.hidden), 0.0, 0.02, dt, device)
-    final_norm = gaussian(w.seed, w.name + "/final_norm", (m.hidden,), 1.0, 0.02, dt, device)
+    embed = gaussian(w.seed, w.wname + "/embed", (m.vocab, m.hidden), 0.0, 0.02, dt, device)
+    final_norm = gaussian(w.seed, w.wname + "/final_norm", (m.hidden,), 1.0, 0.02, dt, device)
     ls = [make_layer(w, l, device) if (layers is None or l in layers) else None for l in range(m.n_layers)]
     return Weights(embed, ls, final_norm)

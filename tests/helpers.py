@@ -19,9 +19,13 @@ def oracle_weights(wt: W.Weights, layers=None) -> dict:
     }
 
 
-def oracle_model(m: W.ModelShape) -> O.Model:
+def oracle_model(m: W.ModelShape, operand: str = None) -> O.Model:
+    """operand: precision of the contraction operands; by default the workload's own mode
+    (fp32 workloads: exact; bf16 workloads: bf16 operands)."""
+    if operand is None:
+        operand = "exact" if m.dtype == "fp32" else "bf16"
     return O.Model(m.n_layers, m.hidden, m.n_q_heads, m.n_kv_heads, m.head_dim, m.ffn, m.vocab,
-                   m.rms_eps, m.rope_base, m.qk_norm)
+                   m.rms_eps, m.rope_base, m.qk_norm, operand)
 
 
 def oracle_select(w: W.Workload, wt=None, tokens=None, **over):
@@ -30,4 +34,5 @@ def oracle_select(w: W.Workload, wt=None, tokens=None, **over):
     kw = dict(checkpoints=w.checkpoints, n_clusters=w.n_clusters, tau=w.cv_threshold, mode=O.MODE_DROP_ONLY)
     kw.update(over)
     K = kw.pop("K", w.K)
-    return O.select(q, cands, K, oracle_weights(wt), oracle_model(w.model), **kw)
+    operand = kw.pop("operand", None)
+    return O.select(q, cands, K, oracle_weights(wt), oracle_model(w.model, operand), **kw)

@@ -226,3 +226,32 @@ def test_head_score_hand_value():
     yes, no = np.array([1.0, 0, 0, 0]), np.array([0, 1.0, 0, 0])
     # z = h * g = [1, -2, 1, -1]; yes - no = 1 - (-2) = 3
     assert abs(O.head_score(h, g, yes, no, 0.0) - 3.0) < 1e-14
+
+
+def test_operand_rounding_is_round_to_nearest_even():
+    # bf16 keeps 8 significand bits: spacing 2^-7 in [1, 2)
+    x = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 2 ** -8 + 2 ** -20, 1.0 + 3 * 2 ** -8, -(1.0 + 2 ** -8), 3.14159265, 1e-3])
+    got = O.round_operand(x, "bf16")
+    assert got[0] == 1.0 and got[1] == 1.0                      # tie -> even (1.0)
+    assert got[2] == 1.0 + 2 ** -7                              # just above the tie -> up
+    assert got[3] == 1.0 + 2 ** -6 and got[4] == -1.0           # tie -> even (1 + 2/128); sign symmetric
+    assert got[5] == 3.140625 and abs(got[6] - 1e-3) < 1e-3 * 2 ** -8
+    ref = torch.tensor(x, dtype=torch.float64).to(torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(got, ref)                             # library conversion agrees
+    r = np.random.default_rng(0).normal(size=4096) * 10.0 ** np.random.default_rng(1).integers(-6, 6, 4096)
+    assert np.array_equal(O.round_operand(r, "bf16"),
+                          torch.tensor(r).to(torch.float32).to(torch.bfloat16).to(torch.float64).numpy())
+    assert np.array_equal(O.round_operand(r, "f16"), torch.tensor(r).to(torch.float16).to(torch.float64).numpy())
+    assert O.round_operand(r, "exact") is r
+
+
+def test_operand_rounding_enters_only_at_contraction_operands():
+    m = _tiny_model()
+    w = _tiny_weights(m, 8)
+    r = np.random.default_rng(9)
+    toks = r.integers(0, m.vocab, 9)
+    exact = O.score_trajectory(toks[:4], toks[4:], w, m, [2])[2]
+    import dataclasses
+    for kind, eps in (("bf16", 2 ** -8), ("f16", 2 ** -11)):
+        got = O.score_trajectory(toks[:4], toks[4:], w, dataclasses.replace(m, operand=kind), [2])[2]
+        assert got != exact and abs(got - exact) < 60 * eps     # a perturbation of the size of the rounding
