@@ -10,8 +10,13 @@
  * Conventions
  *   - Plain C types only.  Every pointer is tagged [host] or [device] below.
  *   - Matrices are row-major [out_features, in_features]; a projection is y = x W^T.
- *   - dtype: PRISM_DTYPE_FP32 or PRISM_DTYPE_BF16 is the storage type of all weights and
- *     the operand type of the layer GEMMs.  The residual stream is fp32 in both modes.
+ *   - prism_model.dtype, PRISM_DTYPE_FP32 or PRISM_DTYPE_BF16, is the storage type of all weights.
+ *     fp32 weights: every step in fp32.  bf16 weights: the operands of the matrix-core contractions
+ *     (normalised GEMM inputs, q, k, v, attention output, SwiGLU output, and the layer weights) are
+ *     16-bit, prism_options.operand says which 16-bit type; accumulation, softmax, norms and the
+ *     residual stream are fp32.  IEEE half operands (the default) hold every bf16 weight exactly
+ *     (down to 2^-17 in magnitude, below that to within 2^-25) and round activations 8x finer than
+ *     bf16, at the same matrix-core rate; bf16 operands trade that precision for range.
  *   - All entry points return PRISM_OK (0) or a negative PRISM_E* code; nothing throws,
  *     aborts or exits; outputs are untouched on error.  prism_last_error() gives detail.
  *   - A context is single-caller.  Different contexts may run concurrently.
@@ -34,6 +39,7 @@ extern "C" {
 
 #define PRISM_DTYPE_FP32 0
 #define PRISM_DTYPE_BF16 1
+#define PRISM_DTYPE_F16  2  /* IEEE half: an operand type (prism_options.operand, kernel-level calls), not a weight type */
 
 #define PRISM_MODE_DROP_ONLY  0  /* Sec. 7: only hopeless candidates are pruned; survivors reach full depth */
 #define PRISM_MODE_THREE_WAY  1  /* Sec. 4.1: selected leave early, deferred continue, early termination */
@@ -85,6 +91,8 @@ typedef struct {
   int32_t chunk_cands;                /* Sec. 4.3 chunked execution: candidates per chunk; 0 = whole pool */
   int64_t hbm_cap_bytes;              /* cap on library-owned device memory; 0 = unlimited */
   void   *stream;                     /* hipStream_t of the caller, or NULL for a library-owned stream */
+  int32_t operand;                    /* bf16 weights only: 0 or PRISM_DTYPE_F16 = IEEE half operands (default),
+                                         PRISM_DTYPE_BF16 = bf16 operands */
 } prism_options;
 
 /* Optional per-call record.  The caller allocates every array ([host]); an "event" is one
@@ -157,30 +165,43 @@ const char *prism_last_error(void);   /* thread-local detail of the last failure
 int prism_op_embed(const int32_t *tokens, int32_t T, const void *table, int32_t hidden, int32_t dtype,
                    float *X, void *stream);
 
-/* RMSNorm of the fp32 residual into the GEMM operand type: out[t,:] = X[t,:]/sqrt(mean(X[t,:]^2)+eps)*gain. */
+/* RMSNorm of the fp32 residual into the GEMM operand type (dtype FP32, BF16 or F16; gain in the same type): out[t,:] = X[t,:]/sqrt(mean(X[t,:]^2)+eps)*gain. */
 int prism_op_rmsnorm(const float *X, const void *gain, int32_t T, int32_t hidden, float eps, int32_t dtype,
                      void *out, void *stream);
 
 #define PRISM_EPI_STORE    0  /* C[M,N] (operand dtype) = A W^T */
 #define PRISM_EPI_RESIDUAL 1  /* X[M,N] (fp32) += A W^T */
 #define PRISM_EPI_SWIGLU   2  /* W is [2F,K] = [W_gate; W_up]; S[M,F] (operand dtype) = silu(A Wg^T) * (A Wu^T) */
+#define PRISM_EPI_STORE_F32 3 /* C[M,N] (fp32) = A W^T: the q/k/v projection, normalised and rotated before rounding */
 /* Layer contraction (Sec. 2.2: latency is dominated by the matrix multiplications of the blocks).
- * A [M,K], W [N,K] in dtype; N is the row count of W (2F for SWIGLU). */
+ * A [M,K], W [N,K] in dtype (FP32, BF16 or F16); N is the row count of W (2F for SWIGLU).  STORE_F32 exists for
+ * the 16-bit types only (with FP32, STORE already writes fp32). */
 int prism_op_gemm(int32_t dtype, int32_t epilogue, const void *A, const void *W, void *out,
                   int32_t M, int32_t N, int32_t K, void *stream);
 
-/* Per-head RMSNorm (optional, over head_dim, gains q_gain / k_gain [head_dim]) then rotate-half RoPE
- * (pair i with i + head_dim/2, angle pos * rope_base^(-2i/head_dim)) on the q and k parts of the fused
- * projection QKV [T, (nq+2nkv)*hd], in place.  pos[t] [device] is the position of token t in its
- * sequence, 0 <= pos[t] < max_pos <= PRISM_MAX_SEQ.  Synchronises the stream before returning. */
-int prism_op_qknorm_rope(int32_t dtype, void *QKV, const int32_t *pos, int32_t max_pos, const void *q_gain,
-                         const void *k_gain, int32_t T, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
-                         float eps, float rope_base, int32_t qk_norm, void *stream);
+/* Finishes the fused q/k/v projection QKV [T, (nq+2nkv)*hd] (fp32, [device]): per-head RMSNorm (optional,
+ * over head_dim, gains q_gain / k_gain [head_dim]) then rotate-half RoPE (pair i with i + head_dim/2, angle
+ * pos * rope_base^(-2i/head_dim)) on q and k.  pos[t] [device] is the position of token t in its sequence,
+ * 0 <= pos[t] < max_pos <= PRISM_MAX_SEQ.
+ *   fp32 mode: q and k are rewritten in place; QK and Vt are ignored (pass NULL).
+ *   BF16 / F16: q and k go to QK [T, (nq+nkv)*hd] in that type; v is rounded to that type and written
+ *     transposed to Vt [nkv][hd][vt_stride], always in IEEE half format (the operand type of the P V
+ *     contraction; it holds bf16 values exactly) at column vt_col[t] [device].  The caller lays the sequences out so that
+ *     each starts at a multiple of 64 columns, and zero-fills Vt once (pad columns must be finite).
+ * Synchronises the stream before returning. */
+int prism_op_qkv_finish(int32_t dtype, void *QKV, const int32_t *pos, int32_t max_pos, const void *q_gain,
+                        const void *k_gain, int32_t T, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                        float eps, float rope_base, int32_t qk_norm, void *QK, void *Vt, const int32_t *vt_col,
+                        int64_t vt_stride, void *stream);
 
 /* Causal GQA attention within each sequence (no token attends across sequences; Sec. 2.2).
- * QKV [T, (nq+2nkv)*hd] [device] with RoPE already applied; cu_seqlens [n_seqs+1] [host]: token offsets of
- * the sequences inside QKV; out [T, nq*hd] [device] in dtype.  Synchronises the stream before returning. */
-int prism_op_attention(int32_t dtype, const void *QKV, const int32_t *cu_seqlens_host, int32_t n_seqs,
+ * cu_seqlens [n_seqs+1] [host]: token offsets of the sequences; out [T, nq*hd] [device] in dtype.
+ *   fp32 mode: QK = the finished QKV buffer [T, (nq+2nkv)*hd] (fp32); Vt, vt_col0 ignored.
+ *   BF16 / F16: QK [T, (nq+nkv)*hd] in that type and Vt / vt_stride as written by prism_op_qkv_finish;
+ *     vt_col0 [n_seqs] [host]: first Vt column of each sequence (multiples of 64).
+ * Synchronises the stream before returning. */
+int prism_op_attention(int32_t dtype, const void *QK, const void *Vt, int64_t vt_stride,
+                       const int32_t *cu_seqlens_host, const int32_t *vt_col0_host, int32_t n_seqs,
                        int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, void *out, void *stream);
 
 /* Intermediate scorer (Sec. 4.1): for each sequence c, the last token's state through the final RMSNorm and

@@ -14,14 +14,14 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libprism.so")
 
 OK, EINVAL, ECAP, EHIP, ENOMEM, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
-DTYPE_FP32, DTYPE_BF16 = 0, 1
+DTYPE_FP32, DTYPE_BF16, DTYPE_F16 = 0, 1, 2
 MODE_DROP_ONLY, MODE_THREE_WAY, MODE_NO_PRUNING = 0, 1, 2
-EPI_STORE, EPI_RESIDUAL, EPI_SWIGLU = 0, 1, 2
+EPI_STORE, EPI_RESIDUAL, EPI_SWIGLU, EPI_STORE_F32 = 0, 1, 2, 3
 FATE_NOT_LIVE, FATE_DROPPED, FATE_DEFERRED, FATE_SELECTED = -1, 0, 1, 2
 MAX_CANDS, MAX_CLUSTERS, MAX_SEQ = 4096, 8, 8192
 
 EXPORTS = ["prism_create", "prism_select", "prism_set_forced_keep", "prism_destroy", "prism_strerror",
-           "prism_last_error", "prism_op_embed", "prism_op_rmsnorm", "prism_op_gemm", "prism_op_qknorm_rope",
+           "prism_last_error", "prism_op_embed", "prism_op_rmsnorm", "prism_op_gemm", "prism_op_qkv_finish",
            "prism_op_attention", "prism_op_score", "prism_op_route", "prism_op_compact", "prism_op_topk"]
 
 
@@ -51,7 +51,7 @@ class prism_weights(C.Structure):
 class prism_options(C.Structure):
     _fields_ = [("checkpoint_layers", C.POINTER(C.c_int32)), ("n_checkpoints", C.c_int32), ("cv_threshold", C.c_float),
                 ("n_clusters", C.c_int32), ("mode", C.c_int32), ("chunk_cands", C.c_int32), ("hbm_cap_bytes", C.c_int64),
-                ("stream", C.c_void_p)]
+                ("stream", C.c_void_p), ("operand", C.c_int32)]
 
 
 class prism_report(C.Structure):
@@ -90,8 +90,8 @@ def lib() -> C.CDLL:
         _lib.prism_op_embed.argtypes = [vp, i32, vp, i32, i32, vp, vp]
         _lib.prism_op_rmsnorm.argtypes = [vp, vp, i32, i32, f32, i32, vp, vp]
         _lib.prism_op_gemm.argtypes = [i32, i32, vp, vp, vp, i32, i32, i32, vp]
-        _lib.prism_op_qknorm_rope.argtypes = [i32, vp, vp, i32, vp, vp, i32, i32, i32, i32, f32, f32, i32, vp]
-        _lib.prism_op_attention.argtypes = [i32, vp, C.POINTER(i32), i32, i32, i32, i32, vp, vp]
+        _lib.prism_op_qkv_finish.argtypes = [i32, vp, vp, i32, vp, vp, i32, i32, i32, i32, f32, f32, i32, vp, vp, vp, C.c_int64, vp]
+        _lib.prism_op_attention.argtypes = [i32, vp, vp, C.c_int64, C.POINTER(i32), C.POINTER(i32), i32, i32, i32, i32, vp, vp]
         _lib.prism_op_score.argtypes = [vp, vp, i32, i32, vp, vp, vp, i32, f32, vp, vp]
         _lib.prism_op_route.argtypes = [vp, i32, i32, i32, f32, vp, vp, vp]
         _lib.prism_op_compact.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp]
@@ -148,9 +148,10 @@ class Prism:
 
     def __init__(self, model, weights, *, checkpoints: Sequence[int] = (), cv_threshold: float = 0.0, n_clusters: int = 3,
                  mode: int = MODE_DROP_ONLY, chunk_cands: int = 0, hbm_cap_bytes: int = 0, stream_weights: bool = False,
-                 stream: Optional[int] = None):
+                 stream: Optional[int] = None, operand: str = "f16"):
         """model: object with n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, rms_eps, rope_base,
-        qk_norm, dtype ("fp32" | "bf16").  weights: object with embed, final_norm, w_yes, w_no (device tensors) and
+        qk_norm, dtype ("fp32" | "bf16": storage type of the weights).  operand ("f16" | "bf16"): 16-bit type of the
+        matrix-core operands when the weights are bf16.  weights: object with embed, final_norm, w_yes, w_no (device tensors) and
         layers: list of dicts of tensors (device, or pinned host when stream_weights)."""
         self._ctx = C.c_void_p()
         m = prism_model(model.n_layers, model.hidden, model.n_q_heads, model.n_kv_heads, model.head_dim, model.ffn,
@@ -165,7 +166,7 @@ class Prism:
                           1 if stream_weights else 0)
         ck, ckp = _i32_array(list(checkpoints))
         o = prism_options(ckp, len(ck), cv_threshold, n_clusters, mode, chunk_cands, hbm_cap_bytes,
-                          _stream() if stream is None else stream)
+                          _stream() if stream is None else stream, DTYPE_BF16 if operand == "bf16" else DTYPE_F16)
         self.n_checkpoints = len(ck)
         _check(lib().prism_create(C.byref(m), C.byref(w), C.byref(o), C.byref(self._ctx)))
 
@@ -228,7 +229,7 @@ class Prism:
 
 def _dt(t) -> int:
     import torch
-    return DTYPE_FP32 if t.dtype == torch.float32 else DTYPE_BF16
+    return {torch.float32: DTYPE_FP32, torch.bfloat16: DTYPE_BF16, torch.float16: DTYPE_F16}[t.dtype]
 
 
 def op_embed(tokens, table, X):
@@ -243,14 +244,18 @@ def op_gemm(epilogue, A, W, out):
     _check(lib().prism_op_gemm(_dt(A), epilogue, _ptr(A), _ptr(W), _ptr(out), A.shape[0], W.shape[0], A.shape[1], _stream()))
 
 
-def op_qknorm_rope(QKV, pos, max_pos, q_gain, k_gain, nq, nkv, hd, eps, base, qk_norm):
-    _check(lib().prism_op_qknorm_rope(_dt(QKV), _ptr(QKV), _ptr(pos), max_pos, _ptr(q_gain), _ptr(k_gain), QKV.shape[0],
-                                      nq, nkv, hd, eps, base, int(qk_norm), _stream()))
+def op_qkv_finish(dtype, QKV, pos, max_pos, q_gain, k_gain, nq, nkv, hd, eps, base, qk_norm, QK=None, Vt=None,
+                  vt_col=None, vt_stride=0):
+    _check(lib().prism_op_qkv_finish(dtype, _ptr(QKV), _ptr(pos), max_pos, _ptr(q_gain), _ptr(k_gain), QKV.shape[0],
+                                     nq, nkv, hd, eps, base, int(qk_norm), _ptr(QK), _ptr(Vt), _ptr(vt_col), vt_stride,
+                                     _stream()))
 
 
-def op_attention(QKV, cu_seqlens, nq, nkv, hd, out):
+def op_attention(dtype, QK, Vt, vt_stride, cu_seqlens, vt_col0, nq, nkv, hd, out):
     cu, cup = _i32_array(cu_seqlens)
-    _check(lib().prism_op_attention(_dt(QKV), _ptr(QKV), cup, len(cu) - 1, nq, nkv, hd, _ptr(out), _stream()))
+    c0, c0p = _i32_array(vt_col0 if vt_col0 is not None else np.zeros(len(cu) - 1))
+    _check(lib().prism_op_attention(dtype, _ptr(QK), _ptr(Vt), vt_stride, cup, c0p, len(cu) - 1, nq, nkv, hd, _ptr(out),
+                                    _stream()))
 
 
 def op_score(X, last_row, final_norm, w_yes, w_no, eps, scores):

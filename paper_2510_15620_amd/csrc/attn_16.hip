@@ -1,4 +1,4 @@
-// Causal GQA attention on the gfx950 matrix cores, varlen-packed: no token attends across
+// Causal GQA attention on the gfx950 matrix cores (16-bit operands), varlen-packed: no token attends across
 // sequences (paper Sec. 2.2) and the work list is rebuilt whenever pruning shrinks the batch.
 //
 // A work item is (one sequence, one block of queries, one KV head).  The workgroup has 8
@@ -8,13 +8,16 @@
 // Everything is computed transposed so that a lane owns ONE query:
 //   S^T[key, query] = K Q^T      (A operand = K tile rows from LDS, B operand = Q from registers)
 //   O^T[d, query]  += V^T P^T    (A operand = V^T tile from LDS,   B operand = P^T = the S^T
-//                                 accumulator registers themselves, converted to bf16)
+//                                 accumulator registers themselves, converted to f16)
 // The 32x32 accumulator layout gives lane l the column l % 32 and rows (e/4)*8 + (l/32)*4 + e%4;
 // those rows, read as the 16 contraction slots of the next MFMA, are keys {0-3, 8-11} for the low
 // half-wave and {4-7, 12-15} for the high one, so the V^T operand is fetched in that key order.
 // Online softmax needs one cross-lane exchange (l <-> l ^ 32) per K/V tile.
-// V^T comes from the [kv head][d][column] buffer written by the V transposition step; a sequence's
-// columns start at a multiple of 64 so every 16-byte chunk is aligned.
+// q and k come from the finished [T, (nq + nkv) * hd] buffer in the operand type OT (bf16 or IEEE half).
+// V^T comes from the [kv head][d][column] buffer of the V finishing step, always IEEE half: the
+// second contraction runs on the f16 MFMA in both modes so that the probabilities keep 11
+// significand bits.  A sequence's columns
+// start at a multiple of 64 so every 16-byte chunk is aligned.
 #include "common.h"
 
 namespace prism {
@@ -22,20 +25,22 @@ namespace prism {
 static constexpr int HD = 128;           // head_dim served by this kernel
 static constexpr int BKV = 64;           // keys per staged tile
 
-template <int G>
-__global__ __launch_bounds__(512) void attention_bf16_kernel(const bf16 *__restrict__ QKV, const bf16 *__restrict__ Vt,
-                                                             int64_t vt_stride, const AttnTile *__restrict__ tiles,
-                                                             int nq, int nkv, bf16 *__restrict__ out) {
+template <typename OT, int G>
+__global__ __launch_bounds__(512) void attention_16_kernel(const OT *__restrict__ QK, const f16 *__restrict__ Vt,
+                                                           int64_t vt_stride, const AttnTile *__restrict__ tiles,
+                                                           int nq, int nkv, OT *__restrict__ out) {
+  typedef typename Mfma<OT>::vec8 vec8;
+  typedef typename Mfma<OT>::vec4 vec4;
   constexpr int QB = 8 / G;              // 32-query blocks per item
   constexpr int BQ = 32 * QB;
-  __shared__ __align__(16) bf16 lK[2][BKV * HD];     // [key][d], 16 chunks per row, swizzled
-  __shared__ __align__(16) bf16 lV[2][HD * BKV];     // [d][key], 8 chunks per row, swizzled
+  __shared__ __align__(16) OT lK[2][BKV * HD];       // [key][d], 16 chunks per row, swizzled
+  __shared__ __align__(16) f16 lV[2][HD * BKV];      // [d][key], 8 chunks per row, swizzled
 
   const AttnTile it = tiles[blockIdx.x];
   const int kvh = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int hq = kvh * G + wave % G, qb = wave / G;
-  const int row_elems = (nq + 2 * nkv) * HD;
+  const int row_elems = (nq + nkv) * HD;
   const int L = it.seq_len;
   const int q_lo = it.q0 + qb * 32;                               // first query of this wave
   const int q_last_blk = (it.q0 + BQ < L ? it.q0 + BQ : L) - 1;   // last valid query of the item
@@ -44,41 +49,42 @@ __global__ __launch_bounds__(512) void attention_bf16_kernel(const bf16 *__restr
   // ---- Q fragments: B operand, lane -> query (lane % 32), d = kk*16 + (lane/32)*8 .. +8
   int qi = q_lo + (lane & 31);
   const int qi_ld = qi < L ? qi : L - 1;
-  bf16x8 qf[HD / 16];
+  vec8 qf[HD / 16];
   {
-    const bf16 *qp = QKV + (int64_t)(it.seq_row0 + qi_ld) * row_elems + (int64_t)hq * HD + (lane >> 5) * 8;
+    const OT *qp = QK + (int64_t)(it.seq_row0 + qi_ld) * row_elems + (int64_t)hq * HD + (lane >> 5) * 8;
 #pragma unroll
-    for (int kk = 0; kk < HD / 16; ++kk) qf[kk] = *reinterpret_cast<const bf16x8 *>(qp + kk * 16);
+    for (int kk = 0; kk < HD / 16; ++kk) qf[kk] = *reinterpret_cast<const vec8 *>(qp + kk * 16);
   }
 
   // ---- staging addresses: 1024 chunks of K and 1024 of V^T per tile, 2 + 2 per thread
-  const bf16 *gK[2], *gV[2];
+  const OT *gK[2];
+  const f16 *gV[2];
   int sK[2], sV[2], krow[2];
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int c = tid + i * 512;
     const int kr = c / 16, kc = c % 16;                            // K: key row, chunk
     krow[i] = kr;
-    gK[i] = QKV + (int64_t)(nq + kvh) * HD + kc * 8;               // + (seq_row0 + key) * row_elems later
+    gK[i] = QK + (int64_t)(nq + kvh) * HD + kc * 8;               // + (seq_row0 + key) * row_elems later
     sK[i] = kr * HD + ((kc ^ (kr & 15)) * 8);
     const int vr = c / 8, vc = c % 8;                              // V^T: d row, chunk of 8 keys
     gV[i] = Vt + ((int64_t)kvh * HD + vr) * vt_stride + it.vt_col0 + vc * 8;
     sV[i] = vr * BKV + ((vc ^ (vr & 7)) * 8);
   }
-  auto load_tile = [&](int kt, bf16x8 (&rk)[2], bf16x8 (&rv)[2]) {
+  auto load_tile = [&](int kt, vec8 (&rk)[2], f16x8 (&rv)[2]) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       int key = kt * BKV + krow[i];
       key = key < L ? key : L - 1;
-      rk[i] = *reinterpret_cast<const bf16x8 *>(gK[i] + (int64_t)(it.seq_row0 + key) * row_elems);
-      rv[i] = *reinterpret_cast<const bf16x8 *>(gV[i] + kt * BKV);
+      rk[i] = *reinterpret_cast<const vec8 *>(gK[i] + (int64_t)(it.seq_row0 + key) * row_elems);
+      rv[i] = *reinterpret_cast<const f16x8 *>(gV[i] + kt * BKV);
     }
   };
-  auto store_tile = [&](int buf, const bf16x8 (&rk)[2], const bf16x8 (&rv)[2]) {
+  auto store_tile = [&](int buf, const vec8 (&rk)[2], const f16x8 (&rv)[2]) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      *reinterpret_cast<bf16x8 *>(&lK[buf][sK[i]]) = rk[i];
-      *reinterpret_cast<bf16x8 *>(&lV[buf][sV[i]]) = rv[i];
+      *reinterpret_cast<vec8 *>(&lK[buf][sK[i]]) = rk[i];
+      *reinterpret_cast<f16x8 *>(&lV[buf][sV[i]]) = rv[i];
     }
   };
 
@@ -90,7 +96,8 @@ __global__ __launch_bounds__(512) void attention_bf16_kernel(const bf16 *__restr
   float m_run = -INFINITY, l_run = 0.f;
   const float c_exp = 1.4426950408889634f / sqrtf((float)HD);      // log2(e) / sqrt(hd)
 
-  bf16x8 rk[2], rv[2];
+  vec8 rk[2];
+  f16x8 rv[2];
   load_tile(0, rk, rv);
   store_tile(0, rk, rv);
   __syncthreads();
@@ -112,8 +119,8 @@ __global__ __launch_bounds__(512) void attention_bf16_kernel(const bf16 *__restr
 #pragma unroll
         for (int kk = 0; kk < HD / 16; ++kk) {
           const int ch = kk * 2 + (lane >> 5);
-          const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(&lK[cur][r * HD + ((ch ^ (r & 15)) * 8)]);
-          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[kb], 0, 0, 0);
+          const vec8 kf = *reinterpret_cast<const vec8 *>(&lK[cur][r * HD + ((ch ^ (r & 15)) * 8)]);
+          s[kb] = Mfma<OT>::mma(kf, qf[kk], s[kb]);
         }
       }
       // ---- causal mask + online softmax (lane owns query qi; partner lane ^ 32 owns the other keys)
@@ -134,14 +141,14 @@ __global__ __launch_bounds__(512) void attention_bf16_kernel(const bf16 *__restr
       const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c_exp);
       const float mb = m_new * c_exp;
       float psum = 0.f;
-      bf16x8 pf[4];                                   // P^T as B operands: 4 contraction steps of 16 keys
+      f16x8 pf[4];                                    // P^T as B operands: 4 contraction steps of 16 keys
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
           const float p = __builtin_amdgcn_exp2f(s[kb][e] * c_exp - mb);
           psum += p;
-          pf[kb * 2 + (e >> 3)][e & 7] = (bf16)p;
+          pf[kb * 2 + (e >> 3)][e & 7] = (f16)p;      // p <= 1: no overflow
         }
       l_run = l_run * alpha + psum;
       m_run = m_new;
@@ -157,12 +164,12 @@ __global__ __launch_bounds__(512) void attention_bf16_kernel(const bf16 *__restr
         for (int ks = 0; ks < 4; ++ks) {
           // contraction slots 0-3 <- keys ks*16 + (lane/32)*4 .. +4 ; slots 4-7 <- the same + 8
           const int c0 = ks * 2, c1 = ks * 2 + 1, half = (lane >> 5) * 4;
-          const bf16x4 v0 = *reinterpret_cast<const bf16x4 *>(&lV[cur][r * BKV + ((c0 ^ (r & 7)) * 8) + half]);
-          const bf16x4 v1 = *reinterpret_cast<const bf16x4 *>(&lV[cur][r * BKV + ((c1 ^ (r & 7)) * 8) + half]);
-          bf16x8 vf;
+          const f16x4 v0 = *reinterpret_cast<const f16x4 *>(&lV[cur][r * BKV + ((c0 ^ (r & 7)) * 8) + half]);
+          const f16x4 v1 = *reinterpret_cast<const f16x4 *>(&lV[cur][r * BKV + ((c1 ^ (r & 7)) * 8) + half]);
+          f16x8 vf;
           vf[0] = v0[0]; vf[1] = v0[1]; vf[2] = v0[2]; vf[3] = v0[3];
           vf[4] = v1[0]; vf[5] = v1[1]; vf[6] = v1[2]; vf[7] = v1[3];
-          o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ks], o[t], 0, 0, 0);
+          o[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf[ks], o[t], 0, 0, 0);
         }
       }
     }
@@ -174,41 +181,48 @@ __global__ __launch_bounds__(512) void attention_bf16_kernel(const bf16 *__restr
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   if (qi < L) {
     const float inv = 1.0f / l_tot;
-    bf16 *op = out + (int64_t)(it.seq_row0 + qi) * nq * HD + (int64_t)hq * HD + (lane >> 5) * 4;
+    OT *op = out + (int64_t)(it.seq_row0 + qi) * nq * HD + (int64_t)hq * HD + (lane >> 5) * 4;
 #pragma unroll
     for (int t = 0; t < HD / 32; ++t)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        bf16x4 v;
+        vec4 v;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = (bf16)(o[t][g * 4 + j] * inv);
-        *reinterpret_cast<bf16x4 *>(op + t * 32 + g * 8) = v;
+        for (int j = 0; j < 4; ++j) v[j] = from_f32<OT>(o[t][g * 4 + j] * inv);
+        *reinterpret_cast<vec4 *>(op + t * 32 + g * 8) = v;
       }
   }
 }
 
-bool attention_bf16_supported(int nq, int nkv, int hd) {
+bool attention_16_supported(int nq, int nkv, int hd) {
   if (hd != HD || nkv <= 0 || nq % nkv != 0) return false;
   const int g = nq / nkv;
   return g == 1 || g == 2 || g == 4 || g == 8;
 }
 
-int attention_bf16_block_queries(int nq, int nkv) { return 32 * (8 / (nq / nkv)); }
+template <typename OT>
+static void launch_typed(dim3 grid, int g, const OT *QK, const f16 *Vt, int64_t vt_stride, const AttnTile *tiles, int nq,
+                         int nkv, OT *out, hipStream_t s) {
+  switch (g) {
+    case 1: attention_16_kernel<OT, 1><<<grid, 512, 0, s>>>(QK, Vt, vt_stride, tiles, nq, nkv, out); break;
+    case 2: attention_16_kernel<OT, 2><<<grid, 512, 0, s>>>(QK, Vt, vt_stride, tiles, nq, nkv, out); break;
+    case 4: attention_16_kernel<OT, 4><<<grid, 512, 0, s>>>(QK, Vt, vt_stride, tiles, nq, nkv, out); break;
+    default: attention_16_kernel<OT, 8><<<grid, 512, 0, s>>>(QK, Vt, vt_stride, tiles, nq, nkv, out); break;
+  }
+}
 
-int launch_attention_bf16(const bf16 *QKV, const bf16 *Vt, int64_t vt_stride, const AttnTile *tiles, int n_tiles,
-                          int T, int nq, int nkv, int hd, bf16 *out, hipStream_t s) {
-  PRISM_REQUIRE(QKV && Vt && tiles && out && n_tiles >= 0 && T >= 0, PRISM_EINVAL, "attention bf16: bad arguments");
-  PRISM_REQUIRE(attention_bf16_supported(nq, nkv, hd), PRISM_EUNSUPPORTED,
-                "attention bf16: needs head_dim 128 and 1, 2, 4 or 8 query heads per KV head (got hd %d, %d/%d)", hd, nq, nkv);
-  PRISM_REQUIRE(vt_stride % 8 == 0, PRISM_EINVAL, "attention bf16: V^T row stride must be a multiple of 8");
+int launch_attention_16(int dtype, const void *QK, const void *Vt, int64_t vt_stride, const AttnTile *tiles, int n_tiles,
+                        int T, int nq, int nkv, int hd, void *out, hipStream_t s) {
+  PRISM_REQUIRE(QK && Vt && tiles && out && n_tiles >= 0 && T >= 0 && is16(dtype), PRISM_EINVAL, "attention: bad arguments");
+  PRISM_REQUIRE(attention_16_supported(nq, nkv, hd), PRISM_EUNSUPPORTED,
+                "attention: 16-bit modes need head_dim 128 and 1, 2, 4 or 8 query heads per KV head (got hd %d, %d/%d)", hd, nq, nkv);
+  PRISM_REQUIRE(vt_stride % 8 == 0, PRISM_EINVAL, "attention: V^T row stride must be a multiple of 8");
   if (n_tiles == 0) return PRISM_OK;
   dim3 grid(n_tiles, nkv);
-  switch (nq / nkv) {
-    case 1: attention_bf16_kernel<1><<<grid, 512, 0, s>>>(QKV, Vt, vt_stride, tiles, nq, nkv, out); break;
-    case 2: attention_bf16_kernel<2><<<grid, 512, 0, s>>>(QKV, Vt, vt_stride, tiles, nq, nkv, out); break;
-    case 4: attention_bf16_kernel<4><<<grid, 512, 0, s>>>(QKV, Vt, vt_stride, tiles, nq, nkv, out); break;
-    default: attention_bf16_kernel<8><<<grid, 512, 0, s>>>(QKV, Vt, vt_stride, tiles, nq, nkv, out); break;
-  }
+  if (dtype == PRISM_DTYPE_BF16)
+    launch_typed<bf16>(grid, nq / nkv, (const bf16 *)QK, (const f16 *)Vt, vt_stride, tiles, nq, nkv, (bf16 *)out, s);
+  else
+    launch_typed<f16>(grid, nq / nkv, (const f16 *)QK, (const f16 *)Vt, vt_stride, tiles, nq, nkv, (f16 *)out, s);
   PRISM_HIP(hipGetLastError());
   return PRISM_OK;
 }

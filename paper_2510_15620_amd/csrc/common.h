@@ -34,14 +34,34 @@ typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef _Float16 f16;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
 
 __device__ __forceinline__ float to_f32(float v) { return v; }
 __device__ __forceinline__ float to_f32(bf16 v) { return (float)v; }
 template <typename T> __device__ __forceinline__ T from_f32(float v);
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }  // round-to-nearest-even
+__device__ __forceinline__ float to_f32(f16 v) { return (float)v; }
+// IEEE half, round-to-nearest-even, saturating at the largest finite half instead of overflowing to infinity
+template <> __device__ __forceinline__ f16 from_f32<f16>(float v) { return (f16)fminf(fmaxf(v, -65504.0f), 65504.0f); }
+
+// matrix-core instruction of a 16-bit operand type: D(32x32, fp32) += A(32x16) B(16x32)
+template <typename T> struct Mfma;
+template <> struct Mfma<bf16> {
+  typedef bf16x8 vec8;
+  typedef bf16x4 vec4;
+  static __device__ __forceinline__ f32x16 mma(vec8 a, vec8 b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
+};
+template <> struct Mfma<f16> {
+  typedef f16x8 vec8;
+  typedef f16x4 vec4;
+  static __device__ __forceinline__ f32x16 mma(vec8 a, vec8 b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
+};
 
 static inline size_t dtype_size(int dtype) { return dtype == PRISM_DTYPE_FP32 ? 4 : 2; }
+static inline bool is16(int dtype) { return dtype == PRISM_DTYPE_BF16 || dtype == PRISM_DTYPE_F16; }
 static inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 static inline int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
@@ -60,25 +80,29 @@ __device__ __forceinline__ float wave_max(float v) {
 int launch_embed(const int32_t *tokens, int T, const void *table, int hidden, int dtype, float *X, hipStream_t s);
 int launch_rmsnorm(const float *X, const void *gain, int T, int hidden, float eps, int dtype, void *out, hipStream_t s);
 int launch_gemm_fp32(int epilogue, const float *A, const float *W, void *out, int M, int N, int K, hipStream_t s);
-int launch_gemm_bf16(int epilogue, const bf16 *A, const bf16 *W, void *out, int M, int N, int K, hipStream_t s);
-bool gemm_bf16_supported(int epilogue, int N, int K);
+// 16-bit operands (dtype PRISM_DTYPE_BF16 or PRISM_DTYPE_F16) on the matrix cores
+int launch_gemm_16(int dtype, int epilogue, const void *A, const void *W, void *out, int M, int N, int K, hipStream_t s);
+bool gemm_16_supported(int epilogue, int N, int K);
 
 // cos/sin table for RoPE: tab[pos * (hd/2) + i] = (cos, sin)(pos * base^(-2i/hd)), evaluated in fp64
 int launch_rope_table(float2 *tab, int n_pos, int head_dim, float rope_base, hipStream_t s);
-int launch_qknorm_rope(int dtype, void *QKV, const int32_t *pos, const void *q_gain, const void *k_gain, int T,
-                       int nq, int nkv, int hd, float eps, int qk_norm, const float2 *rope_tab, hipStream_t s);
-int launch_v_transpose(const bf16 *QKV, int T, int nq, int nkv, int hd, bf16 *Vt, const int32_t *vt_col,
-                       int64_t vt_stride, hipStream_t s);
+// q/k per-head RMSNorm + RoPE from the fp32 projection.  fp32 mode: in place (QK == nullptr).  bf16 mode:
+// q,k -> QK [T, (nq+nkv)*hd] bf16.
+int launch_qk_finish(int dtype, float *QKV, const int32_t *pos, const void *q_gain, const void *k_gain, int T,
+                     int nq, int nkv, int hd, float eps, int qk_norm, const float2 *rope_tab, void *QK, hipStream_t s);
+// v part of the fp32 projection -> Vt [nkv][hd][vt_stride], IEEE half (in bf16-operand mode: bf16-rounded values)
+int launch_v_finish(int dtype, const float *QKV, int T, int nq, int nkv, int hd, void *Vt, const int32_t *vt_col,
+                    int64_t vt_stride, hipStream_t s);
 
 // generic fp32 attention: one workgroup per (token, q head); pos[t] = position of t in its sequence
 int launch_attention_fp32(const float *QKV, const int32_t *pos, int T, int nq, int nkv, int hd, float *out,
                           hipStream_t s);
-// MFMA attention (hd == 128).  tiles: per work item {first token row of the sequence, sequence length,
+// matrix-core attention (hd == 128).  tiles: per work item {first token row of the sequence, sequence length,
 // first query of the tile, column of the sequence's first key in Vt}; see attn_bf16.hip.
 struct AttnTile { int32_t seq_row0, seq_len, q0, vt_col0; };
-int launch_attention_bf16(const bf16 *QKV, const bf16 *Vt, int64_t vt_stride, const AttnTile *tiles, int n_tiles,
-                          int T, int nq, int nkv, int hd, bf16 *out, hipStream_t s);
-bool attention_bf16_supported(int nq, int nkv, int hd);
+int launch_attention_16(int dtype, const void *QK, const void *Vt, int64_t vt_stride, const AttnTile *tiles, int n_tiles,
+                        int T, int nq, int nkv, int hd, void *out, hipStream_t s);
+bool attention_16_supported(int nq, int nkv, int hd);
 static const int kAttnBQ = 64;   // query rows per attention work item
 
 int launch_score(const float *X, const int32_t *last_row, int n, int hidden, const void *final_norm,
@@ -93,5 +117,7 @@ int launch_topk(const float *scores, int n, int K, int32_t *out_pos, float *out_
 int launch_topk_masked(const float *scores, const int8_t *tag, int want, int n, int K, int32_t *out_pos,
                        float *out_scores, hipStream_t s);
 int launch_fill_zero(void *p, size_t bytes, hipStream_t s);
+// in place: n bf16 values -> the same values in IEEE half (exact for every bf16 value of normal half range)
+int launch_bf16_to_f16(void *p, size_t n, hipStream_t s);
 
 }  // namespace prism

@@ -1,5 +1,5 @@
 // Bandwidth- and latency-bound steps of the path: embedding gather, RMSNorm, q/k norm + RoPE,
-// V transposition, the intermediate scorer, compaction and the final top-K.
+// V rounding + transposition, the intermediate scorer, compaction and the final top-K.
 #include "common.h"
 
 namespace prism {
@@ -74,8 +74,10 @@ int launch_rmsnorm(const float *X, const void *gain, int T, int hidden, float ep
   if (T == 0) return PRISM_OK;
   if (dtype == PRISM_DTYPE_FP32)
     rmsnorm_kernel<float><<<T, 256, 0, s>>>(X, (const float *)gain, hidden, eps, (float *)out);
-  else
+  else if (dtype == PRISM_DTYPE_BF16)
     rmsnorm_kernel<bf16><<<T, 256, 0, s>>>(X, (const bf16 *)gain, hidden, eps, (bf16 *)out);
+  else
+    rmsnorm_kernel<f16><<<T, 256, 0, s>>>(X, (const f16 *)gain, hidden, eps, (f16 *)out);
   PRISM_HIP(hipGetLastError());
   return PRISM_OK;
 }
@@ -99,25 +101,28 @@ int launch_rope_table(float2 *tab, int n_pos, int head_dim, float rope_base, hip
   return PRISM_OK;
 }
 
-// Per-head RMSNorm (optional) then rotate-half RoPE on q and k, in place in the fused projection
+// Per-head RMSNorm (optional) then rotate-half RoPE on the q and k parts of the fp32 projection
 // QKV [T, (nq + 2 nkv) * hd].  One wavefront per (token, head); lane i owns pairs (i, i + hd/2),
-// (i + 64, i + 64 + hd/2), ...   HBM-bound: reads and writes the q and k columns once.
+// (i + 64, i + 64 + hd/2), ...  The result is rounded ONCE, to the operand type of the QK^T
+// contraction: fp32 mode rewrites QKV in place, bf16 mode writes QK [T, (nq + nkv) * hd].
 template <typename T>
-__global__ __launch_bounds__(256) void qknorm_rope_kernel(T *__restrict__ QKV, const int32_t *__restrict__ pos,
-                                                          const T *__restrict__ q_gain, const T *__restrict__ k_gain,
-                                                          int n_tok, int nq, int nkv, int hd, float eps, int qk_norm,
-                                                          const float2 *__restrict__ rope_tab) {
+__global__ __launch_bounds__(256) void qk_finish_kernel(float *__restrict__ QKV, const int32_t *__restrict__ pos,
+                                                        const T *__restrict__ q_gain, const T *__restrict__ k_gain,
+                                                        int n_tok, int nq, int nkv, int hd, float eps, int qk_norm,
+                                                        const float2 *__restrict__ rope_tab, T *__restrict__ out,
+                                                        int out_row) {
   const int heads = nq + nkv;
   const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (item >= (int64_t)n_tok * heads) return;
   const int t = (int)(item / heads), h = (int)(item % heads);
   const int lane = threadIdx.x & 63, half = hd / 2;
-  T *x = QKV + (int64_t)t * (nq + 2 * nkv) * hd + (int64_t)h * hd;
+  const float *x = QKV + (int64_t)t * (nq + 2 * nkv) * hd + (int64_t)h * hd;
+  T *o = out + (int64_t)t * out_row + (int64_t)h * hd;
   const T *g = h < nq ? q_gain : k_gain;
   const float2 *tab = rope_tab + (int64_t)pos[t] * half;
   float ss = 0.f;
   for (int i = lane; i < half; i += 64) {
-    const float a = to_f32(x[i]), b = to_f32(x[i + half]);
+    const float a = x[i], b = x[i + half];
     ss += a * a + b * b;
   }
   float r = 1.f;
@@ -126,47 +131,55 @@ __global__ __launch_bounds__(256) void qknorm_rope_kernel(T *__restrict__ QKV, c
     r = 1.0f / sqrtf(ss / (float)hd + eps);
   }
   for (int i = lane; i < half; i += 64) {
-    float a = to_f32(x[i]), b = to_f32(x[i + half]);
+    float a = x[i], b = x[i + half];
     if (qk_norm) {
       a = a * r * to_f32(g[i]);
       b = b * r * to_f32(g[i + half]);
     }
     const float2 cs = tab[i];
-    x[i] = from_f32<T>(a * cs.x - b * cs.y);
-    x[i + half] = from_f32<T>(b * cs.x + a * cs.y);
+    o[i] = from_f32<T>(a * cs.x - b * cs.y);
+    o[i + half] = from_f32<T>(b * cs.x + a * cs.y);
   }
 }
 
-int launch_qknorm_rope(int dtype, void *QKV, const int32_t *pos, const void *q_gain, const void *k_gain, int T,
-                       int nq, int nkv, int hd, float eps, int qk_norm, const float2 *rope_tab, hipStream_t s) {
+int launch_qk_finish(int dtype, float *QKV, const int32_t *pos, const void *q_gain, const void *k_gain, int T,
+                     int nq, int nkv, int hd, float eps, int qk_norm, const float2 *rope_tab, void *QK, hipStream_t s) {
   PRISM_REQUIRE(QKV && pos && rope_tab && T >= 0 && nq > 0 && nkv > 0 && hd > 0 && hd % 2 == 0, PRISM_EINVAL,
-                "qknorm_rope: bad arguments");
-  PRISM_REQUIRE(!qk_norm || (q_gain && k_gain), PRISM_EINVAL, "qknorm_rope: gains missing");
+                "qk_finish: bad arguments");
+  PRISM_REQUIRE(!qk_norm || (q_gain && k_gain), PRISM_EINVAL, "qk_finish: gains missing");
+  PRISM_REQUIRE(dtype == PRISM_DTYPE_FP32 || QK, PRISM_EINVAL, "qk_finish: 16-bit modes need the QK output");
   if (T == 0) return PRISM_OK;
   const int64_t items = (int64_t)T * (nq + nkv);
   const int grid = cdiv(items, 4);
   if (dtype == PRISM_DTYPE_FP32)
-    qknorm_rope_kernel<float><<<grid, 256, 0, s>>>((float *)QKV, pos, (const float *)q_gain, (const float *)k_gain, T,
-                                                    nq, nkv, hd, eps, qk_norm, rope_tab);
+    qk_finish_kernel<float><<<grid, 256, 0, s>>>(QKV, pos, (const float *)q_gain, (const float *)k_gain, T, nq, nkv, hd,
+                                                  eps, qk_norm, rope_tab, QKV, (nq + 2 * nkv) * hd);
+  else if (dtype == PRISM_DTYPE_BF16)
+    qk_finish_kernel<bf16><<<grid, 256, 0, s>>>(QKV, pos, (const bf16 *)q_gain, (const bf16 *)k_gain, T, nq, nkv, hd,
+                                                 eps, qk_norm, rope_tab, (bf16 *)QK, (nq + nkv) * hd);
   else
-    qknorm_rope_kernel<bf16><<<grid, 256, 0, s>>>((bf16 *)QKV, pos, (const bf16 *)q_gain, (const bf16 *)k_gain, T, nq,
-                                                   nkv, hd, eps, qk_norm, rope_tab);
+    qk_finish_kernel<f16><<<grid, 256, 0, s>>>(QKV, pos, (const f16 *)q_gain, (const f16 *)k_gain, T, nq, nkv, hd,
+                                                eps, qk_norm, rope_tab, (f16 *)QK, (nq + nkv) * hd);
   PRISM_HIP(hipGetLastError());
   return PRISM_OK;
 }
 
-// V part of QKV [T, ...] -> Vt [nkv][hd][vt_stride], column vt_col[t]: the PV contraction runs over
-// keys, so the MFMA operand wants keys contiguous.  Tile of 64 tokens x hd through LDS.
-__global__ __launch_bounds__(256) void v_transpose_kernel(const bf16 *__restrict__ QKV, int n_tok, int nq, int nkv,
-                                                          int hd, bf16 *__restrict__ Vt,
-                                                          const int32_t *__restrict__ vt_col, int64_t vt_stride) {
-  __shared__ bf16 tile[64][128 + 2];
+// V part of the fp32 projection -> Vt [nkv][hd][vt_stride], column vt_col[t]: the P V contraction runs
+// over keys, so the MFMA operand wants keys contiguous.  P V always runs on the f16 matrix-core
+// instruction (the probabilities keep 11 significand bits), so Vt is IEEE half; in bf16-operand mode
+// the values are rounded to bf16 first (half holds every bf16 value of normal half range exactly).
+// Tile of 64 tokens x hd through LDS.
+template <typename OT>
+__global__ __launch_bounds__(256) void v_finish_kernel(const float *__restrict__ QKV, int n_tok, int nq, int nkv, int hd,
+                                                       f16 *__restrict__ Vt, const int32_t *__restrict__ vt_col,
+                                                       int64_t vt_stride) {
+  __shared__ f16 tile[64][128 + 2];
   const int t0 = blockIdx.x * 64, h = blockIdx.y;
   const int row_elems = (nq + 2 * nkv) * hd;
-  const bf16 *src = QKV + (int64_t)(nq + nkv + h) * hd;
+  const float *src = QKV + (int64_t)(nq + nkv + h) * hd;
   for (int idx = threadIdx.x; idx < 64 * hd; idx += 256) {
     const int r = idx / hd, d = idx % hd;
-    if (t0 + r < n_tok) tile[r][d] = src[(int64_t)(t0 + r) * row_elems + d];
+    if (t0 + r < n_tok) tile[r][d] = from_f32<f16>(to_f32(from_f32<OT>(src[(int64_t)(t0 + r) * row_elems + d])));
   }
   __syncthreads();
   for (int idx = threadIdx.x; idx < 64 * hd; idx += 256) {
@@ -175,11 +188,14 @@ __global__ __launch_bounds__(256) void v_transpose_kernel(const bf16 *__restrict
   }
 }
 
-int launch_v_transpose(const bf16 *QKV, int T, int nq, int nkv, int hd, bf16 *Vt, const int32_t *vt_col,
-                       int64_t vt_stride, hipStream_t s) {
-  PRISM_REQUIRE(QKV && Vt && vt_col && T >= 0 && hd > 0 && hd <= 128, PRISM_EINVAL, "v_transpose: bad arguments");
+int launch_v_finish(int dtype, const float *QKV, int T, int nq, int nkv, int hd, void *Vt, const int32_t *vt_col,
+                    int64_t vt_stride, hipStream_t s) {
+  PRISM_REQUIRE(QKV && Vt && vt_col && T >= 0 && hd > 0 && hd <= 128 && is16(dtype), PRISM_EINVAL, "v_finish: bad arguments");
   if (T == 0) return PRISM_OK;
-  v_transpose_kernel<<<dim3(cdiv(T, 64), nkv), 256, 0, s>>>(QKV, T, nq, nkv, hd, Vt, vt_col, vt_stride);
+  if (dtype == PRISM_DTYPE_BF16)
+    v_finish_kernel<bf16><<<dim3(cdiv(T, 64), nkv), 256, 0, s>>>(QKV, T, nq, nkv, hd, (f16 *)Vt, vt_col, vt_stride);
+  else
+    v_finish_kernel<f16><<<dim3(cdiv(T, 64), nkv), 256, 0, s>>>(QKV, T, nq, nkv, hd, (f16 *)Vt, vt_col, vt_stride);
   PRISM_HIP(hipGetLastError());
   return PRISM_OK;
 }
@@ -289,6 +305,25 @@ __global__ void fill_zero_kernel(uint4 *p, size_t n16) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   for (; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
+}
+
+__global__ void bf16_to_f16_kernel(unsigned short *p, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) {
+    const float v = __uint_as_float((unsigned)p[i] << 16);
+    const f16 h = from_f32<f16>(v);
+    p[i] = *reinterpret_cast<const unsigned short *>(&h);
+  }
+}
+
+int launch_bf16_to_f16(void *p, size_t n, hipStream_t s) {
+  PRISM_REQUIRE(p, PRISM_EINVAL, "bf16_to_f16: null pointer");
+  if (n == 0) return PRISM_OK;
+  const size_t blocks = (n + 255) / 256;
+  bf16_to_f16_kernel<<<(int)(blocks < 8192 ? blocks : 8192), 256, 0, s>>>((unsigned short *)p, n);
+  PRISM_HIP(hipGetLastError());
+  return PRISM_OK;
 }
 
 int launch_fill_zero(void *p, size_t bytes, hipStream_t s) {

@@ -1,15 +1,16 @@
-// bf16 layer contractions on the gfx950 matrix cores (paper Sec. 2.2: the reranker's latency is
+// 16-bit-operand layer contractions on the gfx950 matrix cores (paper Sec. 2.2: the reranker's latency is
 // dominated by the matrix multiplications of its transformer blocks).
 //
-// C = A W^T, A [M,K] and W [N,K] row-major bf16 (both K-contiguous, which is what the MFMA operand
-// registers want: 8 consecutive k per lane), fp32 accumulation in v_mfma_f32_32x32x16_bf16.
+// C = A W^T, A [M,K] and W [N,K] row-major, both bf16 or both IEEE half (K-contiguous, which is what
+// the MFMA operand registers want: 8 consecutive k per lane), fp32 accumulation in
+// v_mfma_f32_32x32x16_{bf16,f16} (same dense rate).
 //
 // Workgroup tile BM x BN x 64, WM x WN wavefronts, each owning a (BM/WM) x (BN/WN) block of 32x32
 // accumulator tiles.  A and W tiles are staged in LDS (double-buffered; 16-byte chunks XOR-swizzled
 // by row so that the 32-row operand reads spread over the banks).  The next K-slice is fetched into
 // registers while the current one feeds the MFMAs, one barrier per slice.
 //
-// Epilogues: plain store (bf16), residual add into the fp32 stream, and SwiGLU, where the B tile is
+// Epilogues: plain store (bf16 or fp32), residual add into the fp32 stream, and SwiGLU, where the B tile is
 // made of BN/2 gate rows and the BN/2 matching up rows so that a lane holds g and u of one element.
 //
 // Workgroup ids are remapped so that each XCD (ids are dealt round-robin over the 8 XCDs) owns a
@@ -23,9 +24,9 @@ static constexpr int kChunks = BK / 8;   // 16-byte chunks per tile row
 
 __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ (row & 7); }
 
-template <int BM, int BN, int WM, int WN, int EPI>
-__global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(const bf16 *__restrict__ A,
-                                                                 const bf16 *__restrict__ W, void *__restrict__ out_,
+template <typename OT, int BM, int BN, int WM, int WN, int EPI>
+__global__ __launch_bounds__(WM *WN * 64) void gemm_16_kernel(const OT *__restrict__ A,
+                                                               const OT *__restrict__ W, void *__restrict__ out_,
                                                                  int M, int N, int K, int nM, int nN) {
   constexpr int NT = WM * WN * 64;
   constexpr int WMT = BM / WM, WNT = BN / WN;      // wave tile
@@ -34,8 +35,9 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(const bf16 *__re
   static_assert(BM * kChunks % NT == 0 && BN * kChunks % NT == 0, "tile/threads mismatch");
   static_assert(EPI != PRISM_EPI_SWIGLU || TN % 2 == 0, "SwiGLU pairs gate and up tiles");
   extern __shared__ __align__(16) unsigned char smem[];
-  bf16 *lA = reinterpret_cast<bf16 *>(smem);                 // [2][BM][BK]
-  bf16 *lB = lA + 2 * BM * BK;                               // [2][BN][BK]
+  typedef typename Mfma<OT>::vec8 vec8;
+  OT *lA = reinterpret_cast<OT *>(smem);                 // [2][BM][BK]
+  OT *lB = lA + 2 * BM * BK;                               // [2][BN][BK]
 
   // ---- tile mapping: XCD-contiguous ranges, grouped walk ----
   const int n_tiles = nM * nN;
@@ -58,7 +60,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(const bf16 *__re
   const int wm = wave / WN, wn = wave % WN;
 
   // ---- global source pointers of this thread's 16-byte chunks ----
-  const bf16 *gA[A_ITERS], *gB[B_ITERS];
+  const OT *gA[A_ITERS], *gB[B_ITERS];
   int sA[A_ITERS], sB[B_ITERS];                              // LDS element offsets (within one stage)
 #pragma unroll
   for (int i = 0; i < A_ITERS; ++i) {
@@ -103,16 +105,16 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(const bf16 *__re
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  bf16x8 ra[A_ITERS], rb[B_ITERS];
+  vec8 ra[A_ITERS], rb[B_ITERS];
   const int nk = K / BK;
 #pragma unroll
-  for (int i = 0; i < A_ITERS; ++i) ra[i] = *reinterpret_cast<const bf16x8 *>(gA[i]);
+  for (int i = 0; i < A_ITERS; ++i) ra[i] = *reinterpret_cast<const vec8 *>(gA[i]);
 #pragma unroll
-  for (int i = 0; i < B_ITERS; ++i) rb[i] = *reinterpret_cast<const bf16x8 *>(gB[i]);
+  for (int i = 0; i < B_ITERS; ++i) rb[i] = *reinterpret_cast<const vec8 *>(gB[i]);
 #pragma unroll
-  for (int i = 0; i < A_ITERS; ++i) *reinterpret_cast<bf16x8 *>(lA + sA[i]) = ra[i];
+  for (int i = 0; i < A_ITERS; ++i) *reinterpret_cast<vec8 *>(lA + sA[i]) = ra[i];
 #pragma unroll
-  for (int i = 0; i < B_ITERS; ++i) *reinterpret_cast<bf16x8 *>(lB + sB[i]) = rb[i];
+  for (int i = 0; i < B_ITERS; ++i) *reinterpret_cast<vec8 *>(lB + sB[i]) = rb[i];
   __syncthreads();
 
   for (int kt = 0; kt < nk; ++kt) {
@@ -120,32 +122,32 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(const bf16 *__re
     const bool more = kt + 1 < nk;
     if (more) {
 #pragma unroll
-      for (int i = 0; i < A_ITERS; ++i) ra[i] = *reinterpret_cast<const bf16x8 *>(gA[i] + (int64_t)(kt + 1) * BK);
+      for (int i = 0; i < A_ITERS; ++i) ra[i] = *reinterpret_cast<const vec8 *>(gA[i] + (int64_t)(kt + 1) * BK);
 #pragma unroll
-      for (int i = 0; i < B_ITERS; ++i) rb[i] = *reinterpret_cast<const bf16x8 *>(gB[i] + (int64_t)(kt + 1) * BK);
+      for (int i = 0; i < B_ITERS; ++i) rb[i] = *reinterpret_cast<const vec8 *>(gB[i] + (int64_t)(kt + 1) * BK);
     }
-    const bf16 *cA = lA + cur * BM * BK, *cB = lB + cur * BN * BK;
+    const OT *cA = lA + cur * BM * BK, *cB = lB + cur * BN * BK;
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 af[TM], bfr[TN];
+      vec8 af[TM], bfr[TN];
 #pragma unroll
       for (int t = 0; t < TM; ++t)
-        af[t] = *reinterpret_cast<const bf16x8 *>(cA + rA[t] * BK + swz(rA[t], kk * 2 + khalf) * 8);
+        af[t] = *reinterpret_cast<const vec8 *>(cA + rA[t] * BK + swz(rA[t], kk * 2 + khalf) * 8);
 #pragma unroll
       for (int t = 0; t < TN; ++t)
-        bfr[t] = *reinterpret_cast<const bf16x8 *>(cB + rB[t] * BK + swz(rB[t], kk * 2 + khalf) * 8);
+        bfr[t] = *reinterpret_cast<const vec8 *>(cB + rB[t] * BK + swz(rB[t], kk * 2 + khalf) * 8);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = Mfma<OT>::mma(af[i], bfr[j], acc[i][j]);
     }
     if (more) {
-      bf16 *nA = lA + (cur ^ 1) * BM * BK, *nB = lB + (cur ^ 1) * BN * BK;
+      OT *nA = lA + (cur ^ 1) * BM * BK, *nB = lB + (cur ^ 1) * BN * BK;
 #pragma unroll
-      for (int i = 0; i < A_ITERS; ++i) *reinterpret_cast<bf16x8 *>(nA + sA[i]) = ra[i];
+      for (int i = 0; i < A_ITERS; ++i) *reinterpret_cast<vec8 *>(nA + sA[i]) = ra[i];
 #pragma unroll
-      for (int i = 0; i < B_ITERS; ++i) *reinterpret_cast<bf16x8 *>(nB + sB[i]) = rb[i];
+      for (int i = 0; i < B_ITERS; ++i) *reinterpret_cast<vec8 *>(nB + sB[i]) = rb[i];
     }
     __syncthreads();
   }
@@ -165,7 +167,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(const bf16 *__re
           const int col = n0 + wn * (WNT / 2) + j * 32 + col_in;
           if (col < F) {
             const float g = acc[i][j][e], u = acc[i][j + TN / 2][e];
-            reinterpret_cast<bf16 *>(out_)[(int64_t)row * F + col] = (bf16)(g / (1.0f + __expf(-g)) * u);
+            reinterpret_cast<OT *>(out_)[(int64_t)row * F + col] = from_f32<OT>(g / (1.0f + __expf(-g)) * u);
           }
         }
       } else {
@@ -174,7 +176,9 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(const bf16 *__re
           const int col = n0 + wn * WNT + j * 32 + col_in;
           if (col < N) {
             if (EPI == PRISM_EPI_STORE)
-              reinterpret_cast<bf16 *>(out_)[(int64_t)row * N + col] = (bf16)acc[i][j][e];
+              reinterpret_cast<OT *>(out_)[(int64_t)row * N + col] = from_f32<OT>(acc[i][j][e]);
+            else if (EPI == PRISM_EPI_STORE_F32)
+              reinterpret_cast<float *>(out_)[(int64_t)row * N + col] = acc[i][j][e];
             else
               reinterpret_cast<float *>(out_)[(int64_t)row * N + col] += acc[i][j][e];
           }
@@ -184,16 +188,16 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(const bf16 *__re
   }
 }
 
-bool gemm_bf16_supported(int epilogue, int N, int K) {
+bool gemm_16_supported(int epilogue, int N, int K) {
   if (K <= 0 || K % BK != 0 || N <= 0) return false;
   if (epilogue == PRISM_EPI_SWIGLU && N % 2 != 0) return false;
-  return epilogue >= PRISM_EPI_STORE && epilogue <= PRISM_EPI_SWIGLU;
+  return epilogue >= PRISM_EPI_STORE && epilogue <= PRISM_EPI_STORE_F32;
 }
 
-template <int BM, int BN, int WM, int WN, int EPI>
-static int launch_cfg(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, hipStream_t s) {
-  constexpr size_t lds = 2 * (size_t)(BM + BN) * BK * sizeof(bf16);
-  auto kern = gemm_bf16_kernel<BM, BN, WM, WN, EPI>;
+template <typename OT, int BM, int BN, int WM, int WN, int EPI>
+static int launch_cfg(const OT *A, const OT *W, void *out, int M, int N, int K, hipStream_t s) {
+  constexpr size_t lds = 2 * (size_t)(BM + BN) * BK * sizeof(OT);
+  auto kern = gemm_16_kernel<OT, BM, BN, WM, WN, EPI>;
   static bool attr_set = false;   // the attribute is per function; set it once per process
   if (!attr_set) {
     PRISM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -208,24 +212,31 @@ static int launch_cfg(const bf16 *A, const bf16 *W, void *out, int M, int N, int
   return PRISM_OK;
 }
 
-template <int EPI>
-static int launch_epi(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, hipStream_t s) {
+template <typename OT, int EPI>
+static int launch_epi(const OT *A, const OT *W, void *out, int M, int N, int K, hipStream_t s) {
   // big tile when there is enough work to fill 256 CUs with it, else a 128x128 tile
   const int64_t big_tiles = (int64_t)cdiv(M, 256) * cdiv(EPI == PRISM_EPI_SWIGLU ? N / 2 : N, EPI == PRISM_EPI_SWIGLU ? 128 : 256);
-  if (big_tiles >= 256) return launch_cfg<256, 256, 2, 4, EPI>(A, W, out, M, N, K, s);
-  return launch_cfg<128, 128, 2, 2, EPI>(A, W, out, M, N, K, s);
+  if (big_tiles >= 256) return launch_cfg<OT, 256, 256, 2, 4, EPI>(A, W, out, M, N, K, s);
+  return launch_cfg<OT, 128, 128, 2, 2, EPI>(A, W, out, M, N, K, s);
 }
 
-int launch_gemm_bf16(int epilogue, const bf16 *A, const bf16 *W, void *out, int M, int N, int K, hipStream_t s) {
-  PRISM_REQUIRE(A && W && out && M >= 0, PRISM_EINVAL, "gemm bf16: bad arguments");
-  PRISM_REQUIRE(gemm_bf16_supported(epilogue, N, K), PRISM_EUNSUPPORTED,
-                "gemm bf16: N = %d, K = %d, epilogue %d not supported (K must be a multiple of %d)", N, K, epilogue, BK);
-  if (M == 0) return PRISM_OK;
+template <typename OT>
+static int launch_typed(int epilogue, const OT *A, const OT *W, void *out, int M, int N, int K, hipStream_t s) {
   switch (epilogue) {
-    case PRISM_EPI_STORE: return launch_epi<PRISM_EPI_STORE>(A, W, out, M, N, K, s);
-    case PRISM_EPI_RESIDUAL: return launch_epi<PRISM_EPI_RESIDUAL>(A, W, out, M, N, K, s);
-    default: return launch_epi<PRISM_EPI_SWIGLU>(A, W, out, M, N, K, s);
+    case PRISM_EPI_STORE: return launch_epi<OT, PRISM_EPI_STORE>(A, W, out, M, N, K, s);
+    case PRISM_EPI_RESIDUAL: return launch_epi<OT, PRISM_EPI_RESIDUAL>(A, W, out, M, N, K, s);
+    case PRISM_EPI_STORE_F32: return launch_epi<OT, PRISM_EPI_STORE_F32>(A, W, out, M, N, K, s);
+    default: return launch_epi<OT, PRISM_EPI_SWIGLU>(A, W, out, M, N, K, s);
   }
+}
+
+int launch_gemm_16(int dtype, int epilogue, const void *A, const void *W, void *out, int M, int N, int K, hipStream_t s) {
+  PRISM_REQUIRE(A && W && out && M >= 0 && is16(dtype), PRISM_EINVAL, "gemm: bad arguments");
+  PRISM_REQUIRE(gemm_16_supported(epilogue, N, K), PRISM_EUNSUPPORTED,
+                "gemm: N = %d, K = %d, epilogue %d not supported (K must be a multiple of %d)", N, K, epilogue, BK);
+  if (M == 0) return PRISM_OK;
+  if (dtype == PRISM_DTYPE_BF16) return launch_typed<bf16>(epilogue, (const bf16 *)A, (const bf16 *)W, out, M, N, K, s);
+  return launch_typed<f16>(epilogue, (const f16 *)A, (const f16 *)W, out, M, N, K, s);
 }
 
 }  // namespace prism

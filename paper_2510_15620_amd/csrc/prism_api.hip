@@ -88,6 +88,7 @@ using namespace prism;
 struct prism_ctx {
   prism_model m;
   prism_options opt;
+  int op = PRISM_DTYPE_FP32;                      // operand type of the contractions: FP32, BF16 or F16
   std::vector<int32_t> checkpoints;
   LayerLayout lay;
   const void *embed = nullptr, *final_norm = nullptr, *w_yes = nullptr, *w_no = nullptr;
@@ -109,7 +110,7 @@ struct prism_ctx {
   // scratch, grown on demand
   float *X[2] = {nullptr, nullptr};
   int64_t x_cap[2] = {0, 0};                      // tokens
-  char *Xn = nullptr, *QKV = nullptr, *Vt = nullptr, *AO = nullptr, *S = nullptr;
+  char *Xn = nullptr, *QKV = nullptr, *QK = nullptr, *Vt = nullptr, *AO = nullptr, *S = nullptr;
   int64_t chunk_cap = 0, vt_cap = 0;              // tokens / V^T columns
   int32_t *d_meta = nullptr; int64_t meta_cap = 0;   // int32 words
   int32_t *h_meta = nullptr; int64_t h_meta_cap = 0; // pinned staging
@@ -163,12 +164,12 @@ static int validate_model(const prism_model *m) {
   PRISM_REQUIRE(m->rms_eps >= 0.f && m->rope_base > 0.f, PRISM_EINVAL, "model: rms_eps / rope_base out of range");
   if (m->dtype == PRISM_DTYPE_BF16) {
     const int Dq = m->n_q_heads * m->head_dim, Dkv = m->n_kv_heads * m->head_dim;
-    PRISM_REQUIRE(attention_bf16_supported(m->n_q_heads, m->n_kv_heads, m->head_dim), PRISM_EUNSUPPORTED,
+    PRISM_REQUIRE(attention_16_supported(m->n_q_heads, m->n_kv_heads, m->head_dim), PRISM_EUNSUPPORTED,
                   "bf16 mode needs head_dim 128 and 1, 2, 4 or 8 query heads per KV head");
-    PRISM_REQUIRE(gemm_bf16_supported(PRISM_EPI_STORE, Dq + 2 * Dkv, m->hidden) &&
-                      gemm_bf16_supported(PRISM_EPI_RESIDUAL, m->hidden, Dq) &&
-                      gemm_bf16_supported(PRISM_EPI_SWIGLU, 2 * m->ffn, m->hidden) &&
-                      gemm_bf16_supported(PRISM_EPI_RESIDUAL, m->hidden, m->ffn),
+    PRISM_REQUIRE(gemm_16_supported(PRISM_EPI_STORE, Dq + 2 * Dkv, m->hidden) &&
+                      gemm_16_supported(PRISM_EPI_RESIDUAL, m->hidden, Dq) &&
+                      gemm_16_supported(PRISM_EPI_SWIGLU, 2 * m->ffn, m->hidden) &&
+                      gemm_16_supported(PRISM_EPI_RESIDUAL, m->hidden, m->ffn),
                   PRISM_EUNSUPPORTED, "bf16 mode needs hidden, n_q_heads*head_dim and ffn to be multiples of 64");
     PRISM_REQUIRE(m->hidden % 8 == 0 && m->ffn % 8 == 0, PRISM_EUNSUPPORTED, "bf16 mode: rows must be 16-byte aligned");
   }
@@ -182,6 +183,8 @@ static int issue_layer_copy(prism_ctx *c, int layer, int slot, hipStream_t s, hi
     PRISM_HIP(hipMemcpyAsync(c->layer_buf[slot] + it.dst_off, it.src, it.bytes, kind, s));
     if (bytes) *bytes += (int64_t)it.bytes;
   }
+  // half operands: the bf16 weights become the same numbers in IEEE half, in place, on the same stream
+  if (c->op == PRISM_DTYPE_F16) PRISM_TRY(launch_bf16_to_f16(c->layer_buf[slot], c->lay.bytes / 2, s));
   return PRISM_OK;
 }
 
@@ -202,6 +205,8 @@ extern "C" int prism_create(const prism_model *model, const prism_weights *weigh
   PRISM_REQUIRE(options->n_clusters == 0 || (options->n_clusters >= 2 && options->n_clusters <= PRISM_MAX_CLUSTERS),
                 PRISM_EINVAL, "prism_create: n_clusters %d outside 2..%d", options->n_clusters, PRISM_MAX_CLUSTERS);
   PRISM_REQUIRE(options->chunk_cands >= 0 && options->hbm_cap_bytes >= 0, PRISM_EINVAL, "prism_create: negative option");
+  PRISM_REQUIRE(options->operand == 0 || options->operand == PRISM_DTYPE_F16 || options->operand == PRISM_DTYPE_BF16,
+                PRISM_EINVAL, "prism_create: operand must be 0, PRISM_DTYPE_F16 or PRISM_DTYPE_BF16");
   for (int l = 0; l < model->n_layers; ++l) {
     const prism_layer_weights &w = weights->layers[l];
     PRISM_REQUIRE(w.attn_norm && w.wq && w.wk && w.wv && w.wo && w.ffn_norm && w.w_gate && w.w_up && w.w_down &&
@@ -221,6 +226,8 @@ extern "C" int prism_create(const prism_model *model, const prism_weights *weigh
   std::sort(c->checkpoints.begin(), c->checkpoints.end());
   c->checkpoints.erase(std::unique(c->checkpoints.begin(), c->checkpoints.end()), c->checkpoints.end());
   c->opt.checkpoint_layers = nullptr;
+  c->op = model->dtype == PRISM_DTYPE_FP32 ? PRISM_DTYPE_FP32
+                                            : (options->operand == PRISM_DTYPE_BF16 ? PRISM_DTYPE_BF16 : PRISM_DTYPE_F16);
   c->lay = make_layout(*model);
   c->embed = weights->embed; c->final_norm = weights->final_norm; c->w_yes = weights->w_yes; c->w_no = weights->w_no;
   c->streamed = weights->layer_residency == 1;
@@ -265,7 +272,7 @@ extern "C" void prism_destroy(prism_ctx *c) {
   if (c->stream) (void)hipStreamSynchronize(c->stream);
   if (c->copy_stream) (void)hipStreamSynchronize(c->copy_stream);
   for (char *p : c->layer_buf) if (p) (void)hipFree(p);
-  void *ptrs[] = {c->rope_tab, c->X[0], c->X[1], c->Xn, c->QKV, c->Vt, c->AO, c->S, c->d_meta, c->d_scores, c->d_fate,
+  void *ptrs[] = {c->rope_tab, c->X[0], c->X[1], c->Xn, c->QKV, c->QK, c->Vt, c->AO, c->S, c->d_meta, c->d_scores, c->d_fate,
                   c->d_stats, c->route_ws, c->d_top_pos, c->d_top_scores};
   for (void *p : ptrs) if (p) (void)hipFree(p);
   if (c->h_meta) (void)hipHostFree(c->h_meta);
@@ -332,7 +339,7 @@ static void build_plan(const prism_ctx *c, Plan &p) {
   p.tiles.clear();
   p.max_chunk_tokens = p.max_vt_cols = 0;
   const int step = c->opt.chunk_cands > 0 ? c->opt.chunk_cands : std::max(n, 1);
-  const bool mfma = c->m.dtype == PRISM_DTYPE_BF16;
+  const bool mfma = is16(c->op);
   const int bq = mfma ? 32 * (8 / (c->m.n_q_heads / c->m.n_kv_heads)) : 0;
   for (int c0 = 0; c0 < n; c0 += step) {
     Chunk ch;
@@ -380,16 +387,19 @@ static int ensure_scratch(prism_ctx *c, const Plan &p, bool need_second_x, int n
   if (p.max_chunk_tokens > c->chunk_cap) {
     PRISM_HIP(hipStreamSynchronize(c->stream));
     const int64_t old = c->chunk_cap, cap = p.max_chunk_tokens;
-    dev_free(c, c->Xn, (size_t)old * m.hidden * e); dev_free(c, c->QKV, (size_t)old * (Dq + 2 * Dkv) * e);
+    const bool bf = is16(c->op);
+    dev_free(c, c->Xn, (size_t)old * m.hidden * e); dev_free(c, c->QKV, (size_t)old * (Dq + 2 * Dkv) * 4);
+    if (bf) dev_free(c, c->QK, (size_t)old * (Dq + Dkv) * e);
     dev_free(c, c->AO, (size_t)old * Dq * e); dev_free(c, c->S, (size_t)old * m.ffn * e);
-    c->Xn = c->QKV = c->AO = c->S = nullptr; c->chunk_cap = 0;
+    c->Xn = c->QKV = c->QK = c->AO = c->S = nullptr; c->chunk_cap = 0;
     PRISM_TRY(dev_alloc(c, (void **)&c->Xn, (size_t)cap * m.hidden * e));
-    PRISM_TRY(dev_alloc(c, (void **)&c->QKV, (size_t)cap * (Dq + 2 * Dkv) * e));
+    PRISM_TRY(dev_alloc(c, (void **)&c->QKV, (size_t)cap * (Dq + 2 * Dkv) * 4));     // fp32 projection
+    if (bf) PRISM_TRY(dev_alloc(c, (void **)&c->QK, (size_t)cap * (Dq + Dkv) * e));   // finished q, k
     PRISM_TRY(dev_alloc(c, (void **)&c->AO, (size_t)cap * Dq * e));
     PRISM_TRY(dev_alloc(c, (void **)&c->S, (size_t)cap * m.ffn * e));
     c->chunk_cap = cap;
   }
-  if (m.dtype == PRISM_DTYPE_BF16 && p.max_vt_cols > c->vt_cap) {
+  if (is16(c->op) && p.max_vt_cols > c->vt_cap) {
     const int64_t old = c->vt_cap;
     PRISM_TRY(grow(c, &c->Vt, &c->vt_cap, p.max_vt_cols, (size_t)Dkv * 2));
     (void)old;
@@ -456,9 +466,9 @@ static int run_layer(prism_ctx *c, const Plan &p, const MetaOff &mo, float *X, c
   const LayerLayout &L = c->lay;
   const int H = m.hidden, Dq = m.n_q_heads * m.head_dim, Dkv = m.n_kv_heads * m.head_dim, F = m.ffn;
   hipStream_t s = c->stream;
-  const bool bf = m.dtype == PRISM_DTYPE_BF16;
+  const bool bf = is16(c->op);
   auto gemm = [&](int epi, const void *A, const void *W, void *out, int M, int N, int K) {
-    return bf ? launch_gemm_bf16(epi, (const bf16 *)A, (const bf16 *)W, out, M, N, K, s)
+    return bf ? launch_gemm_16(c->op, epi, A, W, out, M, N, K, s)
               : launch_gemm_fp32(epi, (const float *)A, (const float *)W, out, M, N, K, s);
   };
   for (const Chunk &ch : p.chunks) {
@@ -469,26 +479,27 @@ static int run_layer(prism_ctx *c, const Plan &p, const MetaOff &mo, float *X, c
     for (int i = ch.c0; i < ch.c1; ++i) attn_flops += 2.0 * m.n_q_heads * m.head_dim * (double)p.len[i] * (p.len[i] + 1.0);
     const double tk = 2.0 * Tc;
     // ---- attention block: X += Attn(RMSNorm(X)) Wo^T
-    PRISM_TRY(timed_span(c, 5, 0.0, [&] { return launch_rmsnorm(Xc, wbuf + L.attn_norm, Tc, H, m.rms_eps, m.dtype, c->Xn, s); }));
-    PRISM_TRY(timed_span(c, 0, tk * (Dq + 2 * Dkv) * H, [&] { return gemm(PRISM_EPI_STORE, c->Xn, wbuf + L.wqkv, c->QKV, Tc, Dq + 2 * Dkv, H); }));
+    PRISM_TRY(timed_span(c, 5, 0.0, [&] { return launch_rmsnorm(Xc, wbuf + L.attn_norm, Tc, H, m.rms_eps, c->op, c->Xn, s); }));
+    PRISM_TRY(timed_span(c, 0, tk * (Dq + 2 * Dkv) * H, [&] {
+      return gemm(bf ? PRISM_EPI_STORE_F32 : PRISM_EPI_STORE, c->Xn, wbuf + L.wqkv, c->QKV, Tc, Dq + 2 * Dkv, H);
+    }));
     PRISM_TRY(timed_span(c, 5, 0.0, [&] {
-      PRISM_TRY(launch_qknorm_rope(m.dtype, c->QKV, pos, wbuf + L.q_norm, wbuf + L.k_norm, Tc, m.n_q_heads, m.n_kv_heads,
-                                   m.head_dim, m.rms_eps, m.qk_norm, c->rope_tab, s));
+      PRISM_TRY(launch_qk_finish(c->op, (float *)c->QKV, pos, wbuf + L.q_norm, wbuf + L.k_norm, Tc, m.n_q_heads,
+                                 m.n_kv_heads, m.head_dim, m.rms_eps, m.qk_norm, c->rope_tab, c->QK, s));
       if (bf)
-        PRISM_TRY(launch_v_transpose((const bf16 *)c->QKV, Tc, m.n_q_heads, m.n_kv_heads, m.head_dim, (bf16 *)c->Vt,
-                                     c->d_meta + mo.vtcol + ch.r0, c->vt_cap, s));
+        PRISM_TRY(launch_v_finish(c->op, (const float *)c->QKV, Tc, m.n_q_heads, m.n_kv_heads, m.head_dim, c->Vt,
+                                  c->d_meta + mo.vtcol + ch.r0, c->vt_cap, s));
       return (int)PRISM_OK;
     }));
     PRISM_TRY(timed_span(c, 4, attn_flops, [&] {
       if (bf)
-        return launch_attention_bf16((const bf16 *)c->QKV, (const bf16 *)c->Vt, c->vt_cap,
-                                     (const AttnTile *)(c->d_meta + mo.tiles) + ch.tile0, ch.n_tiles, Tc, m.n_q_heads,
-                                     m.n_kv_heads, m.head_dim, (bf16 *)c->AO, s);
+        return launch_attention_16(c->op, c->QK, c->Vt, c->vt_cap, (const AttnTile *)(c->d_meta + mo.tiles) + ch.tile0,
+                                   ch.n_tiles, Tc, m.n_q_heads, m.n_kv_heads, m.head_dim, c->AO, s);
       return launch_attention_fp32((const float *)c->QKV, pos, Tc, m.n_q_heads, m.n_kv_heads, m.head_dim, (float *)c->AO, s);
     }));
     PRISM_TRY(timed_span(c, 1, tk * H * Dq, [&] { return gemm(PRISM_EPI_RESIDUAL, c->AO, wbuf + L.wo, Xc, Tc, H, Dq); }));
     // ---- FFN block: X += (silu(Xn Wg^T) * (Xn Wu^T)) Wd^T
-    PRISM_TRY(timed_span(c, 5, 0.0, [&] { return launch_rmsnorm(Xc, wbuf + L.ffn_norm, Tc, H, m.rms_eps, m.dtype, c->Xn, s); }));
+    PRISM_TRY(timed_span(c, 5, 0.0, [&] { return launch_rmsnorm(Xc, wbuf + L.ffn_norm, Tc, H, m.rms_eps, c->op, c->Xn, s); }));
     PRISM_TRY(timed_span(c, 2, tk * 2 * F * H, [&] { return gemm(PRISM_EPI_SWIGLU, c->Xn, wbuf + L.wgu, c->S, Tc, 2 * F, H); }));
     PRISM_TRY(timed_span(c, 3, tk * H * F, [&] { return gemm(PRISM_EPI_RESIDUAL, c->S, wbuf + L.wd, Xc, Tc, H, F); }));
   }
@@ -768,64 +779,67 @@ extern "C" int prism_op_rmsnorm(const float *X, const void *gain, int32_t T, int
 
 extern "C" int prism_op_gemm(int32_t dtype, int32_t epilogue, const void *A, const void *W, void *out, int32_t M, int32_t N,
                              int32_t K, void *stream) {
-  PRISM_REQUIRE(epilogue >= PRISM_EPI_STORE && epilogue <= PRISM_EPI_SWIGLU, PRISM_EINVAL, "gemm: unknown epilogue %d", epilogue);
+  PRISM_REQUIRE(epilogue >= PRISM_EPI_STORE && epilogue <= PRISM_EPI_STORE_F32, PRISM_EINVAL, "gemm: unknown epilogue %d", epilogue);
+  PRISM_REQUIRE(dtype != PRISM_DTYPE_FP32 || epilogue != PRISM_EPI_STORE_F32, PRISM_EINVAL, "gemm: STORE_F32 is a bf16-mode epilogue");
   if (dtype == PRISM_DTYPE_FP32) return launch_gemm_fp32(epilogue, (const float *)A, (const float *)W, out, M, N, K, (hipStream_t)stream);
-  PRISM_REQUIRE(dtype == PRISM_DTYPE_BF16, PRISM_EINVAL, "gemm: unknown dtype %d", dtype);
-  return launch_gemm_bf16(epilogue, (const bf16 *)A, (const bf16 *)W, out, M, N, K, (hipStream_t)stream);
+  PRISM_REQUIRE(is16(dtype), PRISM_EINVAL, "gemm: unknown dtype %d", dtype);
+  return launch_gemm_16(dtype, epilogue, A, W, out, M, N, K, (hipStream_t)stream);
 }
 
-extern "C" int prism_op_qknorm_rope(int32_t dtype, void *QKV, const int32_t *pos, int32_t max_pos, const void *q_gain,
-                                    const void *k_gain, int32_t T, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
-                                    float eps, float rope_base, int32_t qk_norm, void *stream) {
-  PRISM_REQUIRE(max_pos > 0 && max_pos <= PRISM_MAX_SEQ && head_dim > 0 && head_dim % 2 == 0, PRISM_EINVAL, "qknorm_rope: max_pos / head_dim");
+extern "C" int prism_op_qkv_finish(int32_t dtype, void *QKV, const int32_t *pos, int32_t max_pos, const void *q_gain,
+                                   const void *k_gain, int32_t T, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                   float eps, float rope_base, int32_t qk_norm, void *QK, void *Vt, const int32_t *vt_col,
+                                   int64_t vt_stride, void *stream) {
+  PRISM_REQUIRE(max_pos > 0 && max_pos <= PRISM_MAX_SEQ && head_dim > 0 && head_dim % 2 == 0, PRISM_EINVAL, "qkv_finish: max_pos / head_dim");
+  PRISM_REQUIRE(dtype == PRISM_DTYPE_FP32 || (is16(dtype) && QK && Vt && vt_col && vt_stride > 0), PRISM_EINVAL, "qkv_finish: 16-bit modes need QK, Vt, vt_col");
   hipStream_t s = (hipStream_t)stream;
   TmpDev tab;
   PRISM_TRY(tab.alloc((size_t)max_pos * (head_dim / 2) * sizeof(float2)));
   PRISM_TRY(launch_rope_table((float2 *)tab.p, max_pos, head_dim, rope_base, s));
-  PRISM_TRY(launch_qknorm_rope(dtype, QKV, pos, q_gain, k_gain, T, n_q_heads, n_kv_heads, head_dim, eps, qk_norm,
-                               (const float2 *)tab.p, s));
+  PRISM_TRY(launch_qk_finish(dtype, (float *)QKV, pos, q_gain, k_gain, T, n_q_heads, n_kv_heads, head_dim, eps, qk_norm,
+                             (const float2 *)tab.p, QK, s));
+  if (is16(dtype))
+    PRISM_TRY(launch_v_finish(dtype, (const float *)QKV, T, n_q_heads, n_kv_heads, head_dim, Vt, vt_col, vt_stride, s));
   PRISM_HIP(hipStreamSynchronize(s));   // the table is freed on return
   return PRISM_OK;
 }
 
-extern "C" int prism_op_attention(int32_t dtype, const void *QKV, const int32_t *cu, int32_t n_seqs, int32_t nq, int32_t nkv,
-                                  int32_t hd, void *out, void *stream) {
-  PRISM_REQUIRE(QKV && cu && out && n_seqs >= 0 && nq > 0 && nkv > 0 && nq % nkv == 0, PRISM_EINVAL, "attention: bad arguments");
+extern "C" int prism_op_attention(int32_t dtype, const void *QK, const void *Vt, int64_t vt_stride, const int32_t *cu,
+                                  const int32_t *vt_col0, int32_t n_seqs, int32_t nq, int32_t nkv, int32_t hd, void *out,
+                                  void *stream) {
+  PRISM_REQUIRE(QK && cu && out && n_seqs >= 0 && nq > 0 && nkv > 0 && nq % nkv == 0, PRISM_EINVAL, "attention: bad arguments");
   hipStream_t s = (hipStream_t)stream;
   if (n_seqs == 0) return PRISM_OK;
   const int T = cu[n_seqs];
   for (int i = 0; i < n_seqs; ++i)
     PRISM_REQUIRE(cu[i + 1] > cu[i] && cu[i + 1] - cu[i] <= PRISM_MAX_SEQ, PRISM_EINVAL, "attention: sequence %d has bad length", i);
-  std::vector<int32_t> pos(T), vtcol(T);
+  const bool bf = is16(dtype);
+  PRISM_REQUIRE(bf || dtype == PRISM_DTYPE_FP32, PRISM_EINVAL, "attention: unknown dtype %d", dtype);
+  if (!bf) {
+    std::vector<int32_t> pos(T);
+    for (int i = 0; i < n_seqs; ++i) for (int t = cu[i]; t < cu[i + 1]; ++t) pos[t] = t - cu[i];
+    TmpDev d_pos;
+    PRISM_TRY(d_pos.alloc((size_t)T * 4));
+    PRISM_HIP(hipMemcpyAsync(d_pos.p, pos.data(), (size_t)T * 4, hipMemcpyHostToDevice, s));
+    PRISM_TRY(launch_attention_fp32((const float *)QK, (const int32_t *)d_pos.p, T, nq, nkv, hd, (float *)out, s));
+    PRISM_HIP(hipStreamSynchronize(s));
+    return PRISM_OK;
+  }
+  PRISM_REQUIRE(attention_16_supported(nq, nkv, hd), PRISM_EUNSUPPORTED, "attention bf16: unsupported head shape");
+  PRISM_REQUIRE(Vt && vt_col0 && vt_stride > 0, PRISM_EINVAL, "attention bf16: Vt / vt_col0 missing");
   std::vector<AttnTile> tiles;
-  int64_t col = 0;
-  const bool bf = dtype == PRISM_DTYPE_BF16;
-  PRISM_REQUIRE(!bf || attention_bf16_supported(nq, nkv, hd), PRISM_EUNSUPPORTED, "attention bf16: unsupported head shape");
-  const int bq = bf ? 32 * (8 / (nq / nkv)) : 1;
+  const int bq = 32 * (8 / (nq / nkv));
   for (int i = 0; i < n_seqs; ++i) {
     const int L = cu[i + 1] - cu[i];
-    for (int t = 0; t < L; ++t) { pos[cu[i] + t] = t; vtcol[cu[i] + t] = (int32_t)(col + t); }
-    if (bf) for (int q0 = 0; q0 < L; q0 += bq) tiles.push_back({cu[i], L, q0, (int32_t)col});
-    col += round_up(L, 64);
+    PRISM_REQUIRE(vt_col0[i] >= 0 && vt_col0[i] % 64 == 0 && vt_col0[i] + round_up(L, 64) <= vt_stride, PRISM_EINVAL,
+                  "attention bf16: sequence %d: V^T columns must start at a multiple of 64 and fit the row stride", i);
+    for (int q0 = 0; q0 < L; q0 += bq) tiles.push_back({cu[i], L, q0, vt_col0[i]});
   }
-  TmpDev d_pos, d_vtcol, d_tiles, d_vt;
-  PRISM_TRY(d_pos.alloc((size_t)T * 4));
-  PRISM_HIP(hipMemcpyAsync(d_pos.p, pos.data(), (size_t)T * 4, hipMemcpyHostToDevice, s));
-  if (!bf) {
-    PRISM_TRY(launch_attention_fp32((const float *)QKV, (const int32_t *)d_pos.p, T, nq, nkv, hd, (float *)out, s));
-  } else {
-    PRISM_TRY(d_vtcol.alloc((size_t)T * 4));
-    PRISM_TRY(d_tiles.alloc(tiles.size() * sizeof(AttnTile)));
-    const size_t vt_bytes = (size_t)round_up((size_t)col * nkv * hd * 2, 256);
-    PRISM_TRY(d_vt.alloc(vt_bytes));
-    PRISM_HIP(hipMemcpyAsync(d_vtcol.p, vtcol.data(), (size_t)T * 4, hipMemcpyHostToDevice, s));
-    PRISM_HIP(hipMemcpyAsync(d_tiles.p, tiles.data(), tiles.size() * sizeof(AttnTile), hipMemcpyHostToDevice, s));
-    PRISM_TRY(launch_fill_zero(d_vt.p, vt_bytes, s));
-    PRISM_TRY(launch_v_transpose((const bf16 *)QKV, T, nq, nkv, hd, (bf16 *)d_vt.p, (const int32_t *)d_vtcol.p, col, s));
-    PRISM_TRY(launch_attention_bf16((const bf16 *)QKV, (const bf16 *)d_vt.p, col, (const AttnTile *)d_tiles.p, (int)tiles.size(),
-                                    T, nq, nkv, hd, (bf16 *)out, s));
-  }
-  PRISM_HIP(hipStreamSynchronize(s));   // temporaries and host vectors are released on return
+  TmpDev d_tiles;
+  PRISM_TRY(d_tiles.alloc(tiles.size() * sizeof(AttnTile)));
+  PRISM_HIP(hipMemcpyAsync(d_tiles.p, tiles.data(), tiles.size() * sizeof(AttnTile), hipMemcpyHostToDevice, s));
+  PRISM_TRY(launch_attention_16(dtype, QK, Vt, vt_stride, (const AttnTile *)d_tiles.p, (int)tiles.size(), T, nq, nkv, hd, out, s));
+  PRISM_HIP(hipStreamSynchronize(s));   // temporaries are released on return
   return PRISM_OK;
 }
 

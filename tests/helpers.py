@@ -20,10 +20,8 @@ def oracle_weights(wt: W.Weights, layers=None) -> dict:
 
 
 def oracle_model(m: W.ModelShape, operand: str = None) -> O.Model:
-    """operand: precision of the contraction operands; by default the workload's own mode
-    (fp32 workloads: exact; bf16 workloads: bf16 operands)."""
-    if operand is None:
-        operand = "exact" if m.dtype == "fp32" else "bf16"
+    """operand: precision of the contraction operands, "exact" unless a test asks for a rounded one."""
+    operand = operand or "exact"
     return O.Model(m.n_layers, m.hidden, m.n_q_heads, m.n_kv_heads, m.head_dim, m.ffn, m.vocab,
                    m.rms_eps, m.rope_base, m.qk_norm, operand)
 

@@ -1,4 +1,5 @@
-"""Parity at the benchmark's full sizes, in the launch configuration bench.py times.
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times (IEEE half operands),
+against the exact (fp64) oracle.
 
 The 0.6B-shaped workload is compared with a complete oracle run.  For the 4B- and 8B-shaped workloads a
 complete oracle run would take hours, so the comparison is on sampled outputs the oracle can compute one
@@ -46,6 +47,8 @@ def test_cfg2_full_oracle_parity():
     _progress("cfg2: gpu done, oracle starts")
     ref = oracle_select(w, wt, (q, cands), progress=lambda l, n: _progress(f"cfg2 oracle layer {l} live {n}"))
     check_against_oracle(w, idx, scores, rep, ref, TOL)
+    worst = max(float(np.max(np.abs(rep.scores[e][ev.live] - ev.scores))) for e, ev in enumerate(ref.events))
+    _progress(f"cfg2: worst |gpu - oracle| {worst:.3e}")
 
 
 def _rule1_and_topk(w, idx, scores, rep):
@@ -82,14 +85,14 @@ def _oracle_trajectories(w, wt, q, cands, sample, depth, tag):
     return out
 
 
-def _run_gpu(w, wt, mode=B.MODE_DROP_ONLY):
+def _run_gpu(w, wt, mode=B.MODE_DROP_ONLY, operand="f16"):
     q, cands = W.make_tokens(w)
     weights = wt
     if w.stream_weights:
         host = [{k: v.to("cpu").pin_memory() for k, v in l.items()} for l in wt.layers]
         weights = W.Weights(wt.embed, host, wt.final_norm)
     p = B.Prism(w.model, weights, checkpoints=w.checkpoints, mode=mode, chunk_cands=w.chunk_cands,
-                hbm_cap_bytes=w.hbm_cap_bytes, stream_weights=w.stream_weights)
+                hbm_cap_bytes=w.hbm_cap_bytes, stream_weights=w.stream_weights, operand=operand)
     out = p.select(q, cands, w.K)
     p.destroy()
     return out
@@ -117,7 +120,25 @@ def _sampled_check(w, wt, n_survivors=1):
             worst = max(worst, abs(float(rep.scores[e][c]) - s))
             assert abs(float(rep.scores[e][c]) - s) <= TOL, (w.name, c, l, float(rep.scores[e][c]), s)
     _progress(f"{w.name}: worst |gpu - oracle| over sampled scores {worst:.3e}")
-    return idx, scores, rep
+    return idx, scores, rep, traj
+
+
+def _bf16_operand_variant(w, wt, traj):
+    """The bf16-operand variant at full size: the properties hold exactly; its distance to the exact oracle
+    is inherent to 8-bit significands (a forward with bf16-rounded operands, in any arithmetic, differs from
+    the exact one by up to ~0.1 in score on these random-weight models), so it is logged and only bounded
+    loosely here."""
+    idx, scores, rep = _run_gpu(w, wt, operand="bf16")
+    _rule1_and_topk(w, idx, scores, rep)
+    worst = 0.0
+    for c, tr in traj.items():
+        for l, s in tr.items():
+            if l in rep.layer.tolist():
+                g = rep.scores[int(np.where(rep.layer == l)[0][0])][c]
+                if not np.isnan(g):
+                    worst = max(worst, abs(float(g) - s))
+    _progress(f"{w.name}: bf16 operands: worst |gpu - exact oracle| over sampled scores {worst:.3e}")
+    assert worst < 0.3
 
 
 @pytest.fixture(scope="module")
@@ -128,7 +149,7 @@ def weights_8b():
 def test_cfg3_sampled_oracle_parity_and_properties():
     w = W.WORKLOADS["cfg3_4b"]
     wt = W.make_weights(w, "cuda")
-    idx, scores, rep = _sampled_check(w, wt)
+    idx, scores, rep, traj = _sampled_check(w, wt)
     idx0, s0, rep0 = _run_gpu(w, wt, B.MODE_NO_PRUNING)
     live = ~np.isnan(rep.scores[-1])
     assert np.array_equal(rep.scores[-1][live], rep0.scores[-1][live])   # drop-only survivors = full-depth scores
@@ -136,18 +157,19 @@ def test_cfg3_sampled_oracle_parity_and_properties():
 
 def test_cfg4_headline_sampled_oracle_parity_and_properties(weights_8b):
     w = W.WORKLOADS["cfg4_8b"]
-    idx, scores, rep = _sampled_check(w, weights_8b)
+    idx, scores, rep, traj = _sampled_check(w, weights_8b)
     idx0, s0, rep0 = _run_gpu(w, weights_8b, B.MODE_NO_PRUNING)
     live = ~np.isnan(rep.scores[-1])
     assert np.array_equal(rep.scores[-1][live], rep0.scores[-1][live])
     assert rep.ms_total < rep0.ms_total                                  # pruning cuts the top-K latency
+    _bf16_operand_variant(w, weights_8b, traj)
 
 
 def test_cfg5_streamed_chunked_under_the_hbm_cap(weights_8b):
     """500 candidates, log-normal lengths, weights streamed from pinned host memory one layer ahead,
     chunks of 64 candidates, 24 GB cap on library-owned device memory."""
     w = W.WORKLOADS["cfg5_8b_stream"]
-    idx, scores, rep = _sampled_check(w, weights_8b)
+    idx, scores, rep, traj = _sampled_check(w, weights_8b)
     assert rep.peak_hbm_bytes <= w.hbm_cap_bytes
     per_layer = 2 * (w.model.gemm_flops_per_token_layer() // 2)          # bf16 bytes of the matrices of one layer
     assert rep.bytes_streamed >= w.model.n_layers * per_layer

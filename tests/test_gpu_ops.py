@@ -36,14 +36,20 @@ def test_embed(dtype):
     assert np.array_equal(X.cpu().numpy().astype(np.float64), O.embed(tok.numpy(), _f64(table)))
 
 
-@pytest.mark.parametrize("dtype,hidden", [(torch.float32, 256), (torch.float32, 192), (torch.bfloat16, 4096), (torch.bfloat16, 512)])
+SIXTEEN = [torch.bfloat16, torch.float16]
+EPS16 = {torch.bfloat16: 2.0 ** -8, torch.float16: 2.0 ** -11}      # half an ulp, relative
+OPERAND = {torch.bfloat16: "bf16", torch.float16: "f16"}
+
+
+@pytest.mark.parametrize("dtype,hidden", [(torch.float32, 256), (torch.float32, 192), (torch.bfloat16, 4096), (torch.bfloat16, 512),
+                                          (torch.float16, 4096), (torch.float16, 1024)])
 def test_rmsnorm(dtype, hidden):
     X = _rand((333, hidden), torch.float32, 3, 2.5)
     g = (1 + _rand((hidden,), torch.float32, 4, 0.1)).to(dtype)
     out = torch.empty(333, hidden, dtype=dtype, device=DEV)
     B.op_rmsnorm(X.to(DEV), g.to(DEV), 1e-6, out)
     ref = O.rmsnorm(_f64(X), _f64(g), 1e-6)
-    tol = dict(rtol=1e-5, atol=1e-6) if dtype == torch.float32 else dict(rtol=2 ** -8, atol=1e-6)
+    tol = dict(rtol=1e-5, atol=1e-6) if dtype == torch.float32 else dict(rtol=EPS16[dtype] * 1.01, atol=1e-6)
     np.testing.assert_allclose(_f64(out), ref, **tol)
 
 
@@ -52,7 +58,7 @@ GEMM_SHAPES = [  # M, N (rows of W), K
 ]
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
 @pytest.mark.parametrize("epi", [B.EPI_STORE, B.EPI_RESIDUAL, B.EPI_SWIGLU])
 @pytest.mark.parametrize("shape", GEMM_SHAPES)
 def test_gemm(dtype, epi, shape):
@@ -79,27 +85,64 @@ def test_gemm(dtype, epi, shape):
     elif epi == B.EPI_RESIDUAL:
         np.testing.assert_allclose(_f64(out), ref, rtol=1e-4, atol=1e-4)       # fp32 accumulate, fp32 out
     else:
-        np.testing.assert_allclose(_f64(out), ref, rtol=2 ** -8, atol=2e-3)    # one bf16 rounding of the result
+        np.testing.assert_allclose(_f64(out), ref, rtol=EPS16[dtype] * 1.01, atol=2e-3 * EPS16[dtype] * 256)    # one 16-bit rounding of the result
 
 
-@pytest.mark.parametrize("dtype,nq,nkv,hd", [(torch.float32, 4, 2, 64), (torch.float32, 6, 3, 32), (torch.bfloat16, 8, 2, 128)])
+@pytest.mark.parametrize("dtype", SIXTEEN)
+def test_gemm_16_fp32_output(dtype):
+    M, N, K = 700, 6144, 1024
+    A, Wt = _rand((M, K), dtype, 5), _rand((N, K), dtype, 6, 1.0 / math.sqrt(K))
+    out = torch.zeros(M, N, dtype=torch.float32, device=DEV)
+    B.op_gemm(B.EPI_STORE_F32, A.to(DEV), Wt.to(DEV), out)
+    np.testing.assert_allclose(_f64(out), _f64(A) @ _f64(Wt).T, rtol=1e-4, atol=1e-4)
+
+
+def _vt_layout(lens):
+    """Column of every token in the transposed V buffer: sequences start at multiples of 64."""
+    col0 = np.concatenate([[0], np.cumsum([(l + 63) // 64 * 64 for l in lens])]).astype(np.int32)
+    vt_col = np.concatenate([col0[i] + np.arange(l) for i, l in enumerate(lens)]).astype(np.int32)
+    return col0[:-1], vt_col, int(col0[-1])
+
+
+@pytest.mark.parametrize("dtype,nq,nkv,hd", [(torch.float32, 4, 2, 64), (torch.float32, 6, 3, 32), (torch.bfloat16, 8, 2, 128),
+                                             (torch.float16, 8, 2, 128)])
 @pytest.mark.parametrize("qk_norm", [True, False])
-def test_qknorm_rope(dtype, nq, nkv, hd, qk_norm):
+def test_qkv_finish(dtype, nq, nkv, hd, qk_norm):
     lens = [5, 130, 1, 64, 299]
     T = sum(lens)
     pos = np.concatenate([np.arange(l) for l in lens]).astype(np.int32)
-    QKV = _rand((T, (nq + 2 * nkv) * hd), dtype, 40, 1.5)
+    QKV = _rand((T, (nq + 2 * nkv) * hd), torch.float32, 40, 1.5)
     gq, gk = (1 + _rand((hd,), torch.float32, 41, 0.1)).to(dtype), (1 + _rand((hd,), torch.float32, 42, 0.1)).to(dtype)
-    d = QKV.to(DEV).clone()
-    B.op_qknorm_rope(d, torch.from_numpy(pos).to(DEV), 512, gq.to(DEV), gk.to(DEV), nq, nkv, hd, 1e-6, 1e6, qk_norm)
     x = _f64(QKV).reshape(T, nq + 2 * nkv, hd)
     q, k, v = x[:, :nq], x[:, nq:nq + nkv], x[:, nq + nkv:]
     if qk_norm:
         q, k = O.rmsnorm(q, _f64(gq), 1e-6), O.rmsnorm(k, _f64(gk), 1e-6)
-    ref = np.concatenate([O.rope(q, pos, 1e6), O.rope(k, pos, 1e6), v], axis=1).reshape(T, -1)
-    tol = dict(rtol=1e-5, atol=2e-5) if dtype == torch.float32 else dict(rtol=2 ** -7, atol=2e-2)
-    np.testing.assert_allclose(_f64(d), ref, **tol)
-    assert np.array_equal(_f64(d).reshape(T, -1, hd)[:, nq + nkv:], v)          # v untouched
+    q, k = O.rope(q, pos, 1e6), O.rope(k, pos, 1e6)
+    d = QKV.to(DEV).clone()
+    dpos = torch.from_numpy(pos).to(DEV)
+    if dtype == torch.float32:
+        B.op_qkv_finish(B.DTYPE_FP32, d, dpos, 512, gq.to(DEV), gk.to(DEV), nq, nkv, hd, 1e-6, 1e6, qk_norm)
+        ref = np.concatenate([q, k, v], axis=1).reshape(T, -1)
+        np.testing.assert_allclose(_f64(d), ref, rtol=1e-5, atol=2e-5)
+        return
+    col0, vt_col, ncol = _vt_layout(lens)
+    QK = torch.zeros(T, (nq + nkv) * hd, dtype=dtype, device=DEV)
+    Vt = torch.zeros(nkv, hd, ncol, dtype=torch.float16, device=DEV)
+    B.op_qkv_finish(B._dt(QK), d, dpos, 512, gq.to(DEV), gk.to(DEV), nq, nkv, hd, 1e-6, 1e6, qk_norm,
+                    QK, Vt, torch.from_numpy(vt_col).to(DEV), ncol)
+    ref_qk = np.concatenate([q, k], axis=1).reshape(T, -1)
+    got = _f64(QK)
+    # one rounding to bf16 of a value computed in fp32: within one bf16 ulp of the oracle's rounded value,
+    # and equal to it except where fp32 arithmetic lands on the other side of a rounding boundary
+    np.testing.assert_allclose(got, ref_qk, rtol=EPS16[dtype] * 1.01, atol=1e-6)
+    assert np.mean(got != O.round_operand(ref_qk, OPERAND[dtype])) < 0.02
+    vt = _f64(Vt)
+    ref_v = np.transpose(O.round_operand(v, OPERAND[dtype]), (1, 2, 0))
+    diff = np.abs(vt[:, :, vt_col] - ref_v)
+    # exact (rounding + layout), except that half cannot hold bf16 values below 2^-17 exactly
+    assert diff.max() <= 2.0 ** -25 and np.all(diff[np.abs(ref_v) >= 2.0 ** -14] == 0), (diff.max(), int((diff > 0).sum()))
+    pad = np.setdiff1d(np.arange(ncol), vt_col)
+    assert (vt[:, :, pad] == 0).all()
 
 
 ATTN_CASES = [
@@ -109,6 +152,10 @@ ATTN_CASES = [
     (torch.bfloat16, 16, 8, 128, [200, 129, 31]),                # G = 2
     (torch.bfloat16, 8, 8, 128, [257, 5]),                       # G = 1
     (torch.bfloat16, 8, 1, 128, [97, 32]),                       # G = 8
+    (torch.bfloat16, 32, 8, 128, [1024, 700]),                   # the 8B head shape at its sequence length
+    (torch.float16, 32, 8, 128, [1024, 700]),
+    (torch.float16, 16, 8, 128, [200, 129, 31]),
+    (torch.float16, 8, 2, 128, [1, 63, 64, 65, 130, 300]),
 ]
 
 
@@ -118,11 +165,19 @@ def test_attention(dtype, nq, nkv, hd, lens):
     cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
     QKV = _rand((T, (nq + 2 * nkv) * hd), dtype, 50 + T, 1.0)
     out = torch.zeros(T, nq * hd, dtype=dtype, device=DEV)
-    B.op_attention(QKV.to(DEV), cu, nq, nkv, hd, out)
     x = _f64(QKV).reshape(T, nq + 2 * nkv, hd)
+    if dtype == torch.float32:
+        B.op_attention(B.DTYPE_FP32, QKV.to(DEV), None, 0, cu, None, nq, nkv, hd, out)
+    else:
+        col0, vt_col, ncol = _vt_layout(lens)
+        QK = QKV[:, :(nq + nkv) * hd].contiguous().to(DEV)
+        Vt = torch.zeros(nkv, hd, ncol, dtype=torch.float16)
+        Vt[:, :, torch.from_numpy(vt_col.astype(np.int64))] = QKV.view(T, -1, hd)[:, nq + nkv:].permute(1, 2, 0).to(torch.float16)
+        B.op_attention(B._dt(QK), QK, Vt.to(DEV), ncol, cu, col0, nq, nkv, hd, out)
     ref = np.concatenate([O.causal_gqa_attention(x[a:b, :nq], x[a:b, nq:nq + nkv], x[a:b, nq + nkv:]).reshape(b - a, -1)
                           for a, b in zip(cu[:-1], cu[1:])])
-    tol = dict(rtol=1e-4, atol=1e-5) if dtype == torch.float32 else dict(rtol=2e-2, atol=1.5e-2)
+    # bf16 mode: exact operands, f16 probabilities, fp32 accumulation, one bf16 rounding of the output
+    tol = dict(rtol=1e-4, atol=1e-5) if dtype == torch.float32 else dict(rtol=2 ** -8 if dtype == torch.bfloat16 else 2 ** -9, atol=2e-3)
     np.testing.assert_allclose(_f64(out), ref, **tol)
 
 

@@ -1,9 +1,11 @@
 """End-to-end parity of prism_select with the oracle on the small workloads: every live score at
 every checkpoint, the surviving sets, the final top-K.  Comparison rule:
   1. the GPU's keep decision equals the oracle's route() applied to the GPU's own scores, always;
-  2. every live score agrees with the oracle's within tol (1e-4 fp32 mode, 2e-2 bf16 mode);
+  2. every live score agrees with the oracle's within tol (1e-4 with fp32 weights, 2e-2 with bf16 weights);
   3. surviving sets are identical (these workloads have margins far above tol);
   4. the final top-K order is identical wherever adjacent oracle scores differ by more than 2 tol.
+The oracle is the exact (fp64) one.  Only the bf16-operand variant of the 16-bit mode is compared with the
+oracle run in the same operand precision as well.
 """
 import numpy as np
 import pytest
@@ -62,6 +64,13 @@ def test_select_matches_oracle(name, tol):
     idx, scores, rep = run(w)
     ref = oracle_select(w)
     check_against_oracle(w, idx, scores, rep, ref, tol)
+
+
+def test_bf16_operand_variant_matches_oracle():
+    w = W.WORKLOADS["mini_bf16"]
+    idx, scores, rep = run(w, operand="bf16")
+    check_against_oracle(w, idx, scores, rep, oracle_select(w), 2e-2)                       # exact arithmetic
+    check_against_oracle(w, idx, scores, rep, oracle_select(w, operand="bf16"), 2e-2)       # same operand precision
 
 
 @pytest.mark.parametrize("name,tol", [("cfg1_tiny", 1e-4), ("mini_bf16", 2e-2)])
