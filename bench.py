@@ -25,8 +25,8 @@ KIND_NAMES = ["gemm_qkv", "gemm_o", "gemm_gate_up_swiglu", "gemm_down", "attenti
 
 
 def cpu_baseline(w, wt_dev, q, cands, token_layers_job: int, n_cands: int):
-    """The oracle as it stands, timed on a bounded sample: ONE candidate through the first two layers
-    plus one scoring, extrapolated by token-layers to the job the GPU ran (same pruning schedule)."""
+    """The oracle as it stands, timed on a bounded sample: a few candidates through the first few layers
+    plus their scoring, extrapolated by token-layers to the job the GPU ran (same pruning schedule)."""
     import numpy as np
     from oracle import prism_oracle as O
     from tests.helpers import oracle_model, to_f64
@@ -35,24 +35,39 @@ def cpu_baseline(w, wt_dev, q, cands, token_layers_job: int, n_cands: int):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count() or 1
-    n_layers = min(2, w.model.n_layers)
-    c = int(np.argmin([abs(len(x) - np.median([len(y) for y in cands])) for x in cands]))
+    n_layers = min(4, w.model.n_layers)
+    med = np.median([len(y) for y in cands])
+    picks = [int(i) for i in np.argsort([abs(len(x) - med) for x in cands])[:4]]
     ow = {"embed": None, "final_norm": to_f64(wt_dev.final_norm), "w_yes": to_f64(wt_dev.w_yes), "w_no": to_f64(wt_dev.w_no),
           "layers": [{k: to_f64(v) for k, v in wt_dev.layers[l].items()} for l in range(n_layers)]}
-    toks = np.concatenate([q, cands[c]])
-    emb_rows = to_f64(wt_dev.embed[toks.tolist()])
+    toks = [np.concatenate([q, cands[c]]) for c in picks]
+    emb_rows = [to_f64(wt_dev.embed[t.tolist()]) for t in toks]
     om = oracle_model(w.model)
     t0 = time.perf_counter()
-    X = emb_rows
-    for l in range(n_layers):
-        X = O.layer_forward(X, ow["layers"][l], om)
-    O.head_score(X[-1], ow["final_norm"], ow["w_yes"], ow["w_no"], om.rms_eps)
+    for X in emb_rows:
+        for l in range(n_layers):
+            X = O.layer_forward(X, ow["layers"][l], om)
+        O.head_score(X[-1], ow["final_norm"], ow["w_yes"], ow["w_no"], om.rms_eps)
     dt = time.perf_counter() - t0
-    sample_token_layers = len(toks) * n_layers
+    sample_token_layers = sum(len(t) for t in toks) * n_layers
     job_seconds = dt * token_layers_job / sample_token_layers
     return {"value": n_cands / job_seconds, "unit": "candidates/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"fp64 numpy oracle, candidate {c} ({len(toks)} tokens) through layers 1-{n_layers} + one scoring: "
-                      f"{dt:.2f} s, scaled by token-layers ({token_layers_job} in the pruned job / {sample_token_layers} in the sample)"}
+            "sample": f"fp64 numpy oracle, candidates {picks} ({sum(len(t) for t in toks)} tokens) through layers 1-{n_layers} "
+                      f"+ scoring: {dt:.2f} s, scaled by token-layers ({token_layers_job} in the pruned job / "
+                      f"{sample_token_layers} in the sample)"}
+
+
+def stored_traffic(workload: str, kernel: str):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, if the
+    summary is for this workload and kernel; None otherwise (bench.py cannot run the profiler itself)."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_gate_up_gemm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    kv = dict(l.split(":", 1) for l in open(path) if ":" in l and not l.startswith("#"))
+    kv = {k.strip(): v.strip() for k, v in kv.items()}
+    if kv.get("kernel") != kernel or kv.get("workload") != workload:
+        return None
+    return int(kv["fetch_bytes_per_launch"]) + int(kv["write_bytes_per_launch"])
 
 
 def main():
@@ -61,6 +76,8 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="cfg4_8b")
+    ap.add_argument("--operand", default="f16", choices=["f16", "bf16"],
+                    help="16-bit type of the matrix-core operands when the weights are bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unpruned", action="store_true")
     args = ap.parse_args()
@@ -91,7 +108,7 @@ def main():
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
     opts = dict(checkpoints=w.checkpoints, cv_threshold=w.cv_threshold, n_clusters=w.n_clusters, chunk_cands=w.chunk_cands,
-                hbm_cap_bytes=w.hbm_cap_bytes, stream_weights=w.stream_weights)
+                hbm_cap_bytes=w.hbm_cap_bytes, stream_weights=w.stream_weights, operand=args.operand)
     p = B.Prism(m, wt, **opts)
 
     for _ in range(args.warmup):
@@ -128,8 +145,10 @@ def main():
     dom_fl = sum(r.kind_flops[dom] for r in reps)
     dom_n = sum(r.kind_launches[dom] for r in reps)
     achieved = dom_fl / dom_ms / 1e9
-    roofline = {"bound": "mfma", "kernel": "gemm_bf16_kernel<256,256,2,4,SWIGLU>", "achieved": round(achieved, 1),
-                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+    op_t = "float" if m.dtype == "fp32" else args.operand
+    roofline = {"bound": "mfma", "kernel": f"gemm_16_kernel<{op_t},256,256,2,4,SWIGLU>", "achieved": round(achieved, 1),
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                "traffic": stored_traffic(w.name, f"gemm_16_kernel<{op_t},256,256,2,4,2>"),
                 "flops_per_launch": dom_fl / dom_n, "avg_launch_ms": round(dom_ms / dom_n, 4), "launches": dom_n}
     gemm_ms = sum(r.kind_ms[k] for r in reps for k in range(4))
     gemm_fl = sum(r.kind_flops[k] for r in reps for k in range(4))
@@ -141,12 +160,13 @@ def main():
                   if args.workload == "cfg4_8b" else f"candidates/sec + top-K latency (ms), {args.workload}",
         "value": round(w.n_cands / (ms_per_step / 1e3), 2), "unit": "candidates/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if m.dtype == "bf16" else "f32",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32" if m.dtype == "fp32" else args.operand,
         "data": "synthetic",
         "config": {"workload": f"{w.name}: {m.n_layers} layers, hidden {m.hidden}, {m.n_q_heads}/{m.n_kv_heads} heads x {m.head_dim}, "
                                f"ffn {m.ffn}, vocab {m.vocab}; query {w.query_len} tok, {w.n_cands} candidates, "
                                f"{int(sum(len(c) + len(q) for c in cands))} tokens in all; K={w.K}; "
-                               f"checkpoints after layers {w.checkpoints}; k={w.n_clusters} clusters, tau={w.cv_threshold}, drop-only",
+                               f"checkpoints after layers {w.checkpoints}; k={w.n_clusters} clusters, tau={w.cv_threshold}, drop-only; "
+                               f"weights {m.dtype}, matrix-core operands {op_t}, fp32 accumulation and residual",
                    "n_cands": w.n_cands, "K": w.K, "seed": w.seed, "chunk_cands": w.chunk_cands, "stream_weights": w.stream_weights},
         "topk_latency_ms": round(ms_per_step, 3),
         "unpruned_latency_ms": None if unpruned_ms is None else round(unpruned_ms, 3),
