@@ -50,11 +50,13 @@ template <> __device__ __forceinline__ f16 from_f32<f16>(float v) { return (f16)
 // matrix-core instruction of a 16-bit operand type: D(32x32, fp32) += A(32x16) B(16x32)
 template <typename T> struct Mfma;
 template <> struct Mfma<bf16> {
+  static constexpr bool kIsF16 = false;
   typedef bf16x8 vec8;
   typedef bf16x4 vec4;
   static __device__ __forceinline__ f32x16 mma(vec8 a, vec8 b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
 };
 template <> struct Mfma<f16> {
+  static constexpr bool kIsF16 = true;
   typedef f16x8 vec8;
   typedef f16x4 vec4;
   static __device__ __forceinline__ f32x16 mma(vec8 a, vec8 b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }

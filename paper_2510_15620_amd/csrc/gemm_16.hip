@@ -7,8 +7,10 @@
 //
 // Workgroup tile BM x BN x 64, WM x WN wavefronts, each owning a (BM/WM) x (BN/WN) block of 32x32
 // accumulator tiles.  A and W tiles are staged in LDS (double-buffered; 16-byte chunks XOR-swizzled
-// by row so that the 32-row operand reads spread over the banks).  The next K-slice is fetched into
-// registers while the current one feeds the MFMAs, one barrier per slice.
+// by row so that the 32-row operand reads spread over the banks) by direct global->LDS loads, which
+// need no staging registers; the next K-slice lands while the current one feeds the MFMAs, one
+// barrier per slice.  Inside a slice the operand fragments of step kk+1 are read while step kk's
+// matrix instructions issue.
 //
 // Epilogues: plain store (bf16 or fp32), residual add into the fp32 stream, and SwiGLU, where the B tile is
 // made of BN/2 gate rows and the BN/2 matching up rows so that a lane holds g and u of one element.
@@ -16,28 +18,35 @@
 // Workgroup ids are remapped so that each XCD (ids are dealt round-robin over the 8 XCDs) owns a
 // contiguous range of tiles, walked in groups of 8 row-tiles, to keep the operand panels in its L2.
 #include "common.h"
+#include "gemm_16_kstep.h"
 
 namespace prism {
 
 static constexpr int BK = 64;            // K-slice per stage (elements)
 static constexpr int kChunks = BK / 8;   // 16-byte chunks per tile row
 
-__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ (row & 7); }
+// LDS serves a 16-byte read of 16 consecutive lanes per cycle out of 64 banks; with 128-byte rows the bank
+// half is the row's parity, so the chunk is rotated by bits 1..3 of the row.
+__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
+
+#define PRISM_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
+#define PRISM_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
 template <typename OT, int BM, int BN, int WM, int WN, int EPI>
 __global__ __launch_bounds__(WM *WN * 64) void gemm_16_kernel(const OT *__restrict__ A,
                                                                const OT *__restrict__ W, void *__restrict__ out_,
-                                                                 int M, int N, int K, int nM, int nN) {
-  constexpr int NT = WM * WN * 64;
+                                                               int M, int N, int K, int nM, int nN) {
+  constexpr int NW = WM * WN;
   constexpr int WMT = BM / WM, WNT = BN / WN;      // wave tile
   constexpr int TM = WMT / 32, TN = WNT / 32;      // 32x32 accumulator tiles per wave
-  constexpr int A_ITERS = BM * kChunks / NT, B_ITERS = BN * kChunks / NT;
-  static_assert(BM * kChunks % NT == 0 && BN * kChunks % NT == 0, "tile/threads mismatch");
+  // one direct-to-LDS instruction of a wave moves 64 x 16 B = 8 tile rows
+  constexpr int A_ITERS = BM / 8 / NW, B_ITERS = BN / 8 / NW;
+  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile/waves mismatch");
   static_assert(EPI != PRISM_EPI_SWIGLU || TN % 2 == 0, "SwiGLU pairs gate and up tiles");
-  extern __shared__ __align__(16) unsigned char smem[];
   typedef typename Mfma<OT>::vec8 vec8;
-  OT *lA = reinterpret_cast<OT *>(smem);                 // [2][BM][BK]
-  OT *lB = lA + 2 * BM * BK;                               // [2][BN][BK]
+  extern __shared__ __align__(16) unsigned char smem[];
+  OT *lA = reinterpret_cast<OT *>(smem);                     // [2][BM][BK]
+  OT *lB = lA + 2 * BM * BK;                                 // [2][BN][BK]
 
   // ---- tile mapping: XCD-contiguous ranges, grouped walk ----
   const int n_tiles = nM * nN;
@@ -59,19 +68,22 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_16_kernel(const OT *__restri
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
 
-  // ---- global source pointers of this thread's 16-byte chunks ----
-  const OT *gA[A_ITERS], *gB[B_ITERS];
-  int sA[A_ITERS], sB[B_ITERS];                              // LDS element offsets (within one stage)
+  // ---- global -> LDS staging without registers (global_load_lds_dwordx4).  Instruction j of wave w
+  //      fills tile rows (w * ITERS + j) * 8 .. + 8, lane l landing at row l / 8, chunk slot l % 8.
+  //      The XOR swizzle is applied on the source side: slot p of row r receives chunk swz(r, p).
+  const int lrow = lane >> 3;
+  // byte offsets from A / W (both operands are below 4 GiB: checked by the launcher)
+  uint32_t gA[A_ITERS], gB[B_ITERS];
 #pragma unroll
-  for (int i = 0; i < A_ITERS; ++i) {
-    const int c = tid + i * NT, row = c / kChunks, ch = c % kChunks;
-    int gr = m0 + row; gr = gr < M ? gr : M - 1;
-    gA[i] = A + (int64_t)gr * K + ch * 8;
-    sA[i] = row * BK + swz(row, ch) * 8;
+  for (int j = 0; j < A_ITERS; ++j) {
+    const int row = (wave * A_ITERS + j) * 8 + lrow;
+    int gr = m0 + row;
+    gr = gr < M ? gr : M - 1;
+    gA[j] = ((uint32_t)gr * (uint32_t)K + swz(row, lane & 7) * 8) * 2u;
   }
 #pragma unroll
-  for (int i = 0; i < B_ITERS; ++i) {
-    const int c = tid + i * NT, row = c / kChunks, ch = c % kChunks;
+  for (int j = 0; j < B_ITERS; ++j) {
+    const int row = (wave * B_ITERS + j) * 8 + lrow;
     int gr;
     if (EPI == PRISM_EPI_SWIGLU) {
       const int half = row / (BN / 2), rr = row % (BN / 2);
@@ -80,9 +92,20 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_16_kernel(const OT *__restri
     } else {
       gr = n0 + row; gr = gr < N ? gr : N - 1;
     }
-    gB[i] = W + (int64_t)gr * K + ch * 8;
-    sB[i] = row * BK + swz(row, ch) * 8;
+    gB[j] = ((uint32_t)gr * (uint32_t)K + swz(row, lane & 7) * 8) * 2u;
   }
+  auto stage_loads = [&](int kt, int buf) {
+    const char *baseA = reinterpret_cast<const char *>(A) + (size_t)kt * BK * 2;   // uniform
+    const char *baseB = reinterpret_cast<const char *>(W) + (size_t)kt * BK * 2;
+#pragma unroll
+    for (int j = 0; j < A_ITERS; ++j)
+      __builtin_amdgcn_global_load_lds(PRISM_GLOBAL_PTR(baseA + gA[j]),
+                                       PRISM_LDS_PTR(lA + buf * BM * BK + (wave * A_ITERS + j) * 8 * BK), 16, 0, 0);
+#pragma unroll
+    for (int j = 0; j < B_ITERS; ++j)
+      __builtin_amdgcn_global_load_lds(PRISM_GLOBAL_PTR(baseB + gB[j]),
+                                       PRISM_LDS_PTR(lB + buf * BN * BK + (wave * B_ITERS + j) * 8 * BK), 16, 0, 0);
+  };
 
   // ---- LDS rows this lane reads as MFMA operands ----
   int rA[TM], rB[TN];
@@ -105,82 +128,137 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_16_kernel(const OT *__restri
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  vec8 ra[A_ITERS], rb[B_ITERS];
   const int nk = K / BK;
-#pragma unroll
-  for (int i = 0; i < A_ITERS; ++i) ra[i] = *reinterpret_cast<const vec8 *>(gA[i]);
-#pragma unroll
-  for (int i = 0; i < B_ITERS; ++i) rb[i] = *reinterpret_cast<const vec8 *>(gB[i]);
-#pragma unroll
-  for (int i = 0; i < A_ITERS; ++i) *reinterpret_cast<vec8 *>(lA + sA[i]) = ra[i];
-#pragma unroll
-  for (int i = 0; i < B_ITERS; ++i) *reinterpret_cast<vec8 *>(lB + sB[i]) = rb[i];
-  __syncthreads();
 
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    const bool more = kt + 1 < nk;
-    if (more) {
-#pragma unroll
-      for (int i = 0; i < A_ITERS; ++i) ra[i] = *reinterpret_cast<const vec8 *>(gA[i] + (int64_t)(kt + 1) * BK);
-#pragma unroll
-      for (int i = 0; i < B_ITERS; ++i) rb[i] = *reinterpret_cast<const vec8 *>(gB[i] + (int64_t)(kt + 1) * BK);
+  // The 256x256 / 2x4-wave configuration runs the hand-scheduled slice; other shapes take the compiler's schedule.
+#ifdef PRISM_NO_HAND_SCHED
+  constexpr bool kHandScheduled = false;
+#else
+  constexpr bool kHandScheduled = BM == 256 && BN == 256 && WM == 2 && WN == 4;
+#endif
+  // interior tiles only: the hand-scheduled loop assumes that the tile's rows of A and W all exist
+  const bool interior = m0 + BM <= M && n0 + (EPI == PRISM_EPI_SWIGLU ? BN / 2 : BN) <= F;
+  if (kHandScheduled && interior) {
+    if constexpr (kHandScheduled) {
+      const unsigned ldsA = (unsigned)(uintptr_t)PRISM_LDS_PTR(lA), ldsB = (unsigned)(uintptr_t)PRISM_LDS_PTR(lB);
+      const unsigned aA0 = ldsA + (unsigned)(rA[0] * BK + swz(rA[0], khalf) * 8) * 2u;
+      const unsigned aB0 = ldsB + (unsigned)(rB[0] * BK + swz(rB[0], khalf) * 8) * 2u;
+      const unsigned stride = 8u * (unsigned)K * 2u;
+      const unsigned ldsA_w = __builtin_amdgcn_readfirstlane(ldsA + (unsigned)wave * A_ITERS * 8 * BK * 2);
+      const unsigned ldsB_w = __builtin_amdgcn_readfirstlane(ldsB + (unsigned)wave * B_ITERS * 8 * BK * 2);
+      const uint64_t baseA = (uint64_t)(uintptr_t)A, baseB = (uint64_t)(uintptr_t)W;
+      constexpr bool kF16 = Mfma<OT>::kIsF16;
+      if constexpr (EPI == PRISM_EPI_SWIGLU) {
+        if constexpr (kF16) PRISM_KLOOP("v_mfma_f32_32x32x16_f16", acc, aA0, aB0, gA[0], gB[0], stride, baseA, baseB, nk, ldsA_w, ldsB_w, 16384, 49152);
+        else PRISM_KLOOP("v_mfma_f32_32x32x16_bf16", acc, aA0, aB0, gA[0], gB[0], stride, baseA, baseB, nk, ldsA_w, ldsB_w, 16384, 49152);
+      } else {
+        if constexpr (kF16) PRISM_KLOOP("v_mfma_f32_32x32x16_f16", acc, aA0, aB0, gA[0], gB[0], stride, baseA, baseB, nk, ldsA_w, ldsB_w, 4096, 36864);
+        else PRISM_KLOOP("v_mfma_f32_32x32x16_bf16", acc, aA0, aB0, gA[0], gB[0], stride, baseA, baseB, nk, ldsA_w, ldsB_w, 4096, 36864);
+      }
     }
-    const OT *cA = lA + cur * BM * BK, *cB = lB + cur * BN * BK;
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      vec8 af[TM], bfr[TN];
+  } else {
+    vec8 af[2][TM], bfr[2][TN];
+    auto load_frags = [&](int set, const OT *cA, const OT *cB, int kk) {
 #pragma unroll
       for (int t = 0; t < TM; ++t)
-        af[t] = *reinterpret_cast<const vec8 *>(cA + rA[t] * BK + swz(rA[t], kk * 2 + khalf) * 8);
+        af[set][t] = *reinterpret_cast<const vec8 *>(cA + rA[t] * BK + swz(rA[t], kk * 2 + khalf) * 8);
 #pragma unroll
       for (int t = 0; t < TN; ++t)
-        bfr[t] = *reinterpret_cast<const vec8 *>(cB + rB[t] * BK + swz(rB[t], kk * 2 + khalf) * 8);
+        bfr[set][t] = *reinterpret_cast<const vec8 *>(cB + rB[t] * BK + swz(rB[t], kk * 2 + khalf) * 8);
+    };
+    stage_loads(0, 0);
+    __syncthreads();                                           // waits for the loads (vmcnt) and the workgroup
+    for (int kt = 0; kt < nk; ++kt) {
+      const int cur = kt & 1;
+      if (kt + 1 < nk) stage_loads(kt + 1, cur ^ 1);           // lands while this slice feeds the MFMAs
+      const OT *cA = lA + cur * BM * BK, *cB = lB + cur * BN * BK;
+      load_frags(0, cA, cB, 0);
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int kk = 0; kk < BK / 16; ++kk) {
+        if (kk + 1 < BK / 16) load_frags((kk + 1) & 1, cA, cB, kk + 1);
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = Mfma<OT>::mma(af[i], bfr[j], acc[i][j]);
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = Mfma<OT>::mma(bfr[kk & 1][j], af[kk & 1][i], acc[i][j]);   // transposed tile, see the epilogue
+      }
+      __syncthreads();                                         // next slice landed (vmcnt) and everyone is done with this one
     }
-    if (more) {
-      OT *nA = lA + (cur ^ 1) * BM * BK, *nB = lB + (cur ^ 1) * BN * BK;
-#pragma unroll
-      for (int i = 0; i < A_ITERS; ++i) *reinterpret_cast<vec8 *>(nA + sA[i]) = ra[i];
-#pragma unroll
-      for (int i = 0; i < B_ITERS; ++i) *reinterpret_cast<vec8 *>(nB + sB[i]) = rb[i];
-    }
-    __syncthreads();
   }
 
-  // ---- epilogue.  Accumulator layout of the 32x32 tile: lane holds column (lane % 32) and rows
-  //      (e / 4) * 8 + (lane / 32) * 4 + e % 4 for e = 0..15.
-  const int col_in = lane & 31, row_in = (lane >> 5) * 4;
+  // ---- epilogue.  The W fragment was the instruction's first operand, so the 32x32 accumulator tile is
+  //      transposed: a lane holds ONE row of A, m = lane % 32, and the output columns
+  //      n = (e / 4) * 8 + (lane / 32) * 4 + e % 4, e = 0..15: four runs of 4 consecutive columns, which
+  //      are read / written as 16-byte (fp32) or 8-byte (16-bit) vectors.
+  const int m_in = lane & 31, n_in = (lane >> 5) * 4;
+  const bool full_n = n0 + (EPI == PRISM_EPI_SWIGLU ? BN / 2 : BN) <= F && F % 4 == 0;
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
+    const int row = m0 + wm * WMT + i * 32 + m_in;
+    if (row >= M) continue;
+    if (EPI == PRISM_EPI_SWIGLU) {
+      OT *orow = reinterpret_cast<OT *>(out_) + (int64_t)row * F;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      const int row = m0 + wm * WMT + i * 32 + (e >> 2) * 8 + row_in + (e & 3);
-      if (row >= M) continue;
-      if (EPI == PRISM_EPI_SWIGLU) {
+      for (int j = 0; j < TN / 2; ++j) {
 #pragma unroll
-        for (int j = 0; j < TN / 2; ++j) {
-          const int col = n0 + wn * (WNT / 2) + j * 32 + col_in;
-          if (col < F) {
-            const float g = acc[i][j][e], u = acc[i][j + TN / 2][e];
-            reinterpret_cast<OT *>(out_)[(int64_t)row * F + col] = from_f32<OT>(g / (1.0f + __expf(-g)) * u);
+        for (int g = 0; g < 4; ++g) {
+          const int col = n0 + wn * (WNT / 2) + j * 32 + g * 8 + n_in;
+          typename Mfma<OT>::vec4 v;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const float gt = acc[i][j][g * 4 + q], up = acc[i][j + TN / 2][g * 4 + q];
+            v[q] = from_f32<OT>(gt / (1.0f + __expf(-gt)) * up);
           }
+          if (full_n) *reinterpret_cast<typename Mfma<OT>::vec4 *>(orow + col) = v;
+          else
+            for (int q = 0; q < 4; ++q) if (col + q < F) orow[col + q] = v[q];
         }
-      } else {
+      }
+    } else if (EPI == PRISM_EPI_RESIDUAL) {
+      float *orow = reinterpret_cast<float *>(out_) + (int64_t)row * N;
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          const int col = n0 + wn * WNT + j * 32 + col_in;
-          if (col < N) {
-            if (EPI == PRISM_EPI_STORE)
-              reinterpret_cast<OT *>(out_)[(int64_t)row * N + col] = from_f32<OT>(acc[i][j][e]);
-            else if (EPI == PRISM_EPI_STORE_F32)
-              reinterpret_cast<float *>(out_)[(int64_t)row * N + col] = acc[i][j][e];
+      for (int j = 0; j < TN; ++j) {
+        // all reads of the tile first, then all writes: the compiler cannot reorder a read-modify-write chain
+        // on one pointer, and 16 dependent round trips per tile would serialise on memory latency
+        f32x4 old[4];
+        const int col0 = n0 + wn * WNT + j * 32 + n_in;
+        if (full_n) {
+#pragma unroll
+          for (int g = 0; g < 4; ++g) old[g] = *reinterpret_cast<const f32x4 *>(orow + col0 + g * 8);
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) old[g][q] += acc[i][j][g * 4 + q];
+            *reinterpret_cast<f32x4 *>(orow + col0 + g * 8) = old[g];
+          }
+        } else {
+          for (int g = 0; g < 4; ++g)
+            for (int q = 0; q < 4; ++q)
+              if (col0 + g * 8 + q < N) orow[col0 + g * 8 + q] += acc[i][j][g * 4 + q];
+        }
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int col = n0 + wn * WNT + j * 32 + g * 8 + n_in;
+          if (EPI == PRISM_EPI_STORE_F32) {
+            float *o = reinterpret_cast<float *>(out_) + (int64_t)row * N + col;
+            f32x4 v;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[q] = acc[i][j][g * 4 + q];
+            if (full_n) *reinterpret_cast<f32x4 *>(o) = v;
             else
-              reinterpret_cast<float *>(out_)[(int64_t)row * N + col] += acc[i][j][e];
+              for (int q = 0; q < 4; ++q) if (col + q < N) o[q] = v[q];
+          } else {
+            OT *o = reinterpret_cast<OT *>(out_) + (int64_t)row * N + col;
+            typename Mfma<OT>::vec4 v;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[q] = from_f32<OT>(acc[i][j][g * 4 + q]);
+            if (full_n) *reinterpret_cast<typename Mfma<OT>::vec4 *>(o) = v;
+            else
+              for (int q = 0; q < 4; ++q) if (col + q < N) o[q] = v[q];
           }
         }
       }
@@ -232,6 +310,8 @@ static int launch_typed(int epilogue, const OT *A, const OT *W, void *out, int M
 
 int launch_gemm_16(int dtype, int epilogue, const void *A, const void *W, void *out, int M, int N, int K, hipStream_t s) {
   PRISM_REQUIRE(A && W && out && M >= 0 && is16(dtype), PRISM_EINVAL, "gemm: bad arguments");
+  PRISM_REQUIRE((int64_t)M * K * 2 < ((int64_t)1 << 32) && (int64_t)N * K * 2 < ((int64_t)1 << 32), PRISM_EUNSUPPORTED,
+                "gemm: an operand of %d x %d or %d x %d 16-bit elements exceeds 4 GiB", M, K, N, K);
   PRISM_REQUIRE(gemm_16_supported(epilogue, N, K), PRISM_EUNSUPPORTED,
                 "gemm: N = %d, K = %d, epilogue %d not supported (K must be a multiple of %d)", N, K, epilogue, BK);
   if (M == 0) return PRISM_OK;
