@@ -6,7 +6,9 @@
 // v_mfma_f32_32x32x16_{bf16,f16} (same dense rate).
 //
 // Workgroup tile BM x BN x 64, WM x WN wavefronts, each owning a (BM/WM) x (BN/WN) block of 32x32
-// accumulator tiles.  A and W tiles are staged in LDS (double-buffered; 16-byte chunks XOR-swizzled
+// accumulator tiles.  The production shape is 256 x 256 with 2 x 2 wavefronts (one per SIMD, 128 x 128 each,
+// 256 accumulator registers in AGPRs) and a hand-scheduled K loop (gen_gemm_kloop.py); edge tiles and the
+// small 128 x 128 configuration take the compiler-scheduled loop described next.  A and W tiles are staged in LDS (double-buffered; 16-byte chunks XOR-swizzled
 // by row so that the 32-row operand reads spread over the banks) by direct global->LDS loads, which
 // need no staging registers; the next K-slice lands while the current one feeds the MFMAs, one
 // barrier per slice.  Inside a slice the operand fragments of step kk+1 are read while step kk's
@@ -18,7 +20,7 @@
 // Workgroup ids are remapped so that each XCD (ids are dealt round-robin over the 8 XCDs) owns a
 // contiguous range of tiles, walked in groups of 8 row-tiles, to keep the operand panels in its L2.
 #include "common.h"
-#include "gemm_16_kstep.h"
+#include "gemm_16_kloop.inc"
 
 namespace prism {
 
@@ -130,11 +132,11 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_16_kernel(const OT *__restri
 
   const int nk = K / BK;
 
-  // The 256x256 / 2x4-wave configuration runs the hand-scheduled slice; other shapes take the compiler's schedule.
+  // The 256x256 / 2x2-wave configuration runs the hand-scheduled loop; other shapes take the compiler's schedule.
 #ifdef PRISM_NO_HAND_SCHED
   constexpr bool kHandScheduled = false;
 #else
-  constexpr bool kHandScheduled = BM == 256 && BN == 256 && WM == 2 && WN == 4;
+  constexpr bool kHandScheduled = BM == 256 && BN == 256 && WM == 2 && WN == 2;
 #endif
   // interior tiles only: the hand-scheduled loop assumes that the tile's rows of A and W all exist
   const bool interior = m0 + BM <= M && n0 + (EPI == PRISM_EPI_SWIGLU ? BN / 2 : BN) <= F;
@@ -143,18 +145,33 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_16_kernel(const OT *__restri
       const unsigned ldsA = (unsigned)(uintptr_t)PRISM_LDS_PTR(lA), ldsB = (unsigned)(uintptr_t)PRISM_LDS_PTR(lB);
       const unsigned aA0 = ldsA + (unsigned)(rA[0] * BK + swz(rA[0], khalf) * 8) * 2u;
       const unsigned aB0 = ldsB + (unsigned)(rB[0] * BK + swz(rB[0], khalf) * 8) * 2u;
-      const unsigned stride = 8u * (unsigned)K * 2u;
-      const unsigned ldsA_w = __builtin_amdgcn_readfirstlane(ldsA + (unsigned)wave * A_ITERS * 8 * BK * 2);
-      const unsigned ldsB_w = __builtin_amdgcn_readfirstlane(ldsB + (unsigned)wave * B_ITERS * 8 * BK * 2);
+      // this thread moves chunk (tid % 8) of tile rows tid / 8 + 32 j, j = 0..7, of A and of the B tile
+      const int crow = tid >> 3, cchunk = tid & 7;
+      const unsigned wA = ldsA + (unsigned)(crow * BK + swz(crow, cchunk) * 8) * 2u;
+      const unsigned wB = ldsB + (unsigned)(crow * BK + swz(crow, cchunk) * 8) * 2u;
+      const unsigned gA0 = ((unsigned)(m0 + crow) * (unsigned)K + cchunk * 8) * 2u;
+      const unsigned gB0 = ((unsigned)(n0 + crow) * (unsigned)K + cchunk * 8) * 2u;
+      const unsigned stride32 = 32u * (unsigned)K * 2u;
+      // SwiGLU: B tile rows 128..255 are W rows F + n0 .., i.e. F - 128 rows beyond where plain striding lands
+      const unsigned extraB = EPI == PRISM_EPI_SWIGLU ? (unsigned)(F - BN / 2) * (unsigned)K * 2u : 0u;
       const uint64_t baseA = (uint64_t)(uintptr_t)A, baseB = (uint64_t)(uintptr_t)W;
+#define PRISM_RUN_KLOOP(TEXT)                                                                                           \
+  asm volatile(TEXT                                                                                                     \
+               : "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[0][2]), "+a"(acc[0][3]), "+a"(acc[1][0]), "+a"(acc[1][1]), \
+                 "+a"(acc[1][2]), "+a"(acc[1][3]), "+a"(acc[2][0]), "+a"(acc[2][1]), "+a"(acc[2][2]), "+a"(acc[2][3]), \
+                 "+a"(acc[3][0]), "+a"(acc[3][1]), "+a"(acc[3][2]), "+a"(acc[3][3])                                    \
+               : "v"(aA0), "v"(aB0), "v"(wA), "v"(wB), "v"(gA0), "v"(gB0), "s"(stride32), "s"(baseA), "s"(baseB),      \
+                 "s"(nk), "s"(extraB)                                                                                  \
+               : PRISM_KLOOP4_CLOBBERS)
       constexpr bool kF16 = Mfma<OT>::kIsF16;
       if constexpr (EPI == PRISM_EPI_SWIGLU) {
-        if constexpr (kF16) PRISM_KLOOP("v_mfma_f32_32x32x16_f16", acc, aA0, aB0, gA[0], gB[0], stride, baseA, baseB, nk, ldsA_w, ldsB_w, 16384, 49152);
-        else PRISM_KLOOP("v_mfma_f32_32x32x16_bf16", acc, aA0, aB0, gA[0], gB[0], stride, baseA, baseB, nk, ldsA_w, ldsB_w, 16384, 49152);
+        if constexpr (kF16) PRISM_RUN_KLOOP(PRISM_KLOOP4_F16_SWIGLU);
+        else PRISM_RUN_KLOOP(PRISM_KLOOP4_BF16_SWIGLU);
       } else {
-        if constexpr (kF16) PRISM_KLOOP("v_mfma_f32_32x32x16_f16", acc, aA0, aB0, gA[0], gB[0], stride, baseA, baseB, nk, ldsA_w, ldsB_w, 4096, 36864);
-        else PRISM_KLOOP("v_mfma_f32_32x32x16_bf16", acc, aA0, aB0, gA[0], gB[0], stride, baseA, baseB, nk, ldsA_w, ldsB_w, 4096, 36864);
+        if constexpr (kF16) PRISM_RUN_KLOOP(PRISM_KLOOP4_F16_PLAIN);
+        else PRISM_RUN_KLOOP(PRISM_KLOOP4_BF16_PLAIN);
       }
+#undef PRISM_RUN_KLOOP
     }
   } else {
     vec8 af[2][TM], bfr[2][TN];
@@ -294,7 +311,7 @@ template <typename OT, int EPI>
 static int launch_epi(const OT *A, const OT *W, void *out, int M, int N, int K, hipStream_t s) {
   // big tile when there is enough work to fill 256 CUs with it, else a 128x128 tile
   const int64_t big_tiles = (int64_t)cdiv(M, 256) * cdiv(EPI == PRISM_EPI_SWIGLU ? N / 2 : N, EPI == PRISM_EPI_SWIGLU ? 128 : 256);
-  if (big_tiles >= 256) return launch_cfg<OT, 256, 256, 2, 4, EPI>(A, W, out, M, N, K, s);
+  if (big_tiles >= 256) return launch_cfg<OT, 256, 256, 2, 2, EPI>(A, W, out, M, N, K, s);
   return launch_cfg<OT, 128, 128, 2, 2, EPI>(A, W, out, M, N, K, s);
 }
 
