@@ -146,9 +146,9 @@ def main():
     dom_n = sum(r.kind_launches[dom] for r in reps)
     achieved = dom_fl / dom_ms / 1e9
     op_t = "float" if m.dtype == "fp32" else args.operand
-    roofline = {"bound": "mfma", "kernel": f"gemm_16_kernel<{op_t},256,256,2,4,SWIGLU>", "achieved": round(achieved, 1),
+    roofline = {"bound": "mfma", "kernel": f"gemm_16_kernel<{op_t},256,256,2,2,SWIGLU>", "achieved": round(achieved, 1),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                "traffic": stored_traffic(w.name, f"gemm_16_kernel<{op_t},256,256,2,4,2>"),
+                "traffic": stored_traffic(w.name, f"gemm_16_kernel<{op_t},256,256,2,2,2>"),
                 "flops_per_launch": dom_fl / dom_n, "avg_launch_ms": round(dom_ms / dom_n, 4), "launches": dom_n}
     gemm_ms = sum(r.kind_ms[k] for r in reps for k in range(4))
     gemm_fl = sum(r.kind_flops[k] for r in reps for k in range(4))

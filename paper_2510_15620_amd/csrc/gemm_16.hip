@@ -145,23 +145,18 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_16_kernel(const OT *__restri
       const unsigned ldsA = (unsigned)(uintptr_t)PRISM_LDS_PTR(lA), ldsB = (unsigned)(uintptr_t)PRISM_LDS_PTR(lB);
       const unsigned aA0 = ldsA + (unsigned)(rA[0] * BK + swz(rA[0], khalf) * 8) * 2u;
       const unsigned aB0 = ldsB + (unsigned)(rB[0] * BK + swz(rB[0], khalf) * 8) * 2u;
-      // this thread moves chunk (tid % 8) of tile rows tid / 8 + 32 j, j = 0..7, of A and of the B tile
-      const int crow = tid >> 3, cchunk = tid & 7;
-      const unsigned wA = ldsA + (unsigned)(crow * BK + swz(crow, cchunk) * 8) * 2u;
-      const unsigned wB = ldsB + (unsigned)(crow * BK + swz(crow, cchunk) * 8) * 2u;
-      const unsigned gA0 = ((unsigned)(m0 + crow) * (unsigned)K + cchunk * 8) * 2u;
-      const unsigned gB0 = ((unsigned)(n0 + crow) * (unsigned)K + cchunk * 8) * 2u;
-      const unsigned stride32 = 32u * (unsigned)K * 2u;
-      // SwiGLU: B tile rows 128..255 are W rows F + n0 .., i.e. F - 128 rows beyond where plain striding lands
-      const unsigned extraB = EPI == PRISM_EPI_SWIGLU ? (unsigned)(F - BN / 2) * (unsigned)K * 2u : 0u;
+      // wave w's load instruction j fills tile rows (8 w + j) * 8 .. + 8 of each operand (1 KiB of LDS)
+      const unsigned stride8 = 8u * (unsigned)K * 2u;
+      const unsigned ldsA_w = __builtin_amdgcn_readfirstlane(ldsA + (unsigned)wave * A_ITERS * 8 * BK * 2);
+      const unsigned ldsB_w = __builtin_amdgcn_readfirstlane(ldsB + (unsigned)wave * B_ITERS * 8 * BK * 2);
       const uint64_t baseA = (uint64_t)(uintptr_t)A, baseB = (uint64_t)(uintptr_t)W;
 #define PRISM_RUN_KLOOP(TEXT)                                                                                           \
   asm volatile(TEXT                                                                                                     \
                : "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[0][2]), "+a"(acc[0][3]), "+a"(acc[1][0]), "+a"(acc[1][1]), \
                  "+a"(acc[1][2]), "+a"(acc[1][3]), "+a"(acc[2][0]), "+a"(acc[2][1]), "+a"(acc[2][2]), "+a"(acc[2][3]), \
                  "+a"(acc[3][0]), "+a"(acc[3][1]), "+a"(acc[3][2]), "+a"(acc[3][3])                                    \
-               : "v"(aA0), "v"(aB0), "v"(wA), "v"(wB), "v"(gA0), "v"(gB0), "s"(stride32), "s"(baseA), "s"(baseB),      \
-                 "s"(nk), "s"(extraB)                                                                                  \
+               : "v"(aA0), "v"(aB0), "v"(gA[0]), "v"(gB[0]), "s"(ldsA_w), "s"(ldsB_w), "s"(stride8), "s"(baseA),       \
+                 "s"(baseB), "s"(nk)                                                                                   \
                : PRISM_KLOOP4_CLOBBERS)
       constexpr bool kF16 = Mfma<OT>::kIsF16;
       if constexpr (EPI == PRISM_EPI_SWIGLU) {
