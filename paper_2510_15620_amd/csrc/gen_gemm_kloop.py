@@ -34,7 +34,7 @@ AB = [40 + k for k in range(4)]
 F = [{"A": [64 + 4 * i for i in range(4)], "B": [80 + 4 * j for j in range(4)]},
      {"A": [96 + 4 * i for i in range(4)], "B": [112 + 4 * j for j in range(4)]}]
 CLOBBER_V = list(range(20, 44)) + list(range(64, 128))
-CLOBBER_S = [20, 21, 22, 23, 24, 25, 26, 27, 28]
+CLOBBER_S = [20, 21, 22, 23, 24, 25, 26, 27, 28, 29]
 
 STAGE = 32768                           # bytes per LDS stage of one operand
 A_FRAG_OFF = [0, 4096, 8192, 12288]     # 32 rows x 128 B apart
@@ -68,10 +68,13 @@ def loads(which, stage):
             for j in range(8)]
 
 
-ADVANCE = [  # bases move to the next slice only while that stays inside the operand (s25 = slice index, s26 = last)
-    "s_cmp_lt_u32 s25, s26", "s_cselect_b32 s27, 128, 0", "s_cselect_b32 s28, 1, 0",
-    "s_add_u32 s20, s20, s27", "s_addc_u32 s21, s21, 0", "s_add_u32 s22, s22, s27", "s_addc_u32 s23, s23, 0",
-    "s_add_u32 s25, s25, s28"]
+def advance(which):
+    """Moves one operand's base to the next slice while that stays inside the operand (s25 / s29 = index of the slice the
+    base points at, s26 = last slice)."""
+    idx, lo, hi = ("s25", "s20", "s21") if which == "A" else ("s29", "s22", "s23")
+    return [f"s_cmp_lt_u32 {idx}, s26", "s_cselect_b32 s27, 128, 0", "s_cselect_b32 s28, 1, 0",
+            f"s_add_u32 {lo}, {lo}, s27", f"s_addc_u32 {hi}, {hi}, 0", f"s_add_u32 {idx}, {idx}, s28"]
+
 
 # LDS reads return in order, so lgkmcnt(n) = "all but the n youngest have landed".  The 8 reads of a step's operands
 # (a0,b0,b1,b2,b3,a1,a2,a3) are issued during the step before, one behind every odd MFMA (1,3,..,15), so that LDS sees an
@@ -80,23 +83,27 @@ ADVANCE = [  # bases move to the next slice only while that stays inside the ope
 # MFMA 3 needs b2 -> 4 + 1 = 5; MFMA 4 needs b3 -> 3 + 2 = 5; MFMA 5 needs a1 -> 2 + 2 = 4; MFMA 9 needs a2 -> 1 + 4 = 5;
 # MFMA 13 needs a3 -> 0 + 6 = 6.
 WAITS = {1: 6, 2: 6, 3: 5, 4: 5, 5: 4, 9: 5, 13: 6}
-# last step of a slice: no reads of a next step; after MFMA 8 the barrier and the 8 first reads of the next slice
-WAITS_LAST = {1: 6, 2: 5, 3: 4, 4: 3, 5: 2, 9: 9, 13: 8}
+# last step of a slice: no reads of a next step; everything has landed before the barrier behind MFMA 8 (other waves
+# overwrite this stage right after it)
+WAITS_LAST = {1: 6, 2: 5, 3: 4, 4: 3, 5: 2}
 
 
 def slice_body(mn, cur, b_off):
-    """Slice whose operands sit in LDS stage `cur`; the next slice is loaded into stage 1 - cur."""
+    """Slice t, whose operands sit in LDS stage `cur`.  Stage 1 - cur receives slice t+1: its A half was requested during
+    the last step of slice t-1, its B half is requested here during step 0.  After this slice's barrier stage `cur` is
+    free and the A half of slice t+2 is requested into it."""
     nxt = 1 - cur
     out = []
     order = [(i, j) for i in range(4) for j in range(4)]
     for k in range(4):
         fs = k & 1
         behind_odd = reads(1 - fs, k + 1, cur, b_off) if k < 3 else []          # behind MFMAs 1,3,..,15
-        behind_even = loads("A", nxt) if k == 0 else loads("B", nxt) if k == 1 else []   # behind MFMAs 2,4,..,16
+        behind_even = loads("B", nxt) if k == 0 else []                         # behind MFMAs 2,4,..,16
+        after_barrier = loads("A", cur) if k == 3 else []                       # behind MFMAs 9..16 of the last step
         waits = WAITS if k < 3 else WAITS_LAST
         for m, (i, j) in enumerate(order, start=1):
             if k == 3 and m == 9:
-                out += ["s_waitcnt vmcnt(0)"] + ([] if "nobarrier" in EXP else ["s_barrier"])
+                out += ["s_waitcnt vmcnt(0) lgkmcnt(0)"] + ([] if "nobarrier" in EXP else ["s_barrier"])
                 out += reads(0, 0, nxt, b_off, True)                            # first fragments of the next slice
             if waits.get(m) is not None and "nowaits" not in EXP:
                 out.append(f"s_waitcnt lgkmcnt({waits[m]})")
@@ -105,8 +112,12 @@ def slice_body(mn, cur, b_off):
                 out.append(behind_odd[m // 2])
             elif m % 2 == 0 and behind_even:
                 out.append(behind_even[m // 2 - 1])
-        if k == 1:
-            out += ADVANCE
+            if m >= 9 and after_barrier:
+                out.append(after_barrier[m - 9])
+        if k == 0:
+            out += advance("B")
+        if k == 3:
+            out += advance("A")
     return out
 
 
@@ -120,10 +131,11 @@ def kloop(mn, b_off):
     for j in range(1, 8):
         s += [f"v_add_u32 v{GA[j]}, %22, v{GA[j - 1]}", f"v_add_u32 v{GB[j]}, %22, v{GB[j - 1]}",
               f"v_xor_b32 v{GA[j]}, 64, v{GA[j]}", f"v_xor_b32 v{GB[j]}, 64, v{GB[j]}"]
-    s += ["s_mov_b64 s[20:21], %23", "s_mov_b64 s[22:23], %24", "s_mov_b32 s24, %25", "s_sub_u32 s26, %25, 1", "s_mov_b32 s25, 0"]
+    s += ["s_mov_b64 s[20:21], %23", "s_mov_b64 s[22:23], %24", "s_mov_b32 s24, %25", "s_sub_u32 s26, %25, 1", "s_mov_b32 s25, 0", "s_mov_b32 s29, 0"]
     # ---- prologue: slice 0 -> LDS stage 0, first fragments
-    s += loads("A", 0) + loads("B", 0) + ADVANCE
+    s += loads("A", 0) + loads("B", 0) + advance("A") + advance("B")
     s += ["s_waitcnt vmcnt(0)", "s_barrier"] + reads(0, 0, 0, b_off, True)
+    s += loads("A", 1) + advance("A")                                           # A half of slice 1
     s += ["L_loop_%=:"] + slice_body(mn, 0, b_off)
     s += ["s_sub_u32 s24, s24, 1", "s_cmp_eq_u32 s24, 0", "s_cbranch_scc1 L_done_%="]
     s += slice_body(mn, 1, b_off)
