@@ -194,6 +194,18 @@ int prism_op_qkv_finish(int32_t dtype, void *QKV, const int32_t *pos, int32_t ma
                         float eps, float rope_base, int32_t qk_norm, void *QK, void *Vt, const int32_t *vt_col,
                         int64_t vt_stride, void *stream);
 
+/* The fused form of prism_op_gemm (fp32 store) + prism_op_qkv_finish for the 16-bit modes, which is what prism_select
+ * runs whenever it applies: [Q|K|V] = Xn Wqkv^T with Xn [T, hidden] and Wqkv [(nq+2nkv)*hd, hidden] ([device], dtype),
+ * then per-head RMSNorm (optional) and RoPE on q and k and the transposed half-precision V, all applied to the fp32
+ * accumulators in the GEMM's epilogue (one rounding, no fp32 intermediate in memory).  Outputs, pos, vt_col, gains as
+ * in prism_op_qkv_finish.  Needs head_dim == 128, hidden % 64 == 0 and ceil(T / 256) * (nq + 2 nkv) / 2 >= 256 (one
+ * head per wavefront of a 256 x 256 tile, enough tiles to fill the chip); PRISM_EUNSUPPORTED otherwise.
+ * Synchronises the stream before returning. */
+int prism_op_qkv_project(int32_t dtype, const void *Xn, const void *Wqkv, const int32_t *pos, int32_t max_pos,
+                         const void *q_gain, const void *k_gain, int32_t T, int32_t hidden, int32_t n_q_heads,
+                         int32_t n_kv_heads, int32_t head_dim, float eps, float rope_base, int32_t qk_norm,
+                         void *QK, void *Vt, const int32_t *vt_col, int64_t vt_stride, void *stream);
+
 /* Causal GQA attention within each sequence (no token attends across sequences; Sec. 2.2).
  * cu_seqlens [n_seqs+1] [host]: token offsets of the sequences; out [T, nq*hd] [device] in dtype.
  *   fp32 mode: QK = the finished QKV buffer [T, (nq+2nkv)*hd] (fp32); Vt, vt_col0 ignored.

@@ -21,7 +21,7 @@ FATE_NOT_LIVE, FATE_DROPPED, FATE_DEFERRED, FATE_SELECTED = -1, 0, 1, 2
 MAX_CANDS, MAX_CLUSTERS, MAX_SEQ = 4096, 8, 8192
 
 EXPORTS = ["prism_create", "prism_select", "prism_set_forced_keep", "prism_destroy", "prism_strerror",
-           "prism_last_error", "prism_op_embed", "prism_op_rmsnorm", "prism_op_gemm", "prism_op_qkv_finish",
+           "prism_last_error", "prism_op_embed", "prism_op_rmsnorm", "prism_op_gemm", "prism_op_qkv_finish", "prism_op_qkv_project",
            "prism_op_attention", "prism_op_score", "prism_op_route", "prism_op_compact", "prism_op_topk"]
 
 
@@ -91,6 +91,8 @@ def lib() -> C.CDLL:
         _lib.prism_op_rmsnorm.argtypes = [vp, vp, i32, i32, f32, i32, vp, vp]
         _lib.prism_op_gemm.argtypes = [i32, i32, vp, vp, vp, i32, i32, i32, vp]
         _lib.prism_op_qkv_finish.argtypes = [i32, vp, vp, i32, vp, vp, i32, i32, i32, i32, f32, f32, i32, vp, vp, vp, C.c_int64, vp]
+        _lib.prism_op_qkv_project.argtypes = [i32, vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, f32, f32, i32, vp, vp, vp,
+                                              C.c_int64, vp]
         _lib.prism_op_attention.argtypes = [i32, vp, vp, C.c_int64, C.POINTER(i32), C.POINTER(i32), i32, i32, i32, i32, vp, vp]
         _lib.prism_op_score.argtypes = [vp, vp, i32, i32, vp, vp, vp, i32, f32, vp, vp]
         _lib.prism_op_route.argtypes = [vp, i32, i32, i32, f32, vp, vp, vp]
@@ -249,6 +251,12 @@ def op_qkv_finish(dtype, QKV, pos, max_pos, q_gain, k_gain, nq, nkv, hd, eps, ba
     _check(lib().prism_op_qkv_finish(dtype, _ptr(QKV), _ptr(pos), max_pos, _ptr(q_gain), _ptr(k_gain), QKV.shape[0],
                                      nq, nkv, hd, eps, base, int(qk_norm), _ptr(QK), _ptr(Vt), _ptr(vt_col), vt_stride,
                                      _stream()))
+
+
+def op_qkv_project(Xn, Wqkv, pos, max_pos, q_gain, k_gain, nq, nkv, hd, eps, base, qk_norm, QK, Vt, vt_col, vt_stride):
+    _check(lib().prism_op_qkv_project(_dt(Xn), _ptr(Xn), _ptr(Wqkv), _ptr(pos), max_pos, _ptr(q_gain), _ptr(k_gain),
+                                      Xn.shape[0], Xn.shape[1], nq, nkv, hd, eps, base, int(qk_norm), _ptr(QK), _ptr(Vt),
+                                      _ptr(vt_col), vt_stride, _stream()))
 
 
 def op_attention(dtype, QK, Vt, vt_stride, cu_seqlens, vt_col0, nq, nkv, hd, out):

@@ -85,6 +85,22 @@ int launch_gemm_fp32(int epilogue, const float *A, const float *W, void *out, in
 // 16-bit operands (dtype PRISM_DTYPE_BF16 or PRISM_DTYPE_F16) on the matrix cores
 int launch_gemm_16(int dtype, int epilogue, const void *A, const void *W, void *out, int M, int N, int K, hipStream_t s);
 bool gemm_16_supported(int epilogue, int N, int K);
+// The q/k/v projection with everything that follows it fused into the GEMM epilogue (head_dim 128): per-head RMSNorm
+// (optional) and rotate-half RoPE on the q and k heads, rounded once into QK [T, (nq+nkv)*128]; the v heads rounded to the
+// operand type and written transposed, as IEEE half, to Vt [nkv][128][vt_stride] at column vt_col[t].
+struct QkvEpilogue {
+  const int32_t *pos, *vt_col;
+  const void *q_gain, *k_gain;
+  const float2 *rope_tab;
+  void *QK;
+  void *Vt;
+  int64_t vt_stride;
+  int nq, nkv, qk_norm;
+  float eps;
+};
+static const int kEpiQkv = 4;   // internal epilogue code of launch_gemm_16_qkv
+bool gemm_16_qkv_supported(int M, int nq, int nkv, int hd, int K);
+int launch_gemm_16_qkv(int dtype, const void *Xn, const void *Wqkv, int M, int K, int hd, const QkvEpilogue &e, hipStream_t s);
 
 // cos/sin table for RoPE: tab[pos * (hd/2) + i] = (cos, sin)(pos * base^(-2i/hd)), evaluated in fp64
 int launch_rope_table(float2 *tab, int n_pos, int head_dim, float rope_base, hipStream_t s);

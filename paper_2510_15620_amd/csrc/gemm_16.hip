@@ -37,7 +37,7 @@ __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >>
 template <typename OT, int BM, int BN, int WM, int WN, int EPI>
 __global__ __launch_bounds__(WM *WN * 64) void gemm_16_kernel(const OT *__restrict__ A,
                                                                const OT *__restrict__ W, void *__restrict__ out_,
-                                                               int M, int N, int K, int nM, int nN) {
+                                                               int M, int N, int K, int nM, int nN, QkvEpilogue qe) {
   constexpr int NW = WM * WN;
   constexpr int WMT = BM / WM, WNT = BN / WN;      // wave tile
   constexpr int TM = WMT / 32, TN = WNT / 32;      // 32x32 accumulator tiles per wave
@@ -249,6 +249,65 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_16_kernel(const OT *__restri
               if (col0 + g * 8 + q < N) orow[col0 + g * 8 + q] += acc[i][j][g * 4 + q];
         }
       }
+    } else if (EPI == kEpiQkv) {
+      // The wave's 128 columns are one head.  A row's 128 values sit in lanes l and l ^ 32 (64 each); the rotate-half
+      // partner of column d is d + 64 = the same register of accumulator tile j + 2.
+      if constexpr (EPI == kEpiQkv) {
+        static_assert(WNT == 128 && TN == 4, "one head per wavefront");
+        typedef typename Mfma<OT>::vec4 vec4;
+        const int head = (n0 + wn * WNT) >> 7;                 // wave-uniform
+        if (head < qe.nq + qe.nkv) {
+          float r = 1.f;
+          if (qe.qk_norm) {
+            float ss = 0.f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+              for (int e = 0; e < 16; ++e) ss += acc[i][j][e] * acc[i][j][e];
+            ss += __shfl_xor(ss, 32);
+            r = 1.0f / sqrtf(ss / 128.f + qe.eps);
+          }
+          const OT *gain = reinterpret_cast<const OT *>(head < qe.nq ? qe.q_gain : qe.k_gain);
+          const float2 *tab = qe.rope_tab + (int64_t)qe.pos[row] * 64;
+          OT *orow = reinterpret_cast<OT *>(qe.QK) + (int64_t)row * ((qe.nq + qe.nkv) * 128) + head * 128;
+#pragma unroll
+          for (int j = 0; j < 2; ++j) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+              const int d = j * 32 + g * 8 + n_in;
+              const f32x4 cs01 = *reinterpret_cast<const f32x4 *>(tab + d), cs23 = *reinterpret_cast<const f32x4 *>(tab + d + 2);
+              const float cs[8] = {cs01[0], cs01[1], cs01[2], cs01[3], cs23[0], cs23[1], cs23[2], cs23[3]};
+              vec4 ga, gb, lo, hi;
+              if (qe.qk_norm) {
+                ga = *reinterpret_cast<const vec4 *>(gain + d);
+                gb = *reinterpret_cast<const vec4 *>(gain + d + 64);
+              }
+#pragma unroll
+              for (int q = 0; q < 4; ++q) {
+                float a = acc[i][j][g * 4 + q], b = acc[i][j + 2][g * 4 + q];
+                if (qe.qk_norm) {
+                  a = a * r * to_f32(ga[q]);
+                  b = b * r * to_f32(gb[q]);
+                }
+                lo[q] = from_f32<OT>(a * cs[2 * q] - b * cs[2 * q + 1]);
+                hi[q] = from_f32<OT>(b * cs[2 * q] + a * cs[2 * q + 1]);
+              }
+              *reinterpret_cast<vec4 *>(orow + d) = lo;
+              *reinterpret_cast<vec4 *>(orow + d + 64) = hi;
+            }
+          }
+        } else {
+          // v head: rounded to the operand type, stored as half, transposed (32 consecutive tokens of one d are contiguous)
+          f16 *vt = reinterpret_cast<f16 *>(qe.Vt) + (int64_t)(head - qe.nq - qe.nkv) * 128 * qe.vt_stride + qe.vt_col[row];
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+              const int d = j * 32 + (e >> 2) * 8 + n_in + (e & 3);
+              vt[(int64_t)d * qe.vt_stride] = from_f32<f16>(to_f32(from_f32<OT>(acc[i][j][e])));
+            }
+        }
+      }
     } else {
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
@@ -285,7 +344,8 @@ bool gemm_16_supported(int epilogue, int N, int K) {
 }
 
 template <typename OT, int BM, int BN, int WM, int WN, int EPI>
-static int launch_cfg(const OT *A, const OT *W, void *out, int M, int N, int K, hipStream_t s) {
+static int launch_cfg(const OT *A, const OT *W, void *out, int M, int N, int K, hipStream_t s,
+                      const QkvEpilogue &qe = QkvEpilogue{}) {
   constexpr size_t lds = 2 * (size_t)(BM + BN) * BK * sizeof(OT);
   auto kern = gemm_16_kernel<OT, BM, BN, WM, WN, EPI>;
   static bool attr_set = false;   // the attribute is per function; set it once per process
@@ -297,7 +357,7 @@ static int launch_cfg(const OT *A, const OT *W, void *out, int M, int N, int K, 
   const int ncols = EPI == PRISM_EPI_SWIGLU ? N / 2 : N, bn_out = EPI == PRISM_EPI_SWIGLU ? BN / 2 : BN;
   const int nM = cdiv(M, BM), nN = cdiv(ncols, bn_out);
   const int grid = cdiv((int64_t)nM * nN, 8) * 8;
-  kern<<<grid, WM * WN * 64, lds, s>>>(A, W, out, M, N, K, nM, nN);
+  kern<<<grid, WM * WN * 64, lds, s>>>(A, W, out, M, N, K, nM, nN, qe);
   PRISM_HIP(hipGetLastError());
   return PRISM_OK;
 }
@@ -329,6 +389,26 @@ int launch_gemm_16(int dtype, int epilogue, const void *A, const void *W, void *
   if (M == 0) return PRISM_OK;
   if (dtype == PRISM_DTYPE_BF16) return launch_typed<bf16>(epilogue, (const bf16 *)A, (const bf16 *)W, out, M, N, K, s);
   return launch_typed<f16>(epilogue, (const f16 *)A, (const f16 *)W, out, M, N, K, s);
+}
+
+bool gemm_16_qkv_supported(int M, int nq, int nkv, int hd, int K) {
+  // one head per wavefront of the 256 x 256 tile; smaller problems take the unfused path
+  return hd == 128 && nq > 0 && nkv > 0 && (nq + 2 * nkv) % 2 == 0 && K > 0 && K % BK == 0 &&
+         (int64_t)cdiv(M, 256) * ((nq + 2 * nkv) / 2) >= 256;
+}
+
+int launch_gemm_16_qkv(int dtype, const void *Xn, const void *Wqkv, int M, int K, int hd, const QkvEpilogue &e, hipStream_t s) {
+  PRISM_REQUIRE(Xn && Wqkv && M >= 0 && is16(dtype) && e.pos && e.vt_col && e.rope_tab && e.QK && e.Vt, PRISM_EINVAL,
+                "qkv gemm: bad arguments");
+  PRISM_REQUIRE(!e.qk_norm || (e.q_gain && e.k_gain), PRISM_EINVAL, "qkv gemm: gains missing");
+  PRISM_REQUIRE(gemm_16_qkv_supported(M, e.nq, e.nkv, hd, K), PRISM_EUNSUPPORTED, "qkv gemm: shape not supported by the fused epilogue");
+  const int N = (e.nq + 2 * e.nkv) * 128;
+  PRISM_REQUIRE((int64_t)M * K * 2 < ((int64_t)1 << 32) && (int64_t)N * K * 2 < ((int64_t)1 << 32), PRISM_EUNSUPPORTED,
+                "qkv gemm: an operand exceeds 4 GiB");
+  if (M == 0) return PRISM_OK;
+  if (dtype == PRISM_DTYPE_BF16)
+    return launch_cfg<bf16, 256, 256, 2, 2, kEpiQkv>((const bf16 *)Xn, (const bf16 *)Wqkv, e.QK, M, N, K, s, e);
+  return launch_cfg<f16, 256, 256, 2, 2, kEpiQkv>((const f16 *)Xn, (const f16 *)Wqkv, e.QK, M, N, K, s, e);
 }
 
 }  // namespace prism

@@ -480,10 +480,21 @@ static int run_layer(prism_ctx *c, const Plan &p, const MetaOff &mo, float *X, c
     const double tk = 2.0 * Tc;
     // ---- attention block: X += Attn(RMSNorm(X)) Wo^T
     PRISM_TRY(timed_span(c, 5, 0.0, [&] { return launch_rmsnorm(Xc, wbuf + L.attn_norm, Tc, H, m.rms_eps, c->op, c->Xn, s); }));
+    // 16-bit modes at head_dim 128 with enough rows: norm, RoPE, rounding and the V transposition happen in the
+    // projection's epilogue; otherwise the projection is stored in fp32 and finished by separate kernels
+    const bool fused_qkv = bf && gemm_16_qkv_supported(Tc, m.n_q_heads, m.n_kv_heads, m.head_dim, H);
     PRISM_TRY(timed_span(c, 0, tk * (Dq + 2 * Dkv) * H, [&] {
+      if (fused_qkv) {
+        QkvEpilogue e;
+        e.pos = pos; e.vt_col = c->d_meta + mo.vtcol + ch.r0;
+        e.q_gain = wbuf + L.q_norm; e.k_gain = wbuf + L.k_norm;
+        e.rope_tab = c->rope_tab; e.QK = c->QK; e.Vt = c->Vt; e.vt_stride = c->vt_cap;
+        e.nq = m.n_q_heads; e.nkv = m.n_kv_heads; e.qk_norm = m.qk_norm; e.eps = m.rms_eps;
+        return launch_gemm_16_qkv(c->op, c->Xn, wbuf + L.wqkv, Tc, H, m.head_dim, e, s);
+      }
       return gemm(bf ? PRISM_EPI_STORE_F32 : PRISM_EPI_STORE, c->Xn, wbuf + L.wqkv, c->QKV, Tc, Dq + 2 * Dkv, H);
     }));
-    PRISM_TRY(timed_span(c, 5, 0.0, [&] {
+    if (!fused_qkv) PRISM_TRY(timed_span(c, 5, 0.0, [&] {
       PRISM_TRY(launch_qk_finish(c->op, (float *)c->QKV, pos, wbuf + L.q_norm, wbuf + L.k_norm, Tc, m.n_q_heads,
                                  m.n_kv_heads, m.head_dim, m.rms_eps, m.qk_norm, c->rope_tab, c->QK, s));
       if (bf)
@@ -800,6 +811,27 @@ extern "C" int prism_op_qkv_finish(int32_t dtype, void *QKV, const int32_t *pos,
                              (const float2 *)tab.p, QK, s));
   if (is16(dtype))
     PRISM_TRY(launch_v_finish(dtype, (const float *)QKV, T, n_q_heads, n_kv_heads, head_dim, Vt, vt_col, vt_stride, s));
+  PRISM_HIP(hipStreamSynchronize(s));   // the table is freed on return
+  return PRISM_OK;
+}
+
+extern "C" int prism_op_qkv_project(int32_t dtype, const void *Xn, const void *Wqkv, const int32_t *pos, int32_t max_pos,
+                                    const void *q_gain, const void *k_gain, int32_t T, int32_t hidden, int32_t n_q_heads,
+                                    int32_t n_kv_heads, int32_t head_dim, float eps, float rope_base, int32_t qk_norm,
+                                    void *QK, void *Vt, const int32_t *vt_col, int64_t vt_stride, void *stream) {
+  PRISM_REQUIRE(max_pos > 0 && max_pos <= PRISM_MAX_SEQ, PRISM_EINVAL, "qkv_project: max_pos");
+  PRISM_REQUIRE(is16(dtype) && Xn && Wqkv && pos && QK && Vt && vt_col && vt_stride > 0 && T >= 0, PRISM_EINVAL, "qkv_project: bad arguments");
+  PRISM_REQUIRE(gemm_16_qkv_supported(T, n_q_heads, n_kv_heads, head_dim, hidden), PRISM_EUNSUPPORTED,
+                "qkv_project: needs head_dim 128, hidden a multiple of 64 and at least 256 tiles of 256 x 256 "
+                "(use prism_op_gemm + prism_op_qkv_finish otherwise)");
+  hipStream_t s = (hipStream_t)stream;
+  TmpDev tab;
+  PRISM_TRY(tab.alloc((size_t)max_pos * (head_dim / 2) * sizeof(float2)));
+  PRISM_TRY(launch_rope_table((float2 *)tab.p, max_pos, head_dim, rope_base, s));
+  QkvEpilogue e;
+  e.pos = pos; e.vt_col = vt_col; e.q_gain = q_gain; e.k_gain = k_gain; e.rope_tab = (const float2 *)tab.p;
+  e.QK = QK; e.Vt = Vt; e.vt_stride = vt_stride; e.nq = n_q_heads; e.nkv = n_kv_heads; e.qk_norm = qk_norm; e.eps = eps;
+  PRISM_TRY(launch_gemm_16_qkv(dtype, Xn, Wqkv, T, hidden, head_dim, e, s));
   PRISM_HIP(hipStreamSynchronize(s));   // the table is freed on return
   return PRISM_OK;
 }

@@ -145,6 +145,57 @@ def test_qkv_finish(dtype, nq, nkv, hd, qk_norm):
     assert (vt[:, :, pad] == 0).all()
 
 
+@pytest.mark.parametrize("dtype", SIXTEEN)
+@pytest.mark.parametrize("qk_norm", [True, False])
+def test_qkv_project_fused(dtype, qk_norm):
+    """Projection + norm + RoPE + V transposition in one kernel against the oracle's separate steps, several row
+    tiles with a ragged last one, and against the unfused device path."""
+    nq, nkv, hd, H = 32, 8, 128, 256
+    lens = [700, 1, 1024, 64, 911]
+    T = sum(lens)
+    pos = np.concatenate([np.arange(l) for l in lens]).astype(np.int32)
+    Xn, Wt = _rand((T, H), dtype, 50), _rand(((nq + 2 * nkv) * hd, H), dtype, 51, 1.0 / math.sqrt(H))
+    gq, gk = (1 + _rand((hd,), torch.float32, 52, 0.1)).to(dtype), (1 + _rand((hd,), torch.float32, 53, 0.1)).to(dtype)
+    x = (_f64(Xn) @ _f64(Wt).T).reshape(T, nq + 2 * nkv, hd)
+    q, k, v = x[:, :nq], x[:, nq:nq + nkv], x[:, nq + nkv:]
+    if qk_norm:
+        q, k = O.rmsnorm(q, _f64(gq), 1e-6), O.rmsnorm(k, _f64(gk), 1e-6)
+    q, k = O.rope(q, pos, 1e6), O.rope(k, pos, 1e6)
+    col0, vt_col, ncol = _vt_layout(lens)
+    dpos, dcol = torch.from_numpy(pos).to(DEV), torch.from_numpy(vt_col).to(DEV)
+    QK = torch.zeros(T, (nq + nkv) * hd, dtype=dtype, device=DEV)
+    Vt = torch.zeros(nkv, hd, ncol, dtype=torch.float16, device=DEV)
+    B.op_qkv_project(Xn.to(DEV), Wt.to(DEV), dpos, 1024, gq.to(DEV), gk.to(DEV), nq, nkv, hd, 1e-6, 1e6, qk_norm, QK, Vt, dcol, ncol)
+    ref_qk = np.concatenate([q, k], axis=1).reshape(T, -1)
+    got = _f64(QK)
+    # fp32 accumulation over 256 products, fp32 norm and rotation, then ONE 16-bit rounding
+    np.testing.assert_allclose(got, ref_qk, rtol=EPS16[dtype] * 1.01, atol=2e-6)
+    assert np.mean(got != O.round_operand(ref_qk, OPERAND[dtype])) < 0.02
+    vt = _f64(Vt)
+    ref_v = np.transpose(v, (1, 2, 0))
+    np.testing.assert_allclose(vt[:, :, vt_col], ref_v, rtol=EPS16[dtype] * 1.01, atol=2e-6)
+    pad = np.setdiff1d(np.arange(ncol), vt_col)
+    assert (vt[:, :, pad] == 0).all()
+    # the unfused device path: same arithmetic except the order of the sum of squares
+    QKV = torch.zeros(T, (nq + 2 * nkv) * hd, dtype=torch.float32, device=DEV)
+    B.op_gemm(B.EPI_STORE_F32, Xn.to(DEV), Wt.to(DEV), QKV)
+    QK2, Vt2 = torch.zeros_like(QK), torch.zeros_like(Vt)
+    B.op_qkv_finish(B._dt(QK), QKV, dpos, 1024, gq.to(DEV), gk.to(DEV), nq, nkv, hd, 1e-6, 1e6, qk_norm, QK2, Vt2, dcol, ncol)
+    assert torch.equal(Vt, Vt2)
+    assert (QK != QK2).float().mean().item() < 1e-3
+    np.testing.assert_allclose(_f64(QK), _f64(QK2), rtol=2 * EPS16[dtype] * 1.01, atol=2e-6)   # neighbouring 16-bit values at most
+
+
+def test_qkv_project_rejects_small_problems():
+    Xn, Wt = torch.zeros(100, 256, dtype=torch.float16, device=DEV), torch.zeros(48 * 128, 256, dtype=torch.float16, device=DEV)
+    z = torch.zeros(128, dtype=torch.float16, device=DEV)
+    with pytest.raises(B.PrismError) as e:
+        B.op_qkv_project(Xn, Wt, torch.zeros(100, dtype=torch.int32, device=DEV), 16, z, z, 32, 8, 128, 1e-6, 1e6, True,
+                         torch.zeros(100, 40 * 128, dtype=torch.float16, device=DEV), torch.zeros(8, 128, 128, dtype=torch.float16, device=DEV),
+                         torch.zeros(100, dtype=torch.int32, device=DEV), 128)
+    assert e.value.code == B.EUNSUPPORTED
+
+
 ATTN_CASES = [
     (torch.float32, 4, 2, 64, [1, 17, 64, 100]),
     (torch.float32, 6, 3, 32, [33, 2]),
