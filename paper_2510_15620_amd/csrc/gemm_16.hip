@@ -204,6 +204,42 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_16_kernel(const OT *__restri
   //      are read / written as 16-byte (fp32) or 8-byte (16-bit) vectors.
   const int m_in = lane & 31, n_in = (lane >> 5) * 4;
   const bool full_n = n0 + (EPI == PRISM_EPI_SWIGLU ? BN / 2 : BN) <= F && F % 4 == 0;
+  if constexpr (EPI == PRISM_EPI_RESIDUAL) {
+    if (full_n) {
+      // Read-modify-write of the fp32 stream, software-pipelined over the wave's row blocks: the 16 vector loads of
+      // block i + 1 are in flight while block i is added and stored, so the tile pays the memory latency about twice
+      // instead of once per accumulator tile.
+      f32x4 old[2][TN][4];
+      auto rowptr = [&](int i) {
+        const int row = m0 + wm * WMT + i * 32 + m_in;
+        return reinterpret_cast<float *>(out_) + (int64_t)(row < M ? row : M - 1) * N + n0 + wn * WNT + n_in;
+      };
+      auto load_block = [&](int i, int set) {
+        const float *o = rowptr(i);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) old[set][j][g] = *reinterpret_cast<const f32x4 *>(o + j * 32 + g * 8);
+      };
+      load_block(0, 0);
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        if (i + 1 < TM) load_block(i + 1, (i + 1) & 1);
+        float *o = rowptr(i);
+        const bool live = m0 + wm * WMT + i * 32 + m_in < M;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            f32x4 v = old[i & 1][j][g];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[q] += acc[i][j][g * 4 + q];
+            if (live) *reinterpret_cast<f32x4 *>(o + j * 32 + g * 8) = v;
+          }
+      }
+      return;
+    }
+  }
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int row = m0 + wm * WMT + i * 32 + m_in;
@@ -227,27 +263,13 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_16_kernel(const OT *__restri
         }
       }
     } else if (EPI == PRISM_EPI_RESIDUAL) {
-      float *orow = reinterpret_cast<float *>(out_) + (int64_t)row * N;
+      float *orow = reinterpret_cast<float *>(out_) + (int64_t)row * N;      // ragged N only (see above)
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        // all reads of the tile first, then all writes: the compiler cannot reorder a read-modify-write chain
-        // on one pointer, and 16 dependent round trips per tile would serialise on memory latency
-        f32x4 old[4];
         const int col0 = n0 + wn * WNT + j * 32 + n_in;
-        if (full_n) {
-#pragma unroll
-          for (int g = 0; g < 4; ++g) old[g] = *reinterpret_cast<const f32x4 *>(orow + col0 + g * 8);
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) old[g][q] += acc[i][j][g * 4 + q];
-            *reinterpret_cast<f32x4 *>(orow + col0 + g * 8) = old[g];
-          }
-        } else {
-          for (int g = 0; g < 4; ++g)
-            for (int q = 0; q < 4; ++q)
-              if (col0 + g * 8 + q < N) orow[col0 + g * 8 + q] += acc[i][j][g * 4 + q];
-        }
+        for (int g = 0; g < 4; ++g)
+          for (int q = 0; q < 4; ++q)
+            if (col0 + g * 8 + q < N) orow[col0 + g * 8 + q] += acc[i][j][g * 4 + q];
       }
     } else if (EPI == kEpiQkv) {
       // The wave's 128 columns are one head.  A row's 128 values sit in lanes l and l ^ 32 (64 each); the rotate-half
