@@ -11,7 +11,9 @@
 //                                 accumulator registers themselves, converted to f16)
 // The 32x32 accumulator layout gives lane l the column l % 32 and rows (e/4)*8 + (l/32)*4 + e%4;
 // those rows, read as the 16 contraction slots of the next MFMA, are keys {0-3, 8-11} for the low
-// half-wave and {4-7, 12-15} for the high one, so the V^T operand is fetched in that key order.
+// half-wave and {4-7, 12-15} for the high one.  The V^T tile is stored in LDS with the keys of every group of
+// 16 in exactly that order (0-3, 8-11, 4-7, 12-15), so a lane's operand is ONE 16-byte chunk, and the chunks
+// are XOR-swizzled by bits 1..3 of the row, which spreads the 16 lanes served per cycle over all 64 banks.
 // Online softmax needs one cross-lane exchange (l <-> l ^ 32) per K/V tile.
 // q and k come from the finished [T, (nq + nkv) * hd] buffer in the operand type OT (bf16 or IEEE half).
 // V^T comes from the [kv head][d][column] buffer of the V finishing step, always IEEE half: the
@@ -34,7 +36,7 @@ __global__ __launch_bounds__(512) void attention_16_kernel(const OT *__restrict_
   constexpr int QB = 8 / G;              // 32-query blocks per item
   constexpr int BQ = 32 * QB;
   __shared__ __align__(16) OT lK[2][BKV * HD];       // [key][d], 16 chunks per row, swizzled
-  __shared__ __align__(16) f16 lV[2][HD * BKV];      // [d][key], 8 chunks per row, swizzled
+  __shared__ __align__(16) f16 lV[2][HD * BKV];      // [d][key, permuted within groups of 16], 8 chunks per row, swizzled
 
   const AttnTile it = tiles[blockIdx.x];
   const int kvh = blockIdx.y;
@@ -67,9 +69,10 @@ __global__ __launch_bounds__(512) void attention_16_kernel(const OT *__restrict_
     krow[i] = kr;
     gK[i] = QK + (int64_t)(nq + kvh) * HD + kc * 8;               // + (seq_row0 + key) * row_elems later
     sK[i] = kr * HD + ((kc ^ (kr & 15)) * 8);
-    const int vr = c / 8, vc = c % 8;                              // V^T: d row, chunk of 8 keys
+    const int vr = c / 8, vc = c % 8;                              // V^T: d row, 8 consecutive keys
     gV[i] = Vt + ((int64_t)kvh * HD + vr) * vt_stride + it.vt_col0 + vc * 8;
-    sV[i] = vr * BKV + ((vc ^ (vr & 7)) * 8);
+    // keys 0-3 of the 8 go to chunk 2*(vc/2), keys 4-7 to chunk 2*(vc/2)+1, both at half vc % 2
+    sV[i] = vr * BKV + ((((vc & ~1)) ^ ((vr >> 1) & 7)) * 8) + (vc & 1) * 4;
   }
   auto load_tile = [&](int kt, vec8 (&rk)[2], f16x8 (&rv)[2]) {
 #pragma unroll
@@ -84,7 +87,11 @@ __global__ __launch_bounds__(512) void attention_16_kernel(const OT *__restrict_
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       *reinterpret_cast<vec8 *>(&lK[buf][sK[i]]) = rk[i];
-      *reinterpret_cast<f16x8 *>(&lV[buf][sV[i]]) = rv[i];
+      f16x4 lo4, hi4;
+      lo4[0] = rv[i][0]; lo4[1] = rv[i][1]; lo4[2] = rv[i][2]; lo4[3] = rv[i][3];
+      hi4[0] = rv[i][4]; hi4[1] = rv[i][5]; hi4[2] = rv[i][6]; hi4[3] = rv[i][7];
+      *reinterpret_cast<f16x4 *>(&lV[buf][sV[i]]) = lo4;
+      *reinterpret_cast<f16x4 *>(&lV[buf][sV[i] ^ 8]) = hi4;          // the neighbouring chunk (chunk index ^ 1)
     }
   };
 
@@ -152,23 +159,21 @@ __global__ __launch_bounds__(512) void attention_16_kernel(const OT *__restrict_
         }
       l_run = l_run * alpha + psum;
       m_run = m_new;
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {      // the running maxima usually settle after a few tiles
 #pragma unroll
-      for (int t = 0; t < HD / 32; ++t)
+        for (int t = 0; t < HD / 32; ++t)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
+          for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
+      }
       // ---- O^T += V^T P^T
 #pragma unroll
       for (int t = 0; t < HD / 32; ++t) {
         const int r = t * 32 + (lane & 31);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-          // contraction slots 0-3 <- keys ks*16 + (lane/32)*4 .. +4 ; slots 4-7 <- the same + 8
-          const int c0 = ks * 2, c1 = ks * 2 + 1, half = (lane >> 5) * 4;
-          const f16x4 v0 = *reinterpret_cast<const f16x4 *>(&lV[cur][r * BKV + ((c0 ^ (r & 7)) * 8) + half]);
-          const f16x4 v1 = *reinterpret_cast<const f16x4 *>(&lV[cur][r * BKV + ((c1 ^ (r & 7)) * 8) + half]);
-          f16x8 vf;
-          vf[0] = v0[0]; vf[1] = v0[1]; vf[2] = v0[2]; vf[3] = v0[3];
-          vf[4] = v1[0]; vf[5] = v1[1]; vf[6] = v1[2]; vf[7] = v1[3];
+          // contraction slots 0-3 <- keys ks*16 + (lane/32)*4 .. +4 ; slots 4-7 <- the same + 8: chunk 2 ks + lane/32
+          const int ch = ks * 2 + (lane >> 5);
+          const f16x8 vf = *reinterpret_cast<const f16x8 *>(&lV[cur][r * BKV + ((ch ^ ((r >> 1) & 7)) * 8)]);
           o[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf[ks], o[t], 0, 0, 0);
         }
       }
