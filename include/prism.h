@@ -74,12 +74,15 @@ typedef struct {
 } prism_layer_weights;
 
 typedef struct {
-  const void *embed;                  /* [device] [vocab, hidden] */
+  const void *embed;                  /* [vocab, hidden]; [device] if embed_residency == 0, [pinned host] if 1 */
   const prism_layer_weights *layers;  /* [host] array of n_layers structs; the tensor pointers inside are
                                          [device] if layer_residency == 0, [pinned host] if 1 */
   const void *final_norm;             /* [device] [hidden] */
-  const void *w_yes, *w_no;           /* [device] [hidden] each (a tied head points into embed rows) */
+  const void *w_yes, *w_no;           /* [device] [hidden] each (a tied head points into embed rows, or at device
+                                         copies of the two rows when the table stays on the host) */
   int32_t layer_residency;            /* 0: device; 1: pinned host, streamed one layer ahead (Sec. 4.2) */
+  int32_t embed_residency;            /* 0: device; 1: pinned host (allocated by hipHostMalloc, so that kernels can read
+                                         it), rows fetched on demand into a device LRU cache (Sec. 4.4) */
 } prism_weights;
 
 typedef struct {
@@ -93,6 +96,10 @@ typedef struct {
   void   *stream;                     /* hipStream_t of the caller, or NULL for a library-owned stream */
   int32_t operand;                    /* bf16 weights only: 0 or PRISM_DTYPE_F16 = IEEE half operands (default),
                                          PRISM_DTYPE_BF16 = bf16 operands */
+  int32_t offload_hidden;             /* Sec. 4.3, second half: 1 = the residual stream of the whole pool lives in
+                                         library-owned pinned host memory and at most three chunks of it are on the
+                                         device (computing / being written back / being prefetched); needs chunk_cands > 0 */
+  int32_t embed_cache_rows;           /* embed_residency == 1: rows of the device LRU cache; 0 -> vocab / 10 */
 } prism_options;
 
 /* Optional per-call record.  The caller allocates every array ([host]); an "event" is one
@@ -127,6 +134,9 @@ typedef struct {
   int32_t  kind_launches[PRISM_N_KINDS];
   double   kind_ms[PRISM_N_KINDS];
   double   kind_flops[PRISM_N_KINDS];
+  int64_t  bytes_hidden_moved;  /* out: residual-stream bytes copied device->host and host->device (offload_hidden) */
+  int64_t  embed_rows_hit;      /* out: token occurrences whose embedding row was in the device cache (embed_residency 1) */
+  int64_t  embed_rows_missed;   /* out: token occurrences whose row was fetched from the host table during the call */
 } prism_report;
 
 /* Build a context.  Device-resident layer weights are repacked once into library-owned HBM

@@ -425,6 +425,31 @@ def score_trajectory(query_tokens, cand, weights, m: Model, at_layers: Sequence[
     return out
 
 
+class LruRowCache:
+    """Embedding-table cache of Sec. 4.4: a fixed number of table rows kept by least-recently-used replacement.
+    Textbook LRU over the stream of token ids, in the order the tokens are embedded (sequence by sequence, position by
+    position); the cache persists from one request to the next.  `access` returns True on a hit."""
+
+    def __init__(self, capacity: int):
+        assert capacity >= 1
+        self.capacity = capacity
+        self.order: List[int] = []          # least recently used first
+
+    def access(self, token: int) -> bool:
+        hit = token in self.order
+        if hit:
+            self.order.remove(token)
+        elif len(self.order) == self.capacity:
+            self.order.pop(0)
+        self.order.append(token)
+        return hit
+
+    def run(self, tokens: Sequence[int]) -> tuple:
+        """(hits, misses) of a token stream, updating the cache."""
+        hits = sum(self.access(int(t)) for t in tokens)
+        return hits, len(tokens) - hits
+
+
 def goodman_kruskal_gamma(a: Sequence[float], b: Sequence[float]) -> float:
     """(N_c - N_d) / (N_c + N_d) over candidate pairs (Sec. 3.1): concordant pairs keep
     their relative order between score vectors a and b, discordant pairs reverse it."""

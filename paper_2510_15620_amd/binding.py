@@ -45,13 +45,13 @@ class prism_layer_weights(C.Structure):
 
 class prism_weights(C.Structure):
     _fields_ = [("embed", C.c_void_p), ("layers", C.POINTER(prism_layer_weights)), ("final_norm", C.c_void_p),
-                ("w_yes", C.c_void_p), ("w_no", C.c_void_p), ("layer_residency", C.c_int32)]
+                ("w_yes", C.c_void_p), ("w_no", C.c_void_p), ("layer_residency", C.c_int32), ("embed_residency", C.c_int32)]
 
 
 class prism_options(C.Structure):
     _fields_ = [("checkpoint_layers", C.POINTER(C.c_int32)), ("n_checkpoints", C.c_int32), ("cv_threshold", C.c_float),
                 ("n_clusters", C.c_int32), ("mode", C.c_int32), ("chunk_cands", C.c_int32), ("hbm_cap_bytes", C.c_int64),
-                ("stream", C.c_void_p), ("operand", C.c_int32)]
+                ("stream", C.c_void_p), ("operand", C.c_int32), ("offload_hidden", C.c_int32), ("embed_cache_rows", C.c_int32)]
 
 
 class prism_report(C.Structure):
@@ -64,7 +64,8 @@ class prism_report(C.Structure):
                 ("ms_total", C.c_double), ("ms_layers", C.c_double), ("ms_checks", C.c_double),
                 ("token_layers", C.c_int64), ("peak_hbm_bytes", C.c_int64), ("bytes_streamed", C.c_int64),
                 ("layers_run", C.c_int32), ("kind_launches", C.c_int32 * 6), ("kind_ms", C.c_double * 6),
-                ("kind_flops", C.c_double * 6)]
+                ("kind_flops", C.c_double * 6), ("bytes_hidden_moved", C.c_int64), ("embed_rows_hit", C.c_int64),
+                ("embed_rows_missed", C.c_int64)]
 
 
 _lib = None
@@ -143,6 +144,9 @@ class Report:
     kind_launches: List[int] = field(default_factory=list)   # QKV, O, gate/up, down GEMMs, attention, elementwise
     kind_ms: List[float] = field(default_factory=list)
     kind_flops: List[float] = field(default_factory=list)
+    bytes_hidden_moved: int = 0
+    embed_rows_hit: int = 0
+    embed_rows_missed: int = 0
 
 
 class Prism:
@@ -150,11 +154,14 @@ class Prism:
 
     def __init__(self, model, weights, *, checkpoints: Sequence[int] = (), cv_threshold: float = 0.0, n_clusters: int = 3,
                  mode: int = MODE_DROP_ONLY, chunk_cands: int = 0, hbm_cap_bytes: int = 0, stream_weights: bool = False,
-                 stream: Optional[int] = None, operand: str = "f16"):
+                 stream: Optional[int] = None, operand: str = "f16", offload_hidden: bool = False, embed_on_host: bool = False,
+                 embed_cache_rows: int = 0):
         """model: object with n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, rms_eps, rope_base,
         qk_norm, dtype ("fp32" | "bf16": storage type of the weights).  operand ("f16" | "bf16"): 16-bit type of the
         matrix-core operands when the weights are bf16.  weights: object with embed, final_norm, w_yes, w_no (device tensors) and
-        layers: list of dicts of tensors (device, or pinned host when stream_weights)."""
+        layers: list of dicts of tensors (device, or pinned host when stream_weights).  embed_on_host: weights.embed is a
+        pinned host tensor (w_yes / w_no stay device tensors) read through a device LRU cache of embed_cache_rows rows.
+        offload_hidden: the residual stream lives in pinned host memory, three chunks at a time on the device."""
         self._ctx = C.c_void_p()
         m = prism_model(model.n_layers, model.hidden, model.n_q_heads, model.n_kv_heads, model.head_dim, model.ffn,
                         model.vocab, model.rms_eps, model.rope_base, DTYPE_FP32 if model.dtype == "fp32" else DTYPE_BF16,
@@ -165,10 +172,11 @@ class Prism:
                 setattr(layers[l], n, _ptr(lw[n]))
         self._keep = (weights, layers)      # borrowed by the library for the context's lifetime
         w = prism_weights(_ptr(weights.embed), layers, _ptr(weights.final_norm), _ptr(weights.w_yes), _ptr(weights.w_no),
-                          1 if stream_weights else 0)
+                          1 if stream_weights else 0, 1 if embed_on_host else 0)
         ck, ckp = _i32_array(list(checkpoints))
         o = prism_options(ckp, len(ck), cv_threshold, n_clusters, mode, chunk_cands, hbm_cap_bytes,
-                          _stream() if stream is None else stream, DTYPE_BF16 if operand == "bf16" else DTYPE_F16)
+                          _stream() if stream is None else stream, DTYPE_BF16 if operand == "bf16" else DTYPE_F16,
+                          int(offload_hidden), embed_cache_rows)
         self.n_checkpoints = len(ck)
         _check(lib().prism_create(C.byref(m), C.byref(w), C.byref(o), C.byref(self._ctx)))
 
@@ -205,7 +213,8 @@ class Prism:
                        arrs["gate"][:e].astype(bool), arrs["n_clusters"][:e], arrs["mean"][:e], arrs["std"][:e],
                        arrs["scores"][:e], arrs["fate"][:e], rep.ms_total, rep.ms_layers, rep.ms_checks,
                        rep.token_layers, rep.peak_hbm_bytes, rep.bytes_streamed, rep.layers_run,
-                       list(rep.kind_launches), list(rep.kind_ms), list(rep.kind_flops))
+                       list(rep.kind_launches), list(rep.kind_ms), list(rep.kind_flops), rep.bytes_hidden_moved,
+                       rep.embed_rows_hit, rep.embed_rows_missed)
         return out_idx[:k].copy(), out_scores[:k].copy(), r
 
     def set_forced_keep(self, masks: Optional[np.ndarray]):

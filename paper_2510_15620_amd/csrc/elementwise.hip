@@ -101,6 +101,23 @@ int launch_rope_table(float2 *tab, int n_pos, int head_dim, float rope_base, hip
   return PRISM_OK;
 }
 
+// Row copy between two tables by index lists: one workgroup per row, 16 bytes per lane and step.
+__global__ __launch_bounds__(256) void copy_rows_kernel(const uint4 *__restrict__ src, const int32_t *__restrict__ src_idx,
+                                                        uint4 *__restrict__ dst, const int32_t *__restrict__ dst_idx, int vecs) {
+  const uint4 *a = src + (int64_t)src_idx[blockIdx.x] * vecs;
+  uint4 *b = dst + (int64_t)dst_idx[blockIdx.x] * vecs;
+  for (int i = threadIdx.x; i < vecs; i += 256) b[i] = a[i];
+}
+
+int launch_copy_rows(const void *src, const int32_t *src_idx, void *dst, const int32_t *dst_idx, int n, size_t row_bytes,
+                     hipStream_t s) {
+  PRISM_REQUIRE(src && src_idx && dst && dst_idx && n >= 0 && row_bytes % 16 == 0, PRISM_EINVAL, "copy_rows: bad arguments");
+  if (n == 0) return PRISM_OK;
+  copy_rows_kernel<<<n, 256, 0, s>>>((const uint4 *)src, src_idx, (uint4 *)dst, dst_idx, (int)(row_bytes / 16));
+  PRISM_HIP(hipGetLastError());
+  return PRISM_OK;
+}
+
 // Per-head RMSNorm (optional) then rotate-half RoPE on the q and k parts of the fp32 projection
 // QKV [T, (nq + 2 nkv) * hd].  One wavefront per (token, head); lane i owns pairs (i, i + hd/2),
 // (i + 64, i + 64 + hd/2), ...  The result is rounded ONCE, to the operand type of the QK^T

@@ -119,6 +119,31 @@ struct prism_ctx {
   char *h_res = nullptr;                          // pinned: scores, fate, stats, topk
   std::vector<int8_t> forced; int forced_events = 0, forced_cands = 0;
   int64_t bytes_now = 0, bytes_peak = 0;
+
+  // hidden-state offload (Sec. 4.3): the residual stream of the whole pool in pinned host memory, three chunk-sized
+  // device slots: one computing, one being written back, one being prefetched
+  bool offload = false;
+  float *Xo[3] = {nullptr, nullptr, nullptr};
+  int64_t xo_cap = 0;                             // tokens per slot
+  float *h_X = nullptr; int64_t hx_cap = 0;       // pinned, tokens
+  std::vector<int64_t> hrow;                      // first row in h_X of every ORIGINAL candidate
+  hipStream_t xin_stream = nullptr, xout_stream = nullptr;
+  hipEvent_t ev_in[3] = {nullptr, nullptr, nullptr}, ev_done[3] = {nullptr, nullptr, nullptr}, ev_out[3] = {nullptr, nullptr, nullptr};
+  int64_t ostep = 0;                              // pipeline step = chunk visits so far; slot = ostep % 3
+  bool primed = false;                            // the next step's prefetch has been issued
+  int64_t bytes_hidden = 0;
+
+  // embedding-table cache (Sec. 4.4): table in pinned host memory, least-recently-used rows on the device
+  bool embed_cached = false;
+  const void *embed_dev_alias = nullptr;          // device-visible address of the pinned table
+  int cache_rows = 0;
+  char *d_cache = nullptr;                        // [cache_rows, hidden] in the model dtype
+  std::vector<int32_t> slot_of, tok_of, lru_prev, lru_next;   // token -> slot, slot -> token, recency list
+  int lru_head = -1, lru_tail = -1;               // most / least recently used slot
+  std::vector<int64_t> pin;                       // slot -> pass that last touched it
+  int64_t pass_id = 0;
+  int32_t *h_estage = nullptr, *d_estage = nullptr; int64_t estage_cap = 0, h_estage_cap = 0;   // [slot per row | miss tokens | miss slots]
+  int64_t embed_hit = 0, embed_miss = 0;
 };
 
 namespace prism {
@@ -207,6 +232,31 @@ extern "C" int prism_create(const prism_model *model, const prism_weights *weigh
   PRISM_REQUIRE(options->chunk_cands >= 0 && options->hbm_cap_bytes >= 0, PRISM_EINVAL, "prism_create: negative option");
   PRISM_REQUIRE(options->operand == 0 || options->operand == PRISM_DTYPE_F16 || options->operand == PRISM_DTYPE_BF16,
                 PRISM_EINVAL, "prism_create: operand must be 0, PRISM_DTYPE_F16 or PRISM_DTYPE_BF16");
+  PRISM_REQUIRE(weights->embed_residency == 0 || weights->embed_residency == 1, PRISM_EINVAL, "prism_create: embed_residency");
+  PRISM_REQUIRE(options->offload_hidden == 0 || options->offload_hidden == 1, PRISM_EINVAL, "prism_create: offload_hidden");
+  PRISM_REQUIRE(!options->offload_hidden || options->chunk_cands > 0, PRISM_EINVAL,
+                "prism_create: offload_hidden needs chunked execution (chunk_cands > 0)");
+  PRISM_REQUIRE(options->embed_cache_rows >= 0, PRISM_EINVAL, "prism_create: embed_cache_rows");
+  const void *embed_alias = nullptr;
+  if (weights->embed_residency == 1) {
+    // kernels read the table in place, so it has to be pinned memory that is mapped into the device's address space
+    hipPointerAttribute_t at;
+    hipError_t pe = hipPointerGetAttributes(&at, weights->embed);
+    if (pe != hipSuccess) (void)hipGetLastError();
+    PRISM_REQUIRE(pe == hipSuccess && at.type == hipMemoryTypeHost, PRISM_EINVAL,
+                  "prism_create: embed_residency = 1 needs a table in pinned host memory (hipHostMalloc)");
+    void *dp = nullptr;
+    pe = hipHostGetDevicePointer(&dp, const_cast<void *>(weights->embed), 0);
+    if (pe != hipSuccess) (void)hipGetLastError();
+    PRISM_REQUIRE(pe == hipSuccess && dp, PRISM_EINVAL, "prism_create: the pinned embedding table is not mapped for the device");
+    embed_alias = dp;
+    for (const void *hp : {weights->w_yes, weights->w_no}) {
+      pe = hipPointerGetAttributes(&at, hp);
+      if (pe != hipSuccess) (void)hipGetLastError();
+      PRISM_REQUIRE(pe == hipSuccess && at.type == hipMemoryTypeDevice, PRISM_EINVAL,
+                    "prism_create: w_yes / w_no must be device memory when the embedding table stays on the host");
+    }
+  }
   for (int l = 0; l < model->n_layers; ++l) {
     const prism_layer_weights &w = weights->layers[l];
     PRISM_REQUIRE(w.attn_norm && w.wq && w.wk && w.wv && w.wo && w.ffn_norm && w.w_gate && w.w_up && w.w_down &&
@@ -232,6 +282,9 @@ extern "C" int prism_create(const prism_model *model, const prism_weights *weigh
   c->embed = weights->embed; c->final_norm = weights->final_norm; c->w_yes = weights->w_yes; c->w_no = weights->w_no;
   c->streamed = weights->layer_residency == 1;
   c->host_layers.assign(weights->layers, weights->layers + model->n_layers);
+  c->offload = options->offload_hidden == 1;
+  c->embed_cached = weights->embed_residency == 1;
+  c->embed_dev_alias = embed_alias;
 
   auto fail = [&](int rc) { prism_destroy(c); return rc; };
 #define CREATE_TRY(x) do { int rc__ = (x); if (rc__ != PRISM_OK) return fail(rc__); } while (0)
@@ -260,6 +313,27 @@ extern "C" int prism_create(const prism_model *model, const prism_weights *weigh
   CREATE_TRY(dev_alloc(c, (void **)&c->d_top_pos, PRISM_MAX_CANDS * sizeof(int32_t)));
   CREATE_TRY(dev_alloc(c, (void **)&c->d_top_scores, PRISM_MAX_CANDS * sizeof(float)));
   CREATE_HIP(hipHostMalloc((void **)&c->h_res, PRISM_MAX_CANDS * 16 + 256, hipHostMallocDefault));
+  if (c->offload) {
+    CREATE_HIP(hipStreamCreateWithFlags(&c->xin_stream, hipStreamNonBlocking));
+    CREATE_HIP(hipStreamCreateWithFlags(&c->xout_stream, hipStreamNonBlocking));
+    for (int i = 0; i < 3; ++i) {
+      CREATE_HIP(hipEventCreateWithFlags(&c->ev_in[i], hipEventDisableTiming));
+      CREATE_HIP(hipEventCreateWithFlags(&c->ev_done[i], hipEventDisableTiming));
+      CREATE_HIP(hipEventCreateWithFlags(&c->ev_out[i], hipEventDisableTiming));
+    }
+  }
+  if (c->embed_cached) {
+    c->cache_rows = options->embed_cache_rows > 0 ? std::min(options->embed_cache_rows, model->vocab) : std::max(model->vocab / 10, 1);
+    CREATE_TRY(dev_alloc(c, (void **)&c->d_cache, (size_t)c->cache_rows * model->hidden * dtype_size(model->dtype)));
+    c->slot_of.assign(model->vocab, -1);
+    c->tok_of.assign(c->cache_rows, -1);
+    c->pin.assign(c->cache_rows, -1);
+    c->lru_prev.resize(c->cache_rows);
+    c->lru_next.resize(c->cache_rows);
+    for (int i = 0; i < c->cache_rows; ++i) { c->lru_prev[i] = i - 1; c->lru_next[i] = i + 1 < c->cache_rows ? i + 1 : -1; }
+    c->lru_head = 0;
+    c->lru_tail = c->cache_rows - 1;
+  }
   CREATE_HIP(hipStreamSynchronize(c->stream));
 #undef CREATE_TRY
 #undef CREATE_HIP
@@ -271,7 +345,16 @@ extern "C" void prism_destroy(prism_ctx *c) {
   if (!c) return;
   if (c->stream) (void)hipStreamSynchronize(c->stream);
   if (c->copy_stream) (void)hipStreamSynchronize(c->copy_stream);
+  if (c->xin_stream) (void)hipStreamSynchronize(c->xin_stream);
+  if (c->xout_stream) (void)hipStreamSynchronize(c->xout_stream);
   for (char *p : c->layer_buf) if (p) (void)hipFree(p);
+  for (void *p : {(void *)c->Xo[0], (void *)c->Xo[1], (void *)c->Xo[2], (void *)c->d_cache, (void *)c->d_estage}) if (p) (void)hipFree(p);
+  if (c->h_X) (void)hipHostFree(c->h_X);
+  if (c->h_estage) (void)hipHostFree(c->h_estage);
+  for (int i = 0; i < 3; ++i)
+    for (hipEvent_t e : {c->ev_in[i], c->ev_done[i], c->ev_out[i]}) if (e) (void)hipEventDestroy(e);
+  if (c->xin_stream) (void)hipStreamDestroy(c->xin_stream);
+  if (c->xout_stream) (void)hipStreamDestroy(c->xout_stream);
   void *ptrs[] = {c->rope_tab, c->X[0], c->X[1], c->Xn, c->QKV, c->QK, c->Vt, c->AO, c->S, c->d_meta, c->d_scores, c->d_fate,
                   c->d_stats, c->route_ws, c->d_top_pos, c->d_top_scores};
   for (void *p : ptrs) if (p) (void)hipFree(p);
@@ -382,8 +465,33 @@ static int ensure_scratch(prism_ctx *c, const Plan &p, bool need_second_x, int n
   const prism_model &m = c->m;
   const size_t e = dtype_size(m.dtype);
   const int64_t Dq = (int64_t)m.n_q_heads * m.head_dim, Dkv = (int64_t)m.n_kv_heads * m.head_dim;
-  PRISM_TRY(grow(c, &c->X[0], &c->x_cap[0], p.T, (size_t)m.hidden * 4));
-  if (need_second_x) PRISM_TRY(grow(c, &c->X[1], &c->x_cap[1], p.T, (size_t)m.hidden * 4));
+  if (c->offload) {
+    if (p.max_chunk_tokens > c->xo_cap) {
+      PRISM_HIP(hipDeviceSynchronize());
+      for (int i = 0; i < 3; ++i) { dev_free(c, c->Xo[i], (size_t)c->xo_cap * m.hidden * 4); c->Xo[i] = nullptr; }
+      c->xo_cap = 0;
+      for (int i = 0; i < 3; ++i) PRISM_TRY(dev_alloc(c, (void **)&c->Xo[i], (size_t)p.max_chunk_tokens * m.hidden * 4));
+      c->xo_cap = p.max_chunk_tokens;
+    }
+    if (p.T > c->hx_cap) {
+      PRISM_HIP(hipDeviceSynchronize());
+      if (c->h_X) { (void)hipHostFree(c->h_X); c->h_X = nullptr; c->hx_cap = 0; }
+      PRISM_HIP(hipHostMalloc((void **)&c->h_X, (size_t)p.T * m.hidden * 4, hipHostMallocDefault));
+      c->hx_cap = p.T;
+    }
+  } else {
+    PRISM_TRY(grow(c, &c->X[0], &c->x_cap[0], p.T, (size_t)m.hidden * 4));
+    if (need_second_x) PRISM_TRY(grow(c, &c->X[1], &c->x_cap[1], p.T, (size_t)m.hidden * 4));
+  }
+  if (c->embed_cached) {
+    const int64_t words = 3 * round_up(p.T, 64);
+    PRISM_TRY(grow(c, &c->d_estage, &c->estage_cap, words, 4));
+    if (words > c->h_estage_cap) {
+      if (c->h_estage) { PRISM_HIP(hipStreamSynchronize(c->stream)); (void)hipHostFree(c->h_estage); c->h_estage = nullptr; c->h_estage_cap = 0; }
+      PRISM_HIP(hipHostMalloc((void **)&c->h_estage, (size_t)words * 4, hipHostMallocDefault));
+      c->h_estage_cap = words;
+    }
+  }
   if (p.max_chunk_tokens > c->chunk_cap) {
     PRISM_HIP(hipStreamSynchronize(c->stream));
     const int64_t old = c->chunk_cap, cap = p.max_chunk_tokens;
@@ -461,7 +569,122 @@ static int timed_span(prism_ctx *c, int kind, double flops, Fn body) {
   return PRISM_OK;
 }
 
-static int run_layer(prism_ctx *c, const Plan &p, const MetaOff &mo, float *X, const char *wbuf) {
+// ---- embedding (Sec. 4.5 step 1), optionally through the device row cache (Sec. 4.4)
+static void lru_touch(prism_ctx *c, int s) {          // slot s becomes the most recently used
+  if (c->lru_head == s) return;
+  const int a = c->lru_prev[s], b = c->lru_next[s];
+  if (a >= 0) c->lru_next[a] = b;
+  if (b >= 0) c->lru_prev[b] = a; else c->lru_tail = a;
+  c->lru_prev[s] = -1;
+  c->lru_next[s] = c->lru_head;
+  c->lru_prev[c->lru_head] = s;
+  c->lru_head = s;
+}
+
+// X[0 .. n) = embedding rows of the packed tokens [r0, r0 + n) (host copy tok, device copy d_tok), on stream s.
+// With the cache: a textbook LRU over the token stream.  Rows are gathered from the cache in passes: a pass ends when
+// the least recently used slot is one that this pass still needs, so no row is evicted before it has been gathered.
+static int embed_range(prism_ctx *c, const int32_t *tok, const int32_t *d_tok, int64_t r0, int64_t n, int64_t T, float *X,
+                       hipStream_t s) {
+  const prism_model &m = c->m;
+  if (!c->embed_cached) return launch_embed(d_tok + r0, (int)n, c->embed, m.hidden, m.dtype, X, s);
+  const int64_t Tp = round_up(T, 64);
+  int32_t *h_slot = c->h_estage, *h_mtok = c->h_estage + Tp, *h_mslot = c->h_estage + 2 * Tp;
+  int32_t *d_slot = c->d_estage, *d_mtok = c->d_estage + Tp, *d_mslot = c->d_estage + 2 * Tp;
+  // the miss lists of this range live at [r0, r0 + n) of their regions too (a range has at most n misses), so ranges
+  // and passes never share staging memory and nothing has to be synchronised before the call returns
+  int64_t pass_begin = r0, miss_begin = r0, miss_end = r0;
+  auto flush = [&](int64_t end) -> int {
+    if (end == pass_begin) return PRISM_OK;
+    const int64_t nm = miss_end - miss_begin;
+    PRISM_HIP(hipMemcpyAsync(d_slot + pass_begin, h_slot + pass_begin, (size_t)(end - pass_begin) * 4, hipMemcpyHostToDevice, s));
+    if (nm > 0) {
+      PRISM_HIP(hipMemcpyAsync(d_mtok + miss_begin, h_mtok + miss_begin, (size_t)nm * 4, hipMemcpyHostToDevice, s));
+      PRISM_HIP(hipMemcpyAsync(d_mslot + miss_begin, h_mslot + miss_begin, (size_t)nm * 4, hipMemcpyHostToDevice, s));
+      PRISM_TRY(launch_copy_rows(c->embed_dev_alias, d_mtok + miss_begin, c->d_cache, d_mslot + miss_begin, (int)nm,
+                                 (size_t)m.hidden * dtype_size(m.dtype), s));
+    }
+    PRISM_TRY(launch_embed(d_slot + pass_begin, (int)(end - pass_begin), c->d_cache, m.hidden, m.dtype, X + (pass_begin - r0) * m.hidden, s));
+    pass_begin = end;
+    miss_begin = miss_end;
+    ++c->pass_id;
+    return PRISM_OK;
+  };
+  for (int64_t t = r0; t < r0 + n; ++t) {
+    const int32_t tk = tok[t];
+    int sl = c->slot_of[tk];
+    if (sl >= 0) {
+      ++c->embed_hit;
+    } else {
+      ++c->embed_miss;
+      sl = c->lru_tail;
+      if (c->pin[sl] == c->pass_id) PRISM_TRY(flush(t));       // the victim is still needed by this pass: gather first
+      if (c->tok_of[sl] >= 0) c->slot_of[c->tok_of[sl]] = -1;
+      c->tok_of[sl] = tk;
+      c->slot_of[tk] = sl;
+      h_mtok[miss_end] = tk;
+      h_mslot[miss_end] = sl;
+      ++miss_end;
+    }
+    lru_touch(c, sl);
+    c->pin[sl] = c->pass_id;
+    h_slot[t] = sl;
+  }
+  return flush(r0 + n);
+}
+
+// ---- hidden-state offload: chunk copies between the pinned host copy of the residual stream and a device slot, one
+//      copy per run of candidates that are adjacent in the host layout (which never changes: pruning only drops runs)
+static int copy_chunk(prism_ctx *c, const Plan &p, const Chunk &ch, int slot, bool to_device, hipStream_t st) {
+  const int64_t H = c->m.hidden;
+  int i = ch.c0;
+  while (i < ch.c1) {
+    int j = i;
+    int64_t rows = p.len[i];
+    while (j + 1 < ch.c1 && c->hrow[p.live[j + 1]] == c->hrow[p.live[j]] + p.len[j]) { ++j; rows += p.len[j]; }
+    float *dev = c->Xo[slot] + (p.row0[i] - ch.r0) * H;
+    float *host = c->h_X + c->hrow[p.live[i]] * H;
+    if (to_device) PRISM_HIP(hipMemcpyAsync(dev, host, (size_t)rows * H * 4, hipMemcpyHostToDevice, st));
+    else PRISM_HIP(hipMemcpyAsync(host, dev, (size_t)rows * H * 4, hipMemcpyDeviceToHost, st));
+    c->bytes_hidden += rows * H * 4;
+    i = j + 1;
+  }
+  return PRISM_OK;
+}
+
+// Requests chunk ci of plan p into the slot of pipeline step `step`.  The slot is free once its previous content has
+// been written back; the chunk's data is on the host once its own last write-back is done.  wait_all (first request
+// after the live set or the partition changed): wait for every write-back issued so far.
+static int prefetch_chunk(prism_ctx *c, const Plan &p, int ci, int64_t step, bool wait_all) {
+  const int slot = (int)(step % 3), nch = (int)p.chunks.size();
+  if (wait_all) {
+    for (int i = 0; i < 3; ++i) PRISM_HIP(hipStreamWaitEvent(c->xin_stream, c->ev_out[i], 0));
+  } else {
+    // steady state on one plan: chunk ci was last written back nch steps ago; with three or more chunks that is not
+    // later than the slot's previous write-back (three steps ago) on the in-order write-back stream
+    PRISM_HIP(hipStreamWaitEvent(c->xin_stream, c->ev_out[slot], 0));
+    if (nch < 3 && step >= nch) PRISM_HIP(hipStreamWaitEvent(c->xin_stream, c->ev_out[(step - nch) % 3], 0));
+  }
+  PRISM_TRY(copy_chunk(c, p, p.chunks[ci], slot, true, c->xin_stream));
+  PRISM_HIP(hipEventRecord(c->ev_in[slot], c->xin_stream));
+  return PRISM_OK;
+}
+
+// Writes the slot of the current step back to the host once the compute stream is done with it (copy == false: only
+// marks the slot as free, for results that are not needed again).
+static int retire_chunk(prism_ctx *c, const Plan &p, const Chunk &ch, int slot, bool copy) {
+  PRISM_HIP(hipEventRecord(c->ev_done[slot], c->stream));
+  PRISM_HIP(hipStreamWaitEvent(c->xout_stream, c->ev_done[slot], 0));
+  if (copy) PRISM_TRY(copy_chunk(c, p, ch, slot, false, c->xout_stream));
+  PRISM_HIP(hipEventRecord(c->ev_out[slot], c->xout_stream));
+  return PRISM_OK;
+}
+
+// One transformer layer over every chunk.  Offload mode additionally: score_after = score the chunk's candidates while
+// the chunk is on the device (checkpoint layers and the last one); write_back = the layer's output is needed again;
+// next_layer_same_plan = the next layer runs on the same live set, so its first chunk may be prefetched.
+static int run_layer(prism_ctx *c, const Plan &p, const MetaOff &mo, float *X, const char *wbuf, bool score_after = false,
+                     bool write_back = true, bool next_layer_same_plan = false) {
   const prism_model &m = c->m;
   const LayerLayout &L = c->lay;
   const int H = m.hidden, Dq = m.n_q_heads * m.head_dim, Dkv = m.n_kv_heads * m.head_dim, F = m.ffn;
@@ -471,9 +694,23 @@ static int run_layer(prism_ctx *c, const Plan &p, const MetaOff &mo, float *X, c
     return bf ? launch_gemm_16(c->op, epi, A, W, out, M, N, K, s)
               : launch_gemm_fp32(epi, (const float *)A, (const float *)W, out, M, N, K, s);
   };
-  for (const Chunk &ch : p.chunks) {
+  const int nch = (int)p.chunks.size();
+  for (int ci = 0; ci < nch; ++ci) {
+    const Chunk &ch = p.chunks[ci];
     const int Tc = (int)(ch.r1 - ch.r0);
-    float *Xc = X + ch.r0 * H;
+    float *Xc = c->offload ? nullptr : X + ch.r0 * H;
+    int slot = 0;
+    // offload pipeline: the next chunk visit (next chunk of this layer, or the first chunk of the next layer)
+    const int next_ci = ci + 1 < nch ? ci + 1 : (next_layer_same_plan ? 0 : -1);
+    if (c->offload) {
+      slot = (int)(c->ostep % 3);
+      if (!c->primed) PRISM_TRY(prefetch_chunk(c, p, ci, c->ostep, true));
+      c->primed = false;
+      // with one chunk per layer the next visit needs THIS visit's write-back, so it is requested afterwards
+      if (nch >= 2 && next_ci >= 0) { PRISM_TRY(prefetch_chunk(c, p, next_ci, c->ostep + 1, false)); c->primed = true; }
+      PRISM_HIP(hipStreamWaitEvent(s, c->ev_in[slot], 0));
+      Xc = c->Xo[slot];
+    }
     const int32_t *pos = c->d_meta + mo.pos + ch.r0;
     double attn_flops = 0.0;
     for (int i = ch.c0; i < ch.c1; ++i) attn_flops += 2.0 * m.n_q_heads * m.head_dim * (double)p.len[i] * (p.len[i] + 1.0);
@@ -513,6 +750,14 @@ static int run_layer(prism_ctx *c, const Plan &p, const MetaOff &mo, float *X, c
     PRISM_TRY(timed_span(c, 5, 0.0, [&] { return launch_rmsnorm(Xc, wbuf + L.ffn_norm, Tc, H, m.rms_eps, c->op, c->Xn, s); }));
     PRISM_TRY(timed_span(c, 2, tk * 2 * F * H, [&] { return gemm(PRISM_EPI_SWIGLU, c->Xn, wbuf + L.wgu, c->S, Tc, 2 * F, H); }));
     PRISM_TRY(timed_span(c, 3, tk * H * F, [&] { return gemm(PRISM_EPI_RESIDUAL, c->S, wbuf + L.wd, Xc, Tc, H, F); }));
+    if (c->offload) {
+      if (score_after)   // last_row holds rows of the packed pool; this chunk's rows start at ch.r0
+        PRISM_TRY(launch_score(Xc - ch.r0 * H, c->d_meta + mo.lastrow + ch.c0, ch.c1 - ch.c0, m.hidden, c->final_norm, c->w_yes,
+                               c->w_no, m.dtype, m.rms_eps, c->d_scores + ch.c0, s));
+      PRISM_TRY(retire_chunk(c, p, ch, slot, write_back));
+      if (nch < 2 && next_ci >= 0) { PRISM_TRY(prefetch_chunk(c, p, next_ci, c->ostep + 1, false)); c->primed = true; }
+      ++c->ostep;
+    }
   }
   return PRISM_OK;
 }
@@ -578,7 +823,22 @@ extern "C" int prism_select(prism_ctx *c, const int32_t *query_tokens, int32_t q
   if (timed) PRISM_HIP(hipEventRecord(c->ev_t[0], s));
   PRISM_TRY(upload_meta(c, p, mo, true));
   int cur = 0;
-  PRISM_TRY(launch_embed(c->d_meta + mo.tokens, (int)p.T, c->embed, m.hidden, m.dtype, c->X[cur], s));
+  c->embed_hit = c->embed_miss = 0;
+  c->bytes_hidden = 0;
+  if (c->offload) {
+    // the pool's residual stream is born chunk by chunk and leaves for the host right away
+    c->hrow.assign(p.row0.begin(), p.row0.end());
+    c->primed = false;
+    for (const Chunk &ch : p.chunks) {
+      const int slot = (int)(c->ostep % 3);
+      PRISM_HIP(hipStreamWaitEvent(s, c->ev_out[slot], 0));      // the slot's previous content has been written back
+      PRISM_TRY(embed_range(c, c->h_meta + mo.tokens, c->d_meta + mo.tokens, ch.r0, ch.r1 - ch.r0, p.T, c->Xo[slot], s));
+      PRISM_TRY(retire_chunk(c, p, ch, slot, true));
+      ++c->ostep;
+    }
+  } else {
+    PRISM_TRY(embed_range(c, c->h_meta + mo.tokens, c->d_meta + mo.tokens, 0, p.T, p.T, c->X[cur], s));
+  }
 
   int64_t bytes_streamed = 0, token_layers = 0;
   if (c->streamed) {
@@ -625,7 +885,13 @@ extern "C" int prism_select(prism_ctx *c, const int32_t *query_tokens, int32_t q
     const int slot = c->streamed ? l % 2 : l;
     if (c->streamed) PRISM_HIP(hipStreamWaitEvent(s, c->ev_ready[slot], 0));
     if (timed) PRISM_HIP(hipEventRecord(c->ev_layer[2 * l], s));
-    PRISM_TRY(run_layer(c, p, mo, c->X[cur], c->layer_buf[slot]));
+    // known before the layer runs: will its output be scored for pruning, and is it the last one
+    while (next_ckpt < c->checkpoints.size() && c->checkpoints[next_ckpt] < l + 1) ++next_ckpt;
+    const bool check_after = next_ckpt < c->checkpoints.size() && c->checkpoints[next_ckpt] == l + 1 && l + 1 < m.n_layers &&
+                             may_prune && (int)p.live.size() > K_rem;
+    const bool last_layer = l + 1 == m.n_layers;
+    PRISM_TRY(run_layer(c, p, mo, c->X[cur], c->layer_buf[slot], check_after || last_layer, !last_layer,
+                        !last_layer && !check_after));
     if (timed) PRISM_HIP(hipEventRecord(c->ev_layer[2 * l + 1], s));
     token_layers += p.T;
     layers_run = l + 1;
@@ -635,15 +901,14 @@ extern "C" int prism_select(prism_ctx *c, const int32_t *query_tokens, int32_t q
       PRISM_TRY(issue_layer_copy(c, l + 2, slot, c->copy_stream, hipMemcpyHostToDevice, &bytes_streamed));
       PRISM_HIP(hipEventRecord(c->ev_ready[slot], c->copy_stream));
     }
-    while (next_ckpt < c->checkpoints.size() && c->checkpoints[next_ckpt] < l + 1) ++next_ckpt;
-    const bool is_ckpt = next_ckpt < c->checkpoints.size() && c->checkpoints[next_ckpt] == l + 1;
     const int n_live = (int)p.live.size();
-    if (!is_ckpt || l + 1 >= m.n_layers || !may_prune || n_live <= K_rem) continue;
+    if (!check_after) continue;
 
     // ---- pruning check on the output of layer l + 1, before layer l + 2 runs (Sec. 3.4, 4.1)
     if (timed) PRISM_HIP(hipEventRecord(c->ev_t[2], s));
-    PRISM_TRY(launch_score(c->X[cur], c->d_meta + mo.lastrow, n_live, m.hidden, c->final_norm, c->w_yes, c->w_no, m.dtype,
-                           m.rms_eps, c->d_scores, s));
+    if (!c->offload)   // offload mode scored every chunk while it was on the device
+      PRISM_TRY(launch_score(c->X[cur], c->d_meta + mo.lastrow, n_live, m.hidden, c->final_norm, c->w_yes, c->w_no, m.dtype,
+                             m.rms_eps, c->d_scores, s));
     PRISM_TRY(launch_route(c->d_scores, n_live, K_rem, c->opt.n_clusters, c->opt.cv_threshold, c->d_fate, c->d_stats,
                            c->route_ws, s));
     PRISM_HIP(hipMemcpyAsync(h_scores, c->d_scores, (size_t)n_live * 4, hipMemcpyDeviceToHost, s));
@@ -701,10 +966,14 @@ extern "C" int prism_select(prism_ctx *c, const int32_t *query_tokens, int32_t q
         dst += p.len[i]; ++k;
       }
       build_plan(c, q);
+      // regrouping the survivors can produce a chunk with more tokens than any chunk before it
+      PRISM_TRY(ensure_scratch(c, q, may_prune, n_cands, max_tiles));
       PRISM_TRY(upload_meta(c, q, mo, false));   // also carries src/dst/len, which sit between lastrow and tiles
-      PRISM_TRY(launch_compact(c->X[cur], c->X[cur ^ 1], c->d_meta + mo.src, c->d_meta + mo.dst, c->d_meta + mo.len, n_keep,
-                               m.hidden, s));
-      cur ^= 1;
+      if (!c->offload) {   // offload mode: the host copy keeps its layout, dropped candidates are simply never fetched again
+        PRISM_TRY(launch_compact(c->X[cur], c->X[cur ^ 1], c->d_meta + mo.src, c->d_meta + mo.dst, c->d_meta + mo.len, n_keep,
+                                 m.hidden, s));
+        cur ^= 1;
+      }
       p = q;
     }
     if (timed) {
@@ -720,8 +989,9 @@ extern "C" int prism_select(prism_ctx *c, const int32_t *query_tokens, int32_t q
     // ---- final scoring and top-K (Sec. 2.1)
     const int n_live = (int)p.live.size();
     const int k_out = std::min(K_rem, n_live);
-    PRISM_TRY(launch_score(c->X[cur], c->d_meta + mo.lastrow, n_live, m.hidden, c->final_norm, c->w_yes, c->w_no, m.dtype,
-                           m.rms_eps, c->d_scores, s));
+    if (!c->offload)
+      PRISM_TRY(launch_score(c->X[cur], c->d_meta + mo.lastrow, n_live, m.hidden, c->final_norm, c->w_yes, c->w_no, m.dtype,
+                             m.rms_eps, c->d_scores, s));
     PRISM_TRY(launch_topk(c->d_scores, n_live, k_out, c->d_top_pos, c->d_top_scores, s));
     PRISM_HIP(hipMemcpyAsync(h_scores, c->d_scores, (size_t)n_live * 4, hipMemcpyDeviceToHost, s));
     PRISM_HIP(hipMemcpyAsync(h_top_pos, c->d_top_pos, (size_t)k_out * 4, hipMemcpyDeviceToHost, s));
@@ -735,6 +1005,10 @@ extern "C" int prism_select(prism_ctx *c, const int32_t *query_tokens, int32_t q
     PRISM_HIP(hipStreamSynchronize(s));
   }
   if (c->streamed) PRISM_HIP(hipStreamSynchronize(c->copy_stream));
+  if (c->offload) {
+    PRISM_HIP(hipStreamSynchronize(c->xin_stream));
+    PRISM_HIP(hipStreamSynchronize(c->xout_stream));
+  }
 
   int n_out = 0;
   for (size_t i = 0; i < early_idx.size() && n_out < Kc; ++i, ++n_out) { out_idx[n_out] = early_idx[i]; out_scores[n_out] = early_scores[i]; }
@@ -756,6 +1030,9 @@ extern "C" int prism_select(prism_ctx *c, const int32_t *query_tokens, int32_t q
     rep->peak_hbm_bytes = c->bytes_peak;
     rep->bytes_streamed = bytes_streamed;
     rep->layers_run = layers_run;
+    rep->bytes_hidden_moved = c->bytes_hidden;
+    rep->embed_rows_hit = c->embed_hit;
+    rep->embed_rows_missed = c->embed_miss;
     for (int k = 0; k < PRISM_N_KINDS; ++k) { rep->kind_launches[k] = 0; rep->kind_ms[k] = 0.0; rep->kind_flops[k] = 0.0; }
     for (const prism_ctx::Span &sp : c->spans) {
       PRISM_HIP(hipEventElapsedTime(&ms, sp.a, sp.b));

@@ -1,0 +1,128 @@
+"""Memory-saving execution modes of Sec. 4.3 / 4.4 on the device: hidden-state offload (three chunks of the residual
+stream on the device, the rest in pinned host memory) and the embedding-table cache (table in pinned host memory, LRU
+rows on the device).  Neither changes any arithmetic, so everything the call reports must equal the resident run BIT
+FOR BIT; the cache's hit/miss counts must equal the oracle's LRU on the same token stream."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import prism_oracle as O
+from paper_2510_15620_amd import binding as B
+from paper_2510_15620_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def _same(a, b):
+    (ia, sa, ra), (ib, sb, rb) = a, b
+    assert ia.tolist() == ib.tolist()
+    assert np.array_equal(sa, sb)
+    assert np.array_equal(ra.layer, rb.layer) and np.array_equal(ra.n_after, rb.n_after)
+    assert np.array_equal(ra.scores, rb.scores, equal_nan=True)
+    assert np.array_equal(ra.fate, rb.fate)
+    assert ra.token_layers == rb.token_layers and ra.layers_run == rb.layers_run
+
+
+def _opts(w, **kw):
+    o = dict(checkpoints=w.checkpoints, cv_threshold=w.cv_threshold, n_clusters=w.n_clusters, chunk_cands=w.chunk_cands)
+    o.update(kw)
+    return o
+
+
+@pytest.mark.parametrize("name", ["mini_bf16", "mini_fp32"])
+@pytest.mark.parametrize("chunk", [3, 5, 8, 1000])          # many chunks, a few, two after the first prune, one
+@pytest.mark.parametrize("mode", [B.MODE_DROP_ONLY, B.MODE_THREE_WAY, B.MODE_NO_PRUNING])
+def test_offload_equals_resident(name, chunk, mode):
+    w = W.WORKLOADS[name]
+    wt = W.make_weights(w, "cuda")
+    q, cands = W.make_tokens(w)
+    base = B.Prism(w.model, wt, **_opts(w, chunk_cands=chunk, mode=mode))
+    ref = base.select(q, cands, w.K)
+    base.destroy()
+    p = B.Prism(w.model, wt, **_opts(w, chunk_cands=chunk, mode=mode, offload_hidden=True))
+    for _ in range(2):                                       # the pipeline state carries over between calls
+        out = p.select(q, cands, w.K)
+        _same(out, ref)
+    rep = out[2]
+    H = w.model.hidden
+    lens = np.array([len(q) + len(c) for c in cands])
+    # every live token's row leaves the device after the embedding and after every layer but the model's last one,
+    # and comes back before every layer
+    moved_out = int(lens.sum()) + rep.token_layers
+    if rep.layers_run == w.model.n_layers:
+        moved_out -= int(lens[_live_at_end(rep, len(cands))].sum())
+    assert rep.bytes_hidden_moved == (moved_out + rep.token_layers) * H * 4
+    p.destroy()
+
+
+def _live_at_end(rep, n):
+    """Candidates the last executed layer ran on."""
+    live = ~np.isnan(rep.scores[-1])
+    return np.nonzero(live)[0]
+
+
+def test_offload_bounds_the_device_footprint():
+    w = W.WORKLOADS["mini_bf16"]
+    wt = W.make_weights(w, "cuda")
+    q, cands = W.make_tokens(w)
+    peaks = {}
+    for off in (False, True):
+        p = B.Prism(w.model, wt, **_opts(w, chunk_cands=2, offload_hidden=off))
+        peaks[off] = p.select(q, cands, w.K)[2].peak_hbm_bytes
+        p.destroy()
+    lens = sorted((len(q) + len(c) for c in cands), reverse=True)
+    H = w.model.hidden
+    # two full copies of the pool (compaction ping-pong) against three slots of the largest two-candidate chunk
+    assert peaks[False] - peaks[True] >= (2 * sum(lens) - 3 * (lens[0] + lens[1])) * H * 4 - 4096
+
+
+def test_offload_needs_chunks():
+    w = W.WORKLOADS["cfg1_tiny"]
+    with pytest.raises(B.PrismError) as e:
+        B.Prism(w.model, W.make_weights(w, "cuda"), **_opts(w, chunk_cands=0, offload_hidden=True))
+    assert e.value.code == B.EINVAL
+
+
+class _HostEmbedWeights:
+    def __init__(self, wt):
+        self.embed = wt.embed.cpu().pin_memory()
+        self.layers, self.final_norm = wt.layers, wt.final_norm
+        self.w_yes, self.w_no = wt.w_yes.clone(), wt.w_no.clone()
+
+
+@pytest.mark.parametrize("name", ["mini_bf16", "cfg1_tiny"])
+@pytest.mark.parametrize("rows", [1, 7, 64, 0])             # 0 = the default, a tenth of the vocabulary
+@pytest.mark.parametrize("offload", [False, True])
+def test_embedding_cache_equals_resident_table_and_oracle_lru(name, rows, offload):
+    w = W.WORKLOADS[name]
+    wt = W.make_weights(w, "cuda")
+    q, cands = W.make_tokens(w)
+    chunk = 3 if offload else w.chunk_cands
+    base = B.Prism(w.model, wt, **_opts(w, chunk_cands=chunk))
+    ref = base.select(q, cands, w.K)
+    base.destroy()
+    p = B.Prism(w.model, _HostEmbedWeights(wt), **_opts(w, chunk_cands=chunk, embed_on_host=True, embed_cache_rows=rows,
+                                                         offload_hidden=offload))
+    lru = O.LruRowCache(rows if rows else max(w.model.vocab // 10, 1))
+    stream = np.concatenate([np.concatenate([q, c]) for c in cands])
+    q2, cands2 = q[::-1].copy(), [c[::-1].copy() for c in cands[:5]]      # a second, different request on the warm cache
+    stream2 = np.concatenate([np.concatenate([q2, c]) for c in cands2])
+    out = p.select(q, cands, w.K)
+    _same(out, ref)
+    assert (out[2].embed_rows_hit, out[2].embed_rows_missed) == lru.run(stream)
+    out2 = p.select(q2, cands2, 2)
+    assert (out2[2].embed_rows_hit, out2[2].embed_rows_missed) == lru.run(stream2)
+    base2 = B.Prism(w.model, wt, **_opts(w, chunk_cands=chunk))
+    _same(out2, base2.select(q2, cands2, 2))
+    base2.destroy()
+    p.destroy()
+
+
+def test_embedding_table_must_be_pinned():
+    w = W.WORKLOADS["cfg1_tiny"]
+    wt = W.make_weights(w, "cuda")
+    hw = _HostEmbedWeights(wt)
+    hw.embed = wt.embed.cpu()                                # pageable: kernels could not read it
+    with pytest.raises(B.PrismError) as e:
+        B.Prism(w.model, hw, **_opts(w, embed_on_host=True))
+    assert e.value.code == B.EINVAL

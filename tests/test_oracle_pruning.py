@@ -137,3 +137,37 @@ def test_gamma_formula():
     assert O.goodman_kruskal_gamma(a, [4, 3, 2, 1]) == -1.0
     # pairs: 6; swapping the two middle ones reverses exactly one pair -> (5 - 1) / 6
     assert abs(O.goodman_kruskal_gamma(a, [1, 3, 2, 4]) - 4 / 6) < 1e-15
+
+
+# ---- embedding-table cache (Sec. 4.4): the oracle's LRU against hand-worked traces and what any LRU must satisfy
+
+def test_lru_hand_worked_trace():
+    c = O.LruRowCache(2)
+    # 1 miss, 2 miss, 1 hit (2 is now the oldest), 3 miss evicts 2, 2 miss evicts 1, 3 hit
+    assert [c.access(t) for t in (1, 2, 1, 3, 2, 3)] == [False, False, True, False, False, True]
+    assert c.order == [2, 3]
+
+
+def test_lru_invariants():
+    rng = np.random.default_rng(3)
+    toks = rng.integers(0, 40, size=500).tolist()
+    # capacity >= distinct tokens: one miss per distinct token
+    assert O.LruRowCache(40).run(toks) == (500 - len(set(toks)), len(set(toks)))
+    # capacity 1: a hit only when a token repeats immediately
+    rep = sum(a == b for a, b in zip(toks[:-1], toks[1:]))
+    assert O.LruRowCache(1).run(toks) == (rep, 500 - rep)
+    # inclusion property of LRU: a larger cache never misses more
+    misses = [O.LruRowCache(k).run(toks)[1] for k in (1, 2, 5, 10, 20, 40)]
+    assert misses == sorted(misses, reverse=True)
+    # brute force against the definition: hit iff fewer than `capacity` distinct other tokens since the last use
+    cap = 7
+    c = O.LruRowCache(cap)
+    for i, t in enumerate(toks):
+        prev = max((j for j in range(i) if toks[j] == t), default=None)
+        expect = prev is not None and len(set(toks[prev + 1:i])) < cap
+        assert c.access(t) == expect
+    # state carries over between requests
+    c2 = O.LruRowCache(3)
+    c2.run([5, 6, 7])
+    # 7, 6, 5 hit (5 newest); 8 evicts 7, the oldest; 7 misses again
+    assert c2.run([7, 6, 5, 8, 7]) == (3, 2)
