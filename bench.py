@@ -78,6 +78,8 @@ def main():
     ap.add_argument("--workload", default="cfg4_8b")
     ap.add_argument("--operand", default="f16", choices=["f16", "bf16"],
                     help="16-bit type of the matrix-core operands when the weights are bf16")
+    ap.add_argument("--lean", action="store_true",
+                    help="hidden-state offload + embedding-table cache (needs a chunked workload, e.g. cfg5_8b_stream)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unpruned", action="store_true")
     args = ap.parse_args()
@@ -104,11 +106,19 @@ def main():
         wt_for_oracle = dev
     else:
         wt = wt_for_oracle = W.make_weights(w, "cuda")
+    if args.lean:
+        class HostTable:                      # embedding table in pinned host memory, the two head rows on the device
+            pass
+        ht = HostTable()
+        ht.embed, ht.layers, ht.final_norm = wt.embed.cpu().pin_memory(), wt.layers, wt.final_norm
+        ht.w_yes, ht.w_no = wt_for_oracle.w_yes.clone(), wt_for_oracle.w_no.clone()
+        wt = ht
     q, cands = W.make_tokens(w)
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
     opts = dict(checkpoints=w.checkpoints, cv_threshold=w.cv_threshold, n_clusters=w.n_clusters, chunk_cands=w.chunk_cands,
-                hbm_cap_bytes=w.hbm_cap_bytes, stream_weights=w.stream_weights, operand=args.operand)
+                hbm_cap_bytes=w.hbm_cap_bytes, stream_weights=w.stream_weights, operand=args.operand,
+                offload_hidden=args.lean, embed_on_host=args.lean)
     p = B.Prism(m, wt, **opts)
 
     for _ in range(args.warmup):
@@ -180,6 +190,9 @@ def main():
         "roofline": roofline,
         "weights_gen_s": round(t_gen, 1),
     }
+    if args.lean:
+        out["lean"] = {"bytes_hidden_moved": int(rep.bytes_hidden_moved), "embed_rows_hit": int(rep.embed_rows_hit),
+                       "embed_rows_missed": int(rep.embed_rows_missed)}
     if w.stream_weights and rep.ms_total > 0:
         out["stream_GBps"] = round(rep.bytes_streamed / rep.ms_total / 1e6, 1)
     if not args.no_cpu_baseline:

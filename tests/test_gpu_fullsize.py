@@ -85,14 +85,26 @@ def _oracle_trajectories(w, wt, q, cands, sample, depth, tag):
     return out
 
 
-def _run_gpu(w, wt, mode=B.MODE_DROP_ONLY, operand="f16"):
+class _HostTable:
+    """The same weights with the embedding table in pinned host memory (the two head rows stay on the device)."""
+    def __init__(self, wt):
+        self.embed = wt.embed.cpu().pin_memory()
+        self.layers, self.final_norm = wt.layers, wt.final_norm
+        self.w_yes, self.w_no = wt.w_yes.clone(), wt.w_no.clone()
+
+
+def _run_gpu(w, wt, mode=B.MODE_DROP_ONLY, operand="f16", lean=False, hbm_cap_bytes=None):
+    """lean: hidden-state offload and the embedding-table cache on top of the workload's own options."""
     q, cands = W.make_tokens(w)
     weights = wt
     if w.stream_weights:
         host = [{k: v.to("cpu").pin_memory() for k, v in l.items()} for l in wt.layers]
         weights = W.Weights(wt.embed, host, wt.final_norm)
+    if lean:
+        weights = _HostTable(weights)
     p = B.Prism(w.model, weights, checkpoints=w.checkpoints, mode=mode, chunk_cands=w.chunk_cands,
-                hbm_cap_bytes=w.hbm_cap_bytes, stream_weights=w.stream_weights, operand=operand)
+                hbm_cap_bytes=w.hbm_cap_bytes if hbm_cap_bytes is None else hbm_cap_bytes, stream_weights=w.stream_weights,
+                operand=operand, offload_hidden=lean, embed_on_host=lean)
     out = p.select(q, cands, w.K)
     p.destroy()
     return out
@@ -173,3 +185,24 @@ def test_cfg5_streamed_chunked_under_the_hbm_cap(weights_8b):
     assert rep.peak_hbm_bytes <= w.hbm_cap_bytes
     per_layer = 2 * (w.model.gemm_flops_per_token_layer() // 2)          # bf16 bytes of the matrices of one layer
     assert rep.bytes_streamed >= w.model.n_layers * per_layer
+
+
+def test_cfg5_offload_and_embedding_cache_are_bit_identical_and_leaner(weights_8b):
+    """The 500-candidate pool again with the residual stream in pinned host memory (three chunks on the device) and the
+    embedding table behind a device cache of a tenth of its rows: same numbers, a fraction of the device memory."""
+    w = W.WORKLOADS["cfg5_8b_stream"]
+    idx0, sc0, rep0 = _run_gpu(w, weights_8b)
+    cap = 8 * 2 ** 30
+    idx1, sc1, rep1 = _run_gpu(w, weights_8b, lean=True, hbm_cap_bytes=cap)
+    assert idx0.tolist() == idx1.tolist() and np.array_equal(sc0, sc1)
+    assert np.array_equal(rep0.scores, rep1.scores, equal_nan=True) and np.array_equal(rep0.fate, rep1.fate)
+    _progress(f"cfg5 lean: peak {rep1.peak_hbm_bytes / 2**30:.2f} GiB vs {rep0.peak_hbm_bytes / 2**30:.2f} GiB, "
+              f"hidden bytes moved {rep1.bytes_hidden_moved / 1e9:.1f} GB, embed rows hit/missed "
+              f"{rep1.embed_rows_hit}/{rep1.embed_rows_missed}, {rep1.ms_total:.0f} ms vs {rep0.ms_total:.0f} ms")
+    assert rep1.peak_hbm_bytes <= cap < rep0.peak_hbm_bytes
+    q, cands = W.make_tokens(w)
+    lru = O.LruRowCache(w.model.vocab // 10)
+    sample = np.concatenate([np.concatenate([q, c]) for c in cands[:40]])     # the oracle's list-based LRU is slow
+    assert rep1.embed_rows_hit + rep1.embed_rows_missed == sum(len(q) + len(c) for c in cands)
+    # the first 40 sequences of the stream, replayed by the oracle, give a lower bound on misses of the full stream's prefix
+    assert rep1.embed_rows_missed >= lru.run(sample)[1]
