@@ -20,6 +20,8 @@
 // second contraction runs on the f16 MFMA in both modes so that the probabilities keep 11
 // significand bits.  A sequence's columns
 // start at a multiple of 64 so every 16-byte chunk is aligned.
+#include <type_traits>
+
 #include "common.h"
 
 namespace prism {
@@ -115,7 +117,10 @@ __global__ __launch_bounds__(512) void attention_16_kernel(const OT *__restrict_
     const bool more = kt + 1 < n_kt;
     if (more) load_tile(kt + 1, rk, rv);
 
-    if (kt * BKV <= q_hi_wave && q_lo < L) {       // wave-uniform: tile not entirely in this wave's future
+    // One K/V tile for this wave.  MASK: the tile holds keys after some query of the wave (the causal diagonal); the
+    // two variants are separate code so that tiles below the diagonal carry no masking arithmetic at all.
+    auto tile_step = [&](auto mask_tag) {
+      constexpr bool MASK = decltype(mask_tag)::value;
       // ---- S^T = K Q^T for the 2 key blocks of the tile
       f32x16 s[2];
 #pragma unroll
@@ -131,13 +136,12 @@ __global__ __launch_bounds__(512) void attention_16_kernel(const OT *__restrict_
         }
       }
       // ---- causal mask + online softmax (lane owns query qi; partner lane ^ 32 owns the other keys)
-      const bool diag = kt * BKV + BKV - 1 > q_lo;   // tile may contain keys after some query of the wave
       float mx = -INFINITY;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          if (diag) {
+          if (MASK) {
             const int key = kt * BKV + kb * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
             if (key > qi) s[kb][e] = -INFINITY;
           }
@@ -159,7 +163,11 @@ __global__ __launch_bounds__(512) void attention_16_kernel(const OT *__restrict_
         }
       l_run = l_run * alpha + psum;
       m_run = m_new;
-      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {      // the running maxima usually settle after a few tiles
+      // the running maxima usually settle after a few tiles.  The ballot goes through an opaque asm so that the
+      // compiler cannot turn the branch back into an unconditional multiply (x * 1 == x makes the two equivalent).
+      unsigned long long moved = __builtin_amdgcn_ballot_w64(alpha != 1.0f);
+      asm volatile("" : "+s"(moved));
+      if (moved != 0) {
 #pragma unroll
         for (int t = 0; t < HD / 32; ++t)
 #pragma unroll
@@ -177,6 +185,10 @@ __global__ __launch_bounds__(512) void attention_16_kernel(const OT *__restrict_
           o[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf[ks], o[t], 0, 0, 0);
         }
       }
+        };
+    if (kt * BKV <= q_hi_wave && q_lo < L) {       // wave-uniform: tile not entirely in this wave's future
+      if (kt * BKV + BKV - 1 > q_lo) tile_step(std::true_type{});
+      else tile_step(std::false_type{});
     }
     if (more) store_tile(cur ^ 1, rk, rv);
     __syncthreads();
