@@ -19,6 +19,8 @@
 //
 // Workgroup ids are remapped so that each XCD (ids are dealt round-robin over the 8 XCDs) owns a
 // contiguous range of tiles, walked in groups of 8 row-tiles, to keep the operand panels in its L2.
+#include <algorithm>
+
 #include "common.h"
 #include "gemm_16_kloop.inc"
 
@@ -402,15 +404,30 @@ static int launch_typed(int epilogue, const OT *A, const OT *W, void *out, int M
   }
 }
 
+// The kernel addresses its operands with 32-bit byte offsets.  W has to fit that; A (and the output rows with it) is
+// cut into row panels that do: rows of a GEMM are independent, so the panels are separate launches.
+static int rows_per_launch(int K) {
+  const int64_t rows = (((int64_t)1 << 32) - 1) / ((int64_t)K * 2);
+  return (int)std::max<int64_t>(256, rows / 256 * 256);
+}
+
 int launch_gemm_16(int dtype, int epilogue, const void *A, const void *W, void *out, int M, int N, int K, hipStream_t s) {
   PRISM_REQUIRE(A && W && out && M >= 0 && is16(dtype), PRISM_EINVAL, "gemm: bad arguments");
-  PRISM_REQUIRE((int64_t)M * K * 2 < ((int64_t)1 << 32) && (int64_t)N * K * 2 < ((int64_t)1 << 32), PRISM_EUNSUPPORTED,
-                "gemm: an operand of %d x %d or %d x %d 16-bit elements exceeds 4 GiB", M, K, N, K);
   PRISM_REQUIRE(gemm_16_supported(epilogue, N, K), PRISM_EUNSUPPORTED,
                 "gemm: N = %d, K = %d, epilogue %d not supported (K must be a multiple of %d)", N, K, epilogue, BK);
-  if (M == 0) return PRISM_OK;
-  if (dtype == PRISM_DTYPE_BF16) return launch_typed<bf16>(epilogue, (const bf16 *)A, (const bf16 *)W, out, M, N, K, s);
-  return launch_typed<f16>(epilogue, (const f16 *)A, (const f16 *)W, out, M, N, K, s);
+  PRISM_REQUIRE((int64_t)N * K * 2 < ((int64_t)1 << 32) && (int64_t)256 * K * 2 < ((int64_t)1 << 32), PRISM_EUNSUPPORTED,
+                "gemm: a weight operand of %d x %d 16-bit elements exceeds 4 GiB", N, K);
+  const int step = rows_per_launch(K);
+  const int out_cols = epilogue == PRISM_EPI_SWIGLU ? N / 2 : N;
+  const size_t out_elem = epilogue == PRISM_EPI_RESIDUAL || epilogue == PRISM_EPI_STORE_F32 ? 4 : 2;
+  for (int m0 = 0; m0 < M; m0 += step) {
+    const int rows = std::min(step, M - m0);
+    const char *a = reinterpret_cast<const char *>(A) + (size_t)m0 * K * 2;
+    char *o = reinterpret_cast<char *>(out) + (size_t)m0 * out_cols * out_elem;
+    if (dtype == PRISM_DTYPE_BF16) PRISM_TRY(launch_typed<bf16>(epilogue, (const bf16 *)a, (const bf16 *)W, o, rows, N, K, s));
+    else PRISM_TRY(launch_typed<f16>(epilogue, (const f16 *)a, (const f16 *)W, o, rows, N, K, s));
+  }
+  return PRISM_OK;
 }
 
 bool gemm_16_qkv_supported(int M, int nq, int nkv, int hd, int K) {
@@ -425,12 +442,22 @@ int launch_gemm_16_qkv(int dtype, const void *Xn, const void *Wqkv, int M, int K
   PRISM_REQUIRE(!e.qk_norm || (e.q_gain && e.k_gain), PRISM_EINVAL, "qkv gemm: gains missing");
   PRISM_REQUIRE(gemm_16_qkv_supported(M, e.nq, e.nkv, hd, K), PRISM_EUNSUPPORTED, "qkv gemm: shape not supported by the fused epilogue");
   const int N = (e.nq + 2 * e.nkv) * 128;
-  PRISM_REQUIRE((int64_t)M * K * 2 < ((int64_t)1 << 32) && (int64_t)N * K * 2 < ((int64_t)1 << 32), PRISM_EUNSUPPORTED,
-                "qkv gemm: an operand exceeds 4 GiB");
-  if (M == 0) return PRISM_OK;
-  if (dtype == PRISM_DTYPE_BF16)
-    return launch_cfg<bf16, 256, 256, 2, 2, kEpiQkv>((const bf16 *)Xn, (const bf16 *)Wqkv, e.QK, M, N, K, s, e);
-  return launch_cfg<f16, 256, 256, 2, 2, kEpiQkv>((const f16 *)Xn, (const f16 *)Wqkv, e.QK, M, N, K, s, e);
+  PRISM_REQUIRE((int64_t)N * K * 2 < ((int64_t)1 << 32) && (int64_t)256 * K * 2 < ((int64_t)1 << 32), PRISM_EUNSUPPORTED,
+                "qkv gemm: the weight operand exceeds 4 GiB");
+  const int step = rows_per_launch(K);
+  for (int m0 = 0; m0 < M; m0 += step) {
+    const int rows = std::min(step, M - m0);
+    QkvEpilogue p = e;                       // row panel: every per-row array moves with the rows
+    p.pos = e.pos + m0;
+    p.vt_col = e.vt_col + m0;
+    p.QK = reinterpret_cast<char *>(e.QK) + (size_t)m0 * (e.nq + e.nkv) * 128 * 2;
+    const char *a = reinterpret_cast<const char *>(Xn) + (size_t)m0 * K * 2;
+    if (dtype == PRISM_DTYPE_BF16)
+      PRISM_TRY((launch_cfg<bf16, 256, 256, 2, 2, kEpiQkv>((const bf16 *)a, (const bf16 *)Wqkv, p.QK, rows, N, K, s, p)));
+    else
+      PRISM_TRY((launch_cfg<f16, 256, 256, 2, 2, kEpiQkv>((const f16 *)a, (const f16 *)Wqkv, p.QK, rows, N, K, s, p)));
+  }
+  return PRISM_OK;
 }
 
 }  // namespace prism

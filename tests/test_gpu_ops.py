@@ -97,6 +97,24 @@ def test_gemm_16_fp32_output(dtype):
     np.testing.assert_allclose(_f64(out), _f64(A) @ _f64(Wt).T, rtol=1e-4, atol=1e-4)
 
 
+def test_gemm_16_row_panels_beyond_4gib():
+    """A has more than 4 GiB of bytes: the launcher cuts it into row panels (the kernel addresses with 32-bit offsets).
+    Sampled rows on both sides of the cut against the oracle's plain product."""
+    K, N = 12288, 512
+    M = ((1 << 32) // (K * 2) // 256 + 3) * 256                  # three row tiles past the first panel
+    g = torch.Generator(device=DEV).manual_seed(7)
+    A = torch.randn(M, K, device=DEV, generator=g, dtype=torch.float32).to(torch.float16)
+    Wt = (torch.randn(N, K, device=DEV, generator=g, dtype=torch.float32) / math.sqrt(K)).to(torch.float16)
+    out = torch.zeros(M, N, dtype=torch.float32, device=DEV)
+    B.op_gemm(B.EPI_STORE_F32, A, Wt, out)
+    torch.cuda.synchronize()
+    cut = (1 << 32) // (K * 2) // 256 * 256
+    rows = [0, 1, 255, cut - 1, cut, cut + 1, cut + 300, M - 1]
+    ref = _f64(A[rows]) @ _f64(Wt).T
+    np.testing.assert_allclose(_f64(out[rows]), ref, rtol=1e-4, atol=1e-4)
+    assert out.abs().sum(dim=1).min().item() > 0                 # no row was left unwritten
+
+
 def _vt_layout(lens):
     """Column of every token in the transposed V buffer: sequences start at multiples of 64."""
     col0 = np.concatenate([[0], np.cumsum([(l + 63) // 64 * 64 for l in lens])]).astype(np.int32)
