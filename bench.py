@@ -78,6 +78,9 @@ def main():
     ap.add_argument("--workload", default="cfg4_8b")
     ap.add_argument("--operand", default="f16", choices=["f16", "bf16"],
                     help="16-bit type of the matrix-core operands when the weights are bf16")
+    ap.add_argument("--checkpoints", default="workload", choices=["workload", "every"],
+                    help="pruning checks after the workload's layers (every 4th) or after every layer (Sec. 4.5)")
+    ap.add_argument("--tau", type=float, default=None, help="dispersion threshold (default: the workload's, 0)")
     ap.add_argument("--lean", action="store_true",
                     help="hidden-state offload + embedding-table cache (needs a chunked workload, e.g. cfg5_8b_stream)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -97,6 +100,10 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     w = W.WORKLOADS[args.workload]
+    if args.checkpoints == "every" or args.tau is not None:
+        import dataclasses
+        w = dataclasses.replace(w, checkpoints=list(range(1, w.model.n_layers)) if args.checkpoints == "every" else w.checkpoints,
+                                cv_threshold=w.cv_threshold if args.tau is None else args.tau)
     m = w.model
     t_gen = time.perf_counter()
     if w.stream_weights:

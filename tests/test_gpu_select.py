@@ -168,3 +168,16 @@ def test_errors_are_codes_not_crashes():
     with pytest.raises(B.PrismError) as e:
         B.Prism(m, W.make_weights(W.WORKLOADS["mini_bf16"], "cuda"))
     assert e.value.code == B.EUNSUPPORTED
+
+
+@pytest.mark.parametrize("name,tol", [("cfg1_tiny", 1e-4), ("mini_fp32", 1e-4), ("mini_bf16", 2e-2)])
+@pytest.mark.parametrize("tau", [0.0, 0.35])
+def test_checkpoint_after_every_layer(name, tol, tau):
+    """Sec. 4.5 checks after every layer; the benchmark configurations check every fourth.  Same comparison rule, with a
+    dispersion threshold that closes the gate at some of the checks."""
+    import dataclasses
+    w = dataclasses.replace(W.WORKLOADS[name], checkpoints=list(range(1, W.WORKLOADS[name].model.n_layers)), cv_threshold=tau)
+    idx, scores, rep = run(w)
+    ref = oracle_select(w)
+    check_against_oracle(w, idx, scores, rep, ref, tol)
+    assert len(rep.layer) >= 2
