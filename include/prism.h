@@ -58,6 +58,15 @@ extern "C" {
 
 typedef struct prism_ctx prism_ctx;
 
+/* Layer weight formats.  W4G128 is this library's reading of the paper's 4-bit-weight / 16-bit-activation variant
+ * (Sec. 6), which the paper names without detail: symmetric codes q in [-7, 7] for groups of 128 consecutive input
+ * features of one output row, one bf16 scale per group (max|w| / 7 rounded to nearest even; 1 for an all-zero group),
+ * q = w / scale rounded to nearest even and clamped; the weight used is q * scale, which is exact in IEEE half.
+ * Blob of an [N, K] matrix (K % 128 == 0): N*K/2 code bytes, row-major, code k of a row in the low (k even) or high
+ * (k odd) nibble of byte k/2, stored as q + 8; then N*K/128 bf16 scales, row-major. */
+#define PRISM_WFMT_PLAIN  0
+#define PRISM_WFMT_W4G128 1
+
 /* Architecture of the reranker (decoder-only, causal; Sec. 2.1).  Sizes in elements. */
 typedef struct {
   int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
@@ -83,6 +92,12 @@ typedef struct {
   int32_t layer_residency;            /* 0: device; 1: pinned host, streamed one layer ahead (Sec. 4.2) */
   int32_t embed_residency;            /* 0: device; 1: pinned host (allocated by hipHostMalloc, so that kernels can read
                                          it), rows fetched on demand into a device LRU cache (Sec. 4.4) */
+  int32_t layer_format;               /* PRISM_WFMT_PLAIN: tensors in the model dtype.  PRISM_WFMT_W4G128 (bf16 models):
+                                         the seven matrices of a layer are 4-bit blobs as written by
+                                         prism_op_quantize_w4 (the norm gains stay bf16); a layer is expanded into
+                                         one of two device slots right before it runs, so device-resident blobs are
+                                         borrowed in place for the context's lifetime, and streamed ones move a
+                                         quarter of the bytes.  Needs hidden, ffn, n_q_heads*head_dim % 128 == 0 */
 } prism_weights;
 
 typedef struct {
@@ -215,6 +230,13 @@ int prism_op_qkv_project(int32_t dtype, const void *Xn, const void *Wqkv, const 
                          const void *q_gain, const void *k_gain, int32_t T, int32_t hidden, int32_t n_q_heads,
                          int32_t n_kv_heads, int32_t head_dim, float eps, float rope_base, int32_t qk_norm,
                          void *QK, void *Vt, const int32_t *vt_col, int64_t vt_stride, void *stream);
+
+/* 4-bit weight blobs (PRISM_WFMT_W4G128).  prism_w4_bytes: size of the blob of an [N, K] matrix.
+ * prism_op_quantize_w4: W [N, K] bf16 [device] -> blob [device].  prism_op_dequantize_w4: blob -> out [N, K] [device] in
+ * dtype BF16 or F16 (what a layer slot holds before the layer runs). */
+int64_t prism_w4_bytes(int32_t N, int32_t K);
+int prism_op_quantize_w4(const void *W, int32_t N, int32_t K, void *blob, void *stream);
+int prism_op_dequantize_w4(const void *blob, int32_t N, int32_t K, int32_t dtype, void *out, void *stream);
 
 /* Causal GQA attention within each sequence (no token attends across sequences; Sec. 2.2).
  * cu_seqlens [n_seqs+1] [host]: token offsets of the sequences; out [T, nq*hd] [device] in dtype.

@@ -425,6 +425,34 @@ def score_trajectory(query_tokens, cand, weights, m: Model, at_layers: Sequence[
     return out
 
 
+W4_GROUP = 128
+
+
+def quantize_w4(W: np.ndarray, group: int = W4_GROUP):
+    """4-bit weights, 16-bit activations (the quantised variant evaluated in Sec. 6).  The paper names the format only;
+    the reading taken here: symmetric codes q in [-7, 7] for groups of `group` consecutive input features of one output
+    row, one scale per group, scale = max|w| / 7 rounded to bf16 (1 if the group is all zero), q = w / scale rounded
+    to nearest (ties to even) and clamped.  With a bf16 scale and |q| <= 7 the product q * scale has at most 11
+    significant bits, so the dequantised weight is exact in IEEE half and in fp32.
+    Every step is in fp32, as on the device.  Returns (codes int8 [N, K], scales float32 [N, K / group])."""
+    W = np.asarray(W, np.float32)
+    N, K = W.shape
+    assert K % group == 0
+    g = W.reshape(N, K // group, group)
+    amax = np.max(np.abs(g), axis=2)
+    scale = round_operand(amax / np.float32(7.0), "bf16").astype(np.float32)
+    scale = np.where(scale == 0, np.float32(1.0), scale).astype(np.float32)
+    q = np.rint(g / scale[:, :, None])                       # fp32 division, round half to even
+    q = np.clip(q, -7, 7).astype(np.int8)
+    return q.reshape(N, K), scale
+
+
+def dequantize_w4(codes: np.ndarray, scales: np.ndarray, group: int = W4_GROUP) -> np.ndarray:
+    """w' = q * scale, exact (see quantize_w4); fp64."""
+    N, K = codes.shape
+    return (codes.reshape(N, K // group, group).astype(F64) * scales.astype(F64)[:, :, None]).reshape(N, K)
+
+
 class LruRowCache:
     """Embedding-table cache of Sec. 4.4: a fixed number of table rows kept by least-recently-used replacement.
     Textbook LRU over the stream of token ids, in the order the tokens are embedded (sequence by sequence, position by

@@ -14,6 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libprism.so")
 
 OK, EINVAL, ECAP, EHIP, ENOMEM, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
+WFMT_PLAIN, WFMT_W4G128 = 0, 1
 DTYPE_FP32, DTYPE_BF16, DTYPE_F16 = 0, 1, 2
 MODE_DROP_ONLY, MODE_THREE_WAY, MODE_NO_PRUNING = 0, 1, 2
 EPI_STORE, EPI_RESIDUAL, EPI_SWIGLU, EPI_STORE_F32 = 0, 1, 2, 3
@@ -21,7 +22,7 @@ FATE_NOT_LIVE, FATE_DROPPED, FATE_DEFERRED, FATE_SELECTED = -1, 0, 1, 2
 MAX_CANDS, MAX_CLUSTERS, MAX_SEQ = 4096, 8, 8192
 
 EXPORTS = ["prism_create", "prism_select", "prism_set_forced_keep", "prism_destroy", "prism_strerror",
-           "prism_last_error", "prism_op_embed", "prism_op_rmsnorm", "prism_op_gemm", "prism_op_qkv_finish", "prism_op_qkv_project",
+           "prism_last_error", "prism_op_embed", "prism_op_rmsnorm", "prism_op_gemm", "prism_op_qkv_finish", "prism_op_qkv_project", "prism_w4_bytes", "prism_op_quantize_w4", "prism_op_dequantize_w4",
            "prism_op_attention", "prism_op_score", "prism_op_route", "prism_op_compact", "prism_op_topk"]
 
 
@@ -45,7 +46,7 @@ class prism_layer_weights(C.Structure):
 
 class prism_weights(C.Structure):
     _fields_ = [("embed", C.c_void_p), ("layers", C.POINTER(prism_layer_weights)), ("final_norm", C.c_void_p),
-                ("w_yes", C.c_void_p), ("w_no", C.c_void_p), ("layer_residency", C.c_int32), ("embed_residency", C.c_int32)]
+                ("w_yes", C.c_void_p), ("w_no", C.c_void_p), ("layer_residency", C.c_int32), ("embed_residency", C.c_int32), ("layer_format", C.c_int32)]
 
 
 class prism_options(C.Structure):
@@ -99,6 +100,10 @@ def lib() -> C.CDLL:
         _lib.prism_op_route.argtypes = [vp, i32, i32, i32, f32, vp, vp, vp]
         _lib.prism_op_compact.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp]
         _lib.prism_op_topk.argtypes = [vp, i32, i32, vp, vp, vp]
+        _lib.prism_w4_bytes.restype = C.c_int64
+        _lib.prism_w4_bytes.argtypes = [i32, i32]
+        _lib.prism_op_quantize_w4.argtypes = [vp, i32, i32, vp, vp]
+        _lib.prism_op_dequantize_w4.argtypes = [vp, i32, i32, i32, vp, vp]
     return _lib
 
 
@@ -155,13 +160,14 @@ class Prism:
     def __init__(self, model, weights, *, checkpoints: Sequence[int] = (), cv_threshold: float = 0.0, n_clusters: int = 3,
                  mode: int = MODE_DROP_ONLY, chunk_cands: int = 0, hbm_cap_bytes: int = 0, stream_weights: bool = False,
                  stream: Optional[int] = None, operand: str = "f16", offload_hidden: bool = False, embed_on_host: bool = False,
-                 embed_cache_rows: int = 0):
+                 embed_cache_rows: int = 0, w4: bool = False):
         """model: object with n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, rms_eps, rope_base,
         qk_norm, dtype ("fp32" | "bf16": storage type of the weights).  operand ("f16" | "bf16"): 16-bit type of the
         matrix-core operands when the weights are bf16.  weights: object with embed, final_norm, w_yes, w_no (device tensors) and
         layers: list of dicts of tensors (device, or pinned host when stream_weights).  embed_on_host: weights.embed is a
         pinned host tensor (w_yes / w_no stay device tensors) read through a device LRU cache of embed_cache_rows rows.
-        offload_hidden: the residual stream lives in pinned host memory, three chunks at a time on the device."""
+        offload_hidden: the residual stream lives in pinned host memory, three chunks at a time on the device.
+        w4: the seven matrices of every layer dict are uint8 blobs from quantize_w4 (gains stay bf16)."""
         self._ctx = C.c_void_p()
         m = prism_model(model.n_layers, model.hidden, model.n_q_heads, model.n_kv_heads, model.head_dim, model.ffn,
                         model.vocab, model.rms_eps, model.rope_base, DTYPE_FP32 if model.dtype == "fp32" else DTYPE_BF16,
@@ -172,7 +178,7 @@ class Prism:
                 setattr(layers[l], n, _ptr(lw[n]))
         self._keep = (weights, layers)      # borrowed by the library for the context's lifetime
         w = prism_weights(_ptr(weights.embed), layers, _ptr(weights.final_norm), _ptr(weights.w_yes), _ptr(weights.w_no),
-                          1 if stream_weights else 0, 1 if embed_on_host else 0)
+                          1 if stream_weights else 0, 1 if embed_on_host else 0, WFMT_W4G128 if w4 else WFMT_PLAIN)
         ck, ckp = _i32_array(list(checkpoints))
         o = prism_options(ckp, len(ck), cv_threshold, n_clusters, mode, chunk_cands, hbm_cap_bytes,
                           _stream() if stream is None else stream, DTYPE_BF16 if operand == "bf16" else DTYPE_F16,
@@ -266,6 +272,31 @@ def op_qkv_project(Xn, Wqkv, pos, max_pos, q_gain, k_gain, nq, nkv, hd, eps, bas
     _check(lib().prism_op_qkv_project(_dt(Xn), _ptr(Xn), _ptr(Wqkv), _ptr(pos), max_pos, _ptr(q_gain), _ptr(k_gain),
                                       Xn.shape[0], Xn.shape[1], nq, nkv, hd, eps, base, int(qk_norm), _ptr(QK), _ptr(Vt),
                                       _ptr(vt_col), vt_stride, _stream()))
+
+
+def w4_bytes(N: int, K: int) -> int:
+    return int(lib().prism_w4_bytes(N, K))
+
+
+def quantize_w4(W):
+    """W [N, K] bf16 device tensor -> uint8 device tensor holding the 4-bit blob (codes, then bf16 scales)."""
+    import torch
+    N, K = W.shape
+    blob = torch.empty(w4_bytes(N, K), dtype=torch.uint8, device=W.device)
+    _check(lib().prism_op_quantize_w4(_ptr(W), N, K, _ptr(blob), _stream()))
+    return blob
+
+
+def dequantize_w4(blob, N: int, K: int, out):
+    _check(lib().prism_op_dequantize_w4(_ptr(blob), N, K, _dt(out), _ptr(out), _stream()))
+
+
+MATRICES = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
+
+
+def quantize_layers_w4(layers):
+    """Layer dicts with the seven matrices replaced by their 4-bit blobs (device tensors in, device tensors out)."""
+    return [{k: (quantize_w4(v) if k in MATRICES else v) for k, v in l.items()} for l in layers]
 
 
 def op_attention(dtype, QK, Vt, vt_stride, cu_seqlens, vt_col0, nq, nkv, hd, out):

@@ -107,6 +107,12 @@ int launch_gemm_16_qkv(int dtype, const void *Xn, const void *Wqkv, int M, int K
 int launch_copy_rows(const void *src, const int32_t *src_idx, void *dst, const int32_t *dst_idx, int n, size_t row_bytes,
                      hipStream_t s);
 
+// 4-bit weight blobs (quant.hip): codes then bf16 scales, groups of 128 along K
+int64_t w4_blob_bytes(int64_t N, int64_t K);
+int launch_quantize_w4(const void *W_bf16, int N, int K, void *blob, hipStream_t s);
+int launch_dequantize_w4(const void *blob, int N, int K, int dtype, void *out, hipStream_t s);
+int launch_convert_bf16(const void *src, int64_t n, int dtype, void *dst, hipStream_t s);
+
 // cos/sin table for RoPE: tab[pos * (hd/2) + i] = (cos, sin)(pos * base^(-2i/hd)), evaluated in fp64
 int launch_rope_table(float2 *tab, int n_pos, int head_dim, float rope_base, hipStream_t s);
 // q/k per-head RMSNorm + RoPE from the fp32 projection.  fp32 mode: in place (QK == nullptr).  bf16 mode:

@@ -58,26 +58,27 @@ static LayerLayout make_layout(const prism_model &m) {
   return L;
 }
 
-struct CopyItem { size_t dst_off; const void *src; size_t bytes; };
+struct CopyItem { size_t dst_off; const void *src; size_t bytes; int64_t N, K; /* K = 0: a vector of N elements */ };
 
 static void layer_copy_items(const prism_model &m, const LayerLayout &L, const prism_layer_weights &w,
                              std::vector<CopyItem> &items) {
   const size_t e = dtype_size(m.dtype);
   const size_t H = m.hidden, Dq = (size_t)m.n_q_heads * m.head_dim, Dkv = (size_t)m.n_kv_heads * m.head_dim, F = m.ffn;
   items.clear();
-  items.push_back({L.attn_norm, w.attn_norm, H * e});
-  items.push_back({L.wqkv, w.wq, Dq * H * e});
-  items.push_back({L.wk, w.wk, Dkv * H * e});
-  items.push_back({L.wv, w.wv, Dkv * H * e});
+  const int64_t hd = m.head_dim;
+  items.push_back({L.attn_norm, w.attn_norm, H * e, (int64_t)H, 0});
+  items.push_back({L.wqkv, w.wq, Dq * H * e, (int64_t)Dq, (int64_t)H});
+  items.push_back({L.wk, w.wk, Dkv * H * e, (int64_t)Dkv, (int64_t)H});
+  items.push_back({L.wv, w.wv, Dkv * H * e, (int64_t)Dkv, (int64_t)H});
   if (m.qk_norm) {
-    items.push_back({L.q_norm, w.q_norm, (size_t)m.head_dim * e});
-    items.push_back({L.k_norm, w.k_norm, (size_t)m.head_dim * e});
+    items.push_back({L.q_norm, w.q_norm, (size_t)hd * e, hd, 0});
+    items.push_back({L.k_norm, w.k_norm, (size_t)hd * e, hd, 0});
   }
-  items.push_back({L.wo, w.wo, H * Dq * e});
-  items.push_back({L.ffn_norm, w.ffn_norm, H * e});
-  items.push_back({L.wgu, w.w_gate, F * H * e});
-  items.push_back({L.wu, w.w_up, F * H * e});
-  items.push_back({L.wd, w.w_down, H * F * e});
+  items.push_back({L.wo, w.wo, H * Dq * e, (int64_t)H, (int64_t)Dq});
+  items.push_back({L.ffn_norm, w.ffn_norm, H * e, (int64_t)H, 0});
+  items.push_back({L.wgu, w.w_gate, F * H * e, (int64_t)F, (int64_t)H});
+  items.push_back({L.wu, w.w_up, F * H * e, (int64_t)F, (int64_t)H});
+  items.push_back({L.wd, w.w_down, H * F * e, (int64_t)H, (int64_t)F});
 }
 
 }  // namespace prism
@@ -92,8 +93,12 @@ struct prism_ctx {
   std::vector<int32_t> checkpoints;
   LayerLayout lay;
   const void *embed = nullptr, *final_norm = nullptr, *w_yes = nullptr, *w_no = nullptr;
-  bool streamed = false;
-  std::vector<prism_layer_weights> host_layers;   // pinned-host tensors when streamed
+  bool streamed = false;                          // layer weights arrive from pinned host memory during every call
+  bool w4 = false;                                // layer matrices are 4-bit blobs, expanded into a slot right before use
+  bool two_slot = false;                          // streamed or w4: two layer slots, layer l + 2 prepared while l + 1 computes
+  std::vector<char *> packed_buf;                 // streamed + w4: landing buffers of the 4-bit layers (2)
+  size_t packed_bytes = 0;
+  std::vector<prism_layer_weights> host_layers;   // the caller's tensors (pinned host when streamed)
   std::vector<char *> layer_buf;                  // n_layers slots (resident) or 2 (streamed)
   hipStream_t stream = nullptr, copy_stream = nullptr;
   bool own_stream = false;
@@ -201,9 +206,38 @@ static int validate_model(const prism_model *m) {
   return PRISM_OK;
 }
 
+static size_t packed_layer_bytes(const prism_model &m, const LayerLayout &L, const prism_layer_weights &w) {
+  std::vector<CopyItem> items;
+  layer_copy_items(m, L, w, items);
+  size_t b = 0;
+  for (const CopyItem &it : items) b += (size_t)round_up(it.K ? w4_blob_bytes(it.N, it.K) : it.N * 2, 256);
+  return b;
+}
+
+// Fills layer slot `slot` with layer `layer` on stream s.  Plain weights: a handful of copies (device to device at
+// create, pinned host to device when streamed), then bf16 -> half in place if the operands are half.  4-bit weights:
+// the blobs (copied to the device first when they live on the host) are expanded into the slot, the norm gains
+// converted beside them.
 static int issue_layer_copy(prism_ctx *c, int layer, int slot, hipStream_t s, hipMemcpyKind kind, int64_t *bytes) {
   std::vector<CopyItem> items;
   layer_copy_items(c->m, c->lay, c->host_layers[layer], items);
+  if (c->w4) {
+    size_t poff = 0;
+    for (const CopyItem &it : items) {
+      const size_t sb = it.K ? (size_t)w4_blob_bytes(it.N, it.K) : (size_t)it.N * 2;
+      const void *src = it.src;
+      if (c->streamed) {
+        char *land = c->packed_buf[slot] + poff;
+        PRISM_HIP(hipMemcpyAsync(land, it.src, sb, hipMemcpyHostToDevice, s));
+        src = land;
+        poff += (size_t)round_up(sb, 256);
+        if (bytes) *bytes += (int64_t)sb;
+      }
+      if (it.K) PRISM_TRY(launch_dequantize_w4(src, (int)it.N, (int)it.K, c->op, c->layer_buf[slot] + it.dst_off, s));
+      else PRISM_TRY(launch_convert_bf16(src, it.N, c->op, c->layer_buf[slot] + it.dst_off, s));
+    }
+    return PRISM_OK;
+  }
   for (const CopyItem &it : items) {
     PRISM_HIP(hipMemcpyAsync(c->layer_buf[slot] + it.dst_off, it.src, it.bytes, kind, s));
     if (bytes) *bytes += (int64_t)it.bytes;
@@ -233,6 +267,13 @@ extern "C" int prism_create(const prism_model *model, const prism_weights *weigh
   PRISM_REQUIRE(options->operand == 0 || options->operand == PRISM_DTYPE_F16 || options->operand == PRISM_DTYPE_BF16,
                 PRISM_EINVAL, "prism_create: operand must be 0, PRISM_DTYPE_F16 or PRISM_DTYPE_BF16");
   PRISM_REQUIRE(weights->embed_residency == 0 || weights->embed_residency == 1, PRISM_EINVAL, "prism_create: embed_residency");
+  PRISM_REQUIRE(weights->layer_format == PRISM_WFMT_PLAIN || weights->layer_format == PRISM_WFMT_W4G128, PRISM_EINVAL,
+                "prism_create: layer_format");
+  if (weights->layer_format == PRISM_WFMT_W4G128) {
+    PRISM_REQUIRE(model->dtype == PRISM_DTYPE_BF16, PRISM_EUNSUPPORTED, "prism_create: 4-bit layer weights need the bf16 model type");
+    PRISM_REQUIRE(model->hidden % 128 == 0 && model->ffn % 128 == 0 && (model->n_q_heads * model->head_dim) % 128 == 0,
+                  PRISM_EUNSUPPORTED, "prism_create: 4-bit layer weights need hidden, ffn and n_q_heads*head_dim to be multiples of 128");
+  }
   PRISM_REQUIRE(options->offload_hidden == 0 || options->offload_hidden == 1, PRISM_EINVAL, "prism_create: offload_hidden");
   PRISM_REQUIRE(!options->offload_hidden || options->chunk_cands > 0, PRISM_EINVAL,
                 "prism_create: offload_hidden needs chunked execution (chunk_cands > 0)");
@@ -281,6 +322,8 @@ extern "C" int prism_create(const prism_model *model, const prism_weights *weigh
   c->lay = make_layout(*model);
   c->embed = weights->embed; c->final_norm = weights->final_norm; c->w_yes = weights->w_yes; c->w_no = weights->w_no;
   c->streamed = weights->layer_residency == 1;
+  c->w4 = weights->layer_format == PRISM_WFMT_W4G128;
+  c->two_slot = c->streamed || c->w4;
   c->host_layers.assign(weights->layers, weights->layers + model->n_layers);
   c->offload = options->offload_hidden == 1;
   c->embed_cached = weights->embed_residency == 1;
@@ -298,10 +341,15 @@ extern "C" int prism_create(const prism_model *model, const prism_weights *weigh
   }
   for (int i = 0; i < 4; ++i) CREATE_HIP(hipEventCreate(&c->ev_t[i]));
 
-  const int n_slots = c->streamed ? std::min(2, model->n_layers) : model->n_layers;
+  const int n_slots = c->two_slot ? std::min(2, model->n_layers) : model->n_layers;
   c->layer_buf.assign(n_slots, nullptr);
   for (int s = 0; s < n_slots; ++s) CREATE_TRY(dev_alloc(c, (void **)&c->layer_buf[s], c->lay.bytes));
-  if (!c->streamed) {
+  if (c->w4 && c->streamed) {
+    c->packed_bytes = packed_layer_bytes(*model, c->lay, c->host_layers[0]);
+    c->packed_buf.assign(n_slots, nullptr);
+    for (int s = 0; s < n_slots; ++s) CREATE_TRY(dev_alloc(c, (void **)&c->packed_buf[s], c->packed_bytes));
+  }
+  if (!c->two_slot) {
     for (int l = 0; l < model->n_layers; ++l) CREATE_TRY(issue_layer_copy(c, l, l, c->stream, hipMemcpyDeviceToDevice, nullptr));
   }
   CREATE_TRY(dev_alloc(c, (void **)&c->rope_tab, (size_t)PRISM_MAX_SEQ * (model->head_dim / 2) * sizeof(float2)));
@@ -348,6 +396,7 @@ extern "C" void prism_destroy(prism_ctx *c) {
   if (c->xin_stream) (void)hipStreamSynchronize(c->xin_stream);
   if (c->xout_stream) (void)hipStreamSynchronize(c->xout_stream);
   for (char *p : c->layer_buf) if (p) (void)hipFree(p);
+  for (char *p : c->packed_buf) if (p) (void)hipFree(p);
   for (void *p : {(void *)c->Xo[0], (void *)c->Xo[1], (void *)c->Xo[2], (void *)c->d_cache, (void *)c->d_estage}) if (p) (void)hipFree(p);
   if (c->h_X) (void)hipHostFree(c->h_X);
   if (c->h_estage) (void)hipHostFree(c->h_estage);
@@ -841,8 +890,8 @@ extern "C" int prism_select(prism_ctx *c, const int32_t *query_tokens, int32_t q
   }
 
   int64_t bytes_streamed = 0, token_layers = 0;
-  if (c->streamed) {
-    // Sec. 4.2: two buffers; layer l computes from slot l % 2 while layer l + 1 arrives in the other
+  if (c->two_slot) {
+    // Sec. 4.2: two buffers; layer l computes from slot l % 2 while layer l + 1 arrives (or is expanded) in the other
     for (int l = 0; l < std::min(2, m.n_layers); ++l) {
       PRISM_TRY(issue_layer_copy(c, l, l, c->copy_stream, hipMemcpyHostToDevice, &bytes_streamed));
       PRISM_HIP(hipEventRecord(c->ev_ready[l], c->copy_stream));
@@ -882,8 +931,8 @@ extern "C" int prism_select(prism_ctx *c, const int32_t *query_tokens, int32_t q
   };
 
   for (int l = 0; l < m.n_layers && !terminated; ++l) {
-    const int slot = c->streamed ? l % 2 : l;
-    if (c->streamed) PRISM_HIP(hipStreamWaitEvent(s, c->ev_ready[slot], 0));
+    const int slot = c->two_slot ? l % 2 : l;
+    if (c->two_slot) PRISM_HIP(hipStreamWaitEvent(s, c->ev_ready[slot], 0));
     if (timed) PRISM_HIP(hipEventRecord(c->ev_layer[2 * l], s));
     // known before the layer runs: will its output be scored for pruning, and is it the last one
     while (next_ckpt < c->checkpoints.size() && c->checkpoints[next_ckpt] < l + 1) ++next_ckpt;
@@ -895,7 +944,7 @@ extern "C" int prism_select(prism_ctx *c, const int32_t *query_tokens, int32_t q
     if (timed) PRISM_HIP(hipEventRecord(c->ev_layer[2 * l + 1], s));
     token_layers += p.T;
     layers_run = l + 1;
-    if (c->streamed && l + 2 < m.n_layers) {
+    if (c->two_slot && l + 2 < m.n_layers) {
       PRISM_HIP(hipEventRecord(c->ev_free[slot], s));
       PRISM_HIP(hipStreamWaitEvent(c->copy_stream, c->ev_free[slot], 0));
       PRISM_TRY(issue_layer_copy(c, l + 2, slot, c->copy_stream, hipMemcpyHostToDevice, &bytes_streamed));
@@ -1004,7 +1053,7 @@ extern "C" int prism_select(prism_ctx *c, const int32_t *query_tokens, int32_t q
     if (timed) PRISM_HIP(hipEventRecord(c->ev_t[1], s));
     PRISM_HIP(hipStreamSynchronize(s));
   }
-  if (c->streamed) PRISM_HIP(hipStreamSynchronize(c->copy_stream));
+  if (c->two_slot) PRISM_HIP(hipStreamSynchronize(c->copy_stream));
   if (c->offload) {
     PRISM_HIP(hipStreamSynchronize(c->xin_stream));
     PRISM_HIP(hipStreamSynchronize(c->xout_stream));
@@ -1111,6 +1160,16 @@ extern "C" int prism_op_qkv_project(int32_t dtype, const void *Xn, const void *W
   PRISM_TRY(launch_gemm_16_qkv(dtype, Xn, Wqkv, T, hidden, head_dim, e, s));
   PRISM_HIP(hipStreamSynchronize(s));   // the table is freed on return
   return PRISM_OK;
+}
+
+extern "C" int64_t prism_w4_bytes(int32_t N, int32_t K) { return N > 0 && K > 0 && K % 128 == 0 ? w4_blob_bytes(N, K) : -1; }
+
+extern "C" int prism_op_quantize_w4(const void *W, int32_t N, int32_t K, void *blob, void *stream) {
+  return launch_quantize_w4(W, N, K, blob, (hipStream_t)stream);
+}
+
+extern "C" int prism_op_dequantize_w4(const void *blob, int32_t N, int32_t K, int32_t dtype, void *out, void *stream) {
+  return launch_dequantize_w4(blob, N, K, dtype, out, (hipStream_t)stream);
 }
 
 extern "C" int prism_op_attention(int32_t dtype, const void *QK, const void *Vt, int64_t vt_stride, const int32_t *cu,

@@ -36,7 +36,7 @@ def test_struct_layouts_match_the_header():
     # sizes implied by the header's field lists (natural alignment, LP64)
     assert ctypes.sizeof(binding.prism_model) == 11 * 4
     assert ctypes.sizeof(binding.prism_layer_weights) == 11 * 8
-    assert ctypes.sizeof(binding.prism_weights) == 6 * 8
+    assert ctypes.sizeof(binding.prism_weights) == 7 * 8
     assert ctypes.sizeof(binding.prism_options) == 8 + 4 * 6 + 8 + 8 + 4 * 4
     assert ctypes.sizeof(binding.prism_report) == 3 * 4 + 4 + 10 * 8 + 3 * 8 + 3 * 8 + 4 + 6 * 4 + 4 + 6 * 8 + 6 * 8 + 3 * 8
 

@@ -171,3 +171,41 @@ def test_lru_invariants():
     c2.run([5, 6, 7])
     # 7, 6, 5 hit (5 newest); 8 evicts 7, the oldest; 7 misses again
     assert c2.run([7, 6, 5, 8, 7]) == (3, 2)
+
+
+# ---- 4-bit weights (Sec. 6, the quantised variant): the oracle's quantiser against a hand-worked group and its invariants
+
+def test_w4_hand_worked_group():
+    w = np.zeros((1, 128), np.float32)
+    w[0, :5] = [0.7, -0.35, 0.1, -0.05, 0.0499]
+    codes, scales = O.quantize_w4(w)
+    # 0.7 / 7 = 0.1 -> bf16 0.10009765625 (0x3DCD); 0.7 / s = 6.993 -> 7; -0.35 / s = -3.4966 -> -3; 0.1 / s = 0.999 -> 1;
+    # -0.05 / s = -0.4995 -> 0; 0.0499 / s = 0.4985 -> 0
+    assert scales.shape == (1, 1) and float(scales[0, 0]) == 0.10009765625
+    assert codes[0, :5].tolist() == [7, -3, 1, 0, 0] and not codes[0, 5:].any()
+    back = O.dequantize_w4(codes, scales)
+    assert back[0, :3].tolist() == [7 * 0.10009765625, -3 * 0.10009765625, 0.10009765625]
+
+
+def test_w4_invariants():
+    rng = np.random.default_rng(11)
+    w = O.round_operand(rng.normal(0, 0.02, size=(24, 512)), "bf16").astype(np.float32)
+    w[3, 128:256] = 0                                         # an all-zero group
+    codes, scales = O.quantize_w4(w)
+    assert codes.min() >= -7 and codes.max() <= 7
+    assert np.all(scales > 0) and np.array_equal(O.round_operand(scales, "bf16"), scales.astype(np.float64))
+    assert float(scales[3, 1]) == 1.0 and not codes[3, 128:256].any()
+    back = O.dequantize_w4(codes, scales)
+    # nearest code: the error is at most half a step, except where the largest element was clamped to +-7
+    err = np.abs(back - w).reshape(24, 4, 128)
+    step = scales[:, :, None].astype(np.float64)
+    assert np.all(err <= 0.5 * step * (1 + 2 ** -20) + np.abs(w).reshape(24, 4, 128) * 2 ** -7)
+    # the largest element of every non-zero group sits on the outermost code
+    amax = np.argmax(np.abs(w).reshape(24, 4, 128), axis=2)
+    top = np.take_along_axis(codes.reshape(24, 4, 128), amax[:, :, None], axis=2)[:, :, 0]
+    nz = np.abs(w).reshape(24, 4, 128).max(axis=2) > 0
+    assert np.all(np.abs(top[nz]) == 7)
+    # the dequantised weights are exact in half precision and quantise to themselves
+    assert np.array_equal(back.astype(np.float16).astype(np.float64), back)
+    c2, s2 = O.quantize_w4(back.astype(np.float32))
+    assert np.array_equal(c2, codes) and np.array_equal(s2, scales)
