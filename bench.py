@@ -83,6 +83,7 @@ def main():
     ap.add_argument("--tau", type=float, default=None, help="dispersion threshold (default: the workload's, 0)")
     ap.add_argument("--lean", action="store_true",
                     help="hidden-state offload + embedding-table cache (needs a chunked workload, e.g. cfg5_8b_stream)")
+    ap.add_argument("--w4", action="store_true", help="4-bit layer weights (quantised on the device before the timed region)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unpruned", action="store_true")
     args = ap.parse_args()
@@ -113,6 +114,15 @@ def main():
         wt_for_oracle = dev
     else:
         wt = wt_for_oracle = W.make_weights(w, "cuda")
+    if args.w4:
+        class Q4:                             # the same weights with every layer matrix as a 4-bit blob
+            pass
+        q4 = Q4()
+        q4.embed, q4.final_norm, q4.w_yes, q4.w_no = wt.embed, wt.final_norm, wt_for_oracle.w_yes, wt_for_oracle.w_no
+        q4.layers = B.quantize_layers_w4(wt_for_oracle.layers)
+        if w.stream_weights:
+            q4.layers = [{k: v.to("cpu").pin_memory() for k, v in l.items()} for l in q4.layers]
+        wt = q4
     if args.lean:
         class HostTable:                      # embedding table in pinned host memory, the two head rows on the device
             pass
@@ -125,7 +135,7 @@ def main():
     t_gen = time.perf_counter() - t_gen
     opts = dict(checkpoints=w.checkpoints, cv_threshold=w.cv_threshold, n_clusters=w.n_clusters, chunk_cands=w.chunk_cands,
                 hbm_cap_bytes=w.hbm_cap_bytes, stream_weights=w.stream_weights, operand=args.operand,
-                offload_hidden=args.lean, embed_on_host=args.lean)
+                offload_hidden=args.lean, embed_on_host=args.lean, w4=args.w4)
     p = B.Prism(m, wt, **opts)
 
     for _ in range(args.warmup):
@@ -183,7 +193,8 @@ def main():
                                f"ffn {m.ffn}, vocab {m.vocab}; query {w.query_len} tok, {w.n_cands} candidates, "
                                f"{int(sum(len(c) + len(q) for c in cands))} tokens in all; K={w.K}; "
                                f"checkpoints after layers {w.checkpoints}; k={w.n_clusters} clusters, tau={w.cv_threshold}, drop-only; "
-                               f"weights {m.dtype}, matrix-core operands {op_t}, fp32 accumulation and residual",
+                               f"weights {'4-bit (groups of 128) expanded to ' + op_t if args.w4 else m.dtype}, matrix-core operands {op_t}, "
+                               f"fp32 accumulation and residual",
                    "n_cands": w.n_cands, "K": w.K, "seed": w.seed, "chunk_cands": w.chunk_cands, "stream_weights": w.stream_weights},
         "topk_latency_ms": round(ms_per_step, 3),
         "unpruned_latency_ms": None if unpruned_ms is None else round(unpruned_ms, 3),

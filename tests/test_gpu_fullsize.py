@@ -206,3 +206,26 @@ def test_cfg5_offload_and_embedding_cache_are_bit_identical_and_leaner(weights_8
     assert rep1.embed_rows_hit + rep1.embed_rows_missed == sum(len(q) + len(c) for c in cands)
     # the first 40 sequences of the stream, replayed by the oracle, give a lower bound on misses of the full stream's prefix
     assert rep1.embed_rows_missed >= lru.run(sample)[1]
+
+
+def test_cfg5_with_4bit_layers_streams_a_quarter_of_the_bytes(weights_8b):
+    """The 500-candidate pool with every layer matrix as a 4-bit blob in pinned host memory.  The numbers differ from
+    the bf16 run (other weights), so what is checked is what holds for any weights: the routing rule at every check, the
+    final ranking, and the bytes that travelled."""
+    w = W.WORKLOADS["cfg5_8b_stream"]
+    q, cands = W.make_tokens(w)
+
+    class Q4:
+        pass
+    q4 = Q4()
+    q4.embed, q4.final_norm, q4.w_yes, q4.w_no = weights_8b.embed, weights_8b.final_norm, weights_8b.w_yes, weights_8b.w_no
+    q4.layers = [{k: v.cpu().pin_memory() for k, v in l.items()} for l in B.quantize_layers_w4(weights_8b.layers)]
+    p = B.Prism(w.model, q4, checkpoints=w.checkpoints, chunk_cands=w.chunk_cands, hbm_cap_bytes=w.hbm_cap_bytes,
+                stream_weights=True, w4=True)
+    idx, scores, rep = p.select(q, cands, w.K)
+    p.destroy()
+    _rule1_and_topk(w, idx, scores, rep)
+    plain = w.model.n_layers * sum(v.numel() * 2 for v in weights_8b.layers[0].values())
+    assert 0.25 * plain < rep.bytes_streamed < 0.27 * plain
+    assert rep.peak_hbm_bytes <= w.hbm_cap_bytes
+    _progress(f"cfg5 w4: {rep.ms_total:.0f} ms, streamed {rep.bytes_streamed / 1e9:.2f} GB of {plain / 1e9:.2f} GB, survivors {rep.n_after.tolist()}")
