@@ -135,11 +135,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_16_kernel(const OT *__restri
   const int nk = K / BK;
 
   // The 256x256 / 2x2-wave configuration runs the hand-scheduled loop; other shapes take the compiler's schedule.
-#ifdef PRISM_NO_HAND_SCHED
-  constexpr bool kHandScheduled = false;
-#else
   constexpr bool kHandScheduled = BM == 256 && BN == 256 && WM == 2 && WN == 2;
-#endif
   // interior tiles only: the hand-scheduled loop assumes that the tile's rows of A and W all exist
   const bool interior = m0 + BM <= M && n0 + (EPI == PRISM_EPI_SWIGLU ? BN / 2 : BN) <= F;
   if (kHandScheduled && interior) {

@@ -22,10 +22,6 @@ slice bodies free of branches.
 
 The W fragment is the first MFMA operand, so accumulator tiles come out transposed (a lane owns one row of A).
 """
-import os
-
-EXP = os.environ.get("PRISM_KLOOP_EXPERIMENT", "")   # timing experiments only (results become meaningless)
-
 # ---- register plan (all clobbered) ----
 GA = [20 + j for j in range(8)]         # byte offset into A of the chunk this lane fetches in load instruction j
 GB = [28 + j for j in range(8)]
@@ -44,10 +40,8 @@ def v4(r):
     return f"v[{r}:{r + 3}]"
 
 
-def reads(fs, k, stage, b_off, initial=False):
+def reads(fs, k, stage, b_off):
     """The 8 fragment reads of step k from `stage` into fragment set fs, in the order a0,b0,b1,b2,b3,a1,a2,a3."""
-    if "noreads" in EXP and not initial:
-        return ["s_nop 0"] * 8
     ra = lambda i: f"ds_read_b128 {v4(F[fs]['A'][i])}, v{AA[k]} offset:{stage * STAGE + A_FRAG_OFF[i]}"
     rb = lambda j: f"ds_read_b128 {v4(F[fs]['B'][j])}, v{AB[k]} offset:{stage * STAGE + b_off[j]}"
     return [ra(0), rb(0), rb(1), rb(2), rb(3), ra(1), ra(2), ra(3)]
@@ -61,8 +55,6 @@ def mfma(mn, fs, i, j):
 def loads(which, stage):
     """8 direct-to-LDS loads of this wave for one operand: M0 = LDS destination (wave base %20 / %21 + 1 KiB per
     instruction + stage), source = running base s[20:21] / s[22:23] + the lane's byte offset."""
-    if "noloads" in EXP:
-        return ["s_nop 0"] * 8
     base, lds, off = ("s[20:21]", "%20", GA) if which == "A" else ("s[22:23]", "%21", GB)
     return [f"s_add_u32 m0, {lds}, {stage * STAGE + j * 1024}\\n s_nop 0\\n global_load_lds_dwordx4 v{off[j]}, {base}"
             for j in range(8)]
@@ -103,9 +95,9 @@ def slice_body(mn, cur, b_off):
         waits = WAITS if k < 3 else WAITS_LAST
         for m, (i, j) in enumerate(order, start=1):
             if k == 3 and m == 9:
-                out += ["s_waitcnt vmcnt(0) lgkmcnt(0)"] + ([] if "nobarrier" in EXP else ["s_barrier"])
-                out += reads(0, 0, nxt, b_off, True)                            # first fragments of the next slice
-            if waits.get(m) is not None and "nowaits" not in EXP:
+                out += ["s_waitcnt vmcnt(0) lgkmcnt(0)", "s_barrier"]
+                out += reads(0, 0, nxt, b_off)                                  # first fragments of the next slice
+            if waits.get(m) is not None:
                 out.append(f"s_waitcnt lgkmcnt({waits[m]})")
             out.append(mfma(mn, fs, i, j))
             if m % 2 == 1 and behind_odd:
@@ -134,7 +126,7 @@ def kloop(mn, b_off):
     s += ["s_mov_b64 s[20:21], %23", "s_mov_b64 s[22:23], %24", "s_mov_b32 s24, %25", "s_sub_u32 s26, %25, 1", "s_mov_b32 s25, 0", "s_mov_b32 s29, 0"]
     # ---- prologue: slice 0 -> LDS stage 0, first fragments
     s += loads("A", 0) + loads("B", 0) + advance("A") + advance("B")
-    s += ["s_waitcnt vmcnt(0)", "s_barrier"] + reads(0, 0, 0, b_off, True)
+    s += ["s_waitcnt vmcnt(0)", "s_barrier"] + reads(0, 0, 0, b_off)
     s += loads("A", 1) + advance("A")                                           # A half of slice 1
     s += ["L_loop_%=:"] + slice_body(mn, 0, b_off)
     s += ["s_sub_u32 s24, s24, 1", "s_cmp_eq_u32 s24, 0", "s_cbranch_scc1 L_done_%="]

@@ -49,3 +49,13 @@ def test_strerror_and_argument_errors_without_a_gpu(built):
     assert built.prism_create(None, None, None, None) == binding.EINVAL
     assert built.prism_select(None, None, 0, None, None, 0, 0, None, None, None, None) == binding.EINVAL
     built.prism_destroy(None)
+
+
+def test_generated_gemm_loop_is_in_sync_with_its_generator():
+    """gemm_16_kloop.inc is committed next to the script that writes it; the two must not drift apart."""
+    import os
+    import subprocess
+    import sys
+    csrc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2510_15620_amd", "csrc")
+    out = subprocess.run([sys.executable, os.path.join(csrc, "gen_gemm_kloop.py")], capture_output=True, text=True, check=True).stdout
+    assert out == open(os.path.join(csrc, "gemm_16_kloop.inc")).read()
