@@ -78,6 +78,10 @@ def lib() -> C.CDLL:
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise PrismError(EHIP, f"{LIB_PATH} is not built; run `python -m paper_2510_15620_amd.build`")
+        # PyTorch ships its own copy of the HIP runtime.  Streams and device pointers cross between it and this library,
+        # so both must use ONE runtime instance: load PyTorch's first and let the library bind to it.  (Loaded the other
+        # way round, the second copy finds no device.)
+        import torch  # noqa: F401
         _lib = C.CDLL(LIB_PATH)
         _lib.prism_strerror.restype = C.c_char_p
         _lib.prism_last_error.restype = C.c_char_p
