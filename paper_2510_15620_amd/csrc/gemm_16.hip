@@ -69,6 +69,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_16_kernel(const OT *__restri
   const int tile_m = first_m + (bid % (GM * nN)) % gsz, tile_n = (bid % (GM * nN)) / gsz;
   const int m0 = tile_m * BM;
   const int F = EPI == PRISM_EPI_SWIGLU ? N / 2 : N;         // output columns
+  constexpr int BNO = EPI == PRISM_EPI_SWIGLU ? BN / 2 : BN; // output columns per tile
   const int n0 = tile_n * (EPI == PRISM_EPI_SWIGLU ? BN / 2 : BN);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -136,6 +137,29 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_16_kernel(const OT *__restri
 
   const int nk = K / BK;
 
+  // ---- epilogue geometry (see the epilogue): everything it reads or writes goes along the rows, 16 bytes per lane.
+  //      Residual epilogue: the old values of a 32-row block are requested one block ahead.  (Requesting the first
+  //      block before the K loop was tried: holding 64 registers across the loop makes the compiler spill.)
+  constexpr bool kF32Out = EPI == PRISM_EPI_RESIDUAL || EPI == PRISM_EPI_STORE_F32;
+  constexpr int ES = kF32Out ? 4 : 2;                               // bytes per output element
+  constexpr int OUTW = EPI == PRISM_EPI_SWIGLU ? WNT / 2 : WNT;    // output columns of the wave
+  constexpr int RB = OUTW * ES, CPR = RB / 16;                      // bytes / 16-byte chunks per staged row
+  constexpr int NR = 1024 / RB, NI = 32 / NR;                       // rows per instruction, instructions per 32-row block
+  const int f_row = lane / CPR, f_chunk = lane % CPR;               // lane -> (row within an instruction, chunk)
+  const bool full_n = n0 + BNO <= F && (F * ES) % 16 == 0;
+  f32x4 old[2][EPI == PRISM_EPI_RESIDUAL ? NI : 1];
+  float *xo = reinterpret_cast<float *>(out_) + n0 + wn * OUTW + f_chunk * 4;
+  auto load_old = [&](int i) __attribute__((always_inline)) {
+    if constexpr (EPI == PRISM_EPI_RESIDUAL) {
+#pragma unroll
+      for (int rr = 0; rr < NI; ++rr) {
+        const int row = m0 + wm * WMT + i * 32 + rr * NR + f_row;
+        old[i & 1][rr] = *reinterpret_cast<const f32x4 *>(xo + (int64_t)(row < M ? row : M - 1) * N);
+      }
+    }
+  };
+
+
   // The 256x256 / 2x2-wave configuration runs the hand-scheduled loop; other shapes take the compiler's schedule.
   constexpr bool kHandScheduled = BM == 256 && BN == 256 && WM == 2 && WN == 2;
   // interior tiles only: the hand-scheduled loop assumes that the tile's rows of A and W all exist
@@ -200,78 +224,22 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_16_kernel(const OT *__restri
 
   // ---- epilogue.  The W fragment was the instruction's first operand, so the 32x32 accumulator tile is
   //      transposed: a lane holds ONE row of A, m = lane % 32, and the output columns
-  //      n = (e / 4) * 8 + (lane / 32) * 4 + e % 4, e = 0..15: four runs of 4 consecutive columns, which
-  //      are read / written as 16-byte (fp32) or 8-byte (16-bit) vectors.
-  const int m_in = lane & 31, n_in = (lane >> 5) * 4;
-  const bool full_n = n0 + (EPI == PRISM_EPI_SWIGLU ? BN / 2 : BN) <= F && F % 4 == 0;
-  if constexpr (EPI == PRISM_EPI_RESIDUAL) {
-    if (full_n) {
-      // Read-modify-write of the fp32 stream, software-pipelined over the wave's row blocks: the 16 vector loads of
-      // block i + 1 are in flight while block i is added and stored, so the tile pays the memory latency about twice
-      // instead of once per accumulator tile.
-      f32x4 old[2][TN][4];
-      auto rowptr = [&](int i) {
-        const int row = m0 + wm * WMT + i * 32 + m_in;
-        return reinterpret_cast<float *>(out_) + (int64_t)(row < M ? row : M - 1) * N + n0 + wn * WNT + n_in;
-      };
-      auto load_block = [&](int i, int set) {
-        const float *o = rowptr(i);
+  //      n = (e / 4) * 8 + (lane / 32) * 4 + e % 4, e = 0..15: four runs of 4 consecutive columns.
+  //      Written straight from that layout, one store instruction touches 32 rows with 16-32 bytes in each, and
+  //      the number of cache lines an instruction touches - not the bytes - is what the memory path charges for
+  //      (measured: 12-29 us per 256 x 256 tile, a tenth to a fifth of the tile's time).  So every block of 32 rows goes
+  //      through LDS, which is free once the K loop is done: lanes write their row's values, then read back 16 bytes
+  //      each along the rows, so that an instruction reads or writes whole lines (2-8 complete rows of the wave's
+  //      columns).  LDS requests of one wave are served in order, so no barrier is needed between the two phases.
+  if constexpr (EPI == kEpiQkv) {
+    // The q/k/v epilogue writes straight from the accumulator layout: it is bound by its arithmetic (norm, rotation,
+    // conversions: about 7 instructions per value), not by its stores (measured: staging it through LDS costs 4 %).
+    const int m_in = lane & 31, n_in = (lane >> 5) * 4;
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-          for (int g = 0; g < 4; ++g) old[set][j][g] = *reinterpret_cast<const f32x4 *>(o + j * 32 + g * 8);
-      };
-      load_block(0, 0);
-#pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        if (i + 1 < TM) load_block(i + 1, (i + 1) & 1);
-        float *o = rowptr(i);
-        const bool live = m0 + wm * WMT + i * 32 + m_in < M;
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            f32x4 v = old[i & 1][j][g];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) v[q] += acc[i][j][g * 4 + q];
-            if (live) *reinterpret_cast<f32x4 *>(o + j * 32 + g * 8) = v;
-          }
-      }
-      return;
-    }
-  }
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int row = m0 + wm * WMT + i * 32 + m_in;
-    if (row >= M) continue;
-    if (EPI == PRISM_EPI_SWIGLU) {
-      OT *orow = reinterpret_cast<OT *>(out_) + (int64_t)row * F;
-#pragma unroll
-      for (int j = 0; j < TN / 2; ++j) {
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int col = n0 + wn * (WNT / 2) + j * 32 + g * 8 + n_in;
-          typename Mfma<OT>::vec4 v;
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const float gt = acc[i][j][g * 4 + q], up = acc[i][j + TN / 2][g * 4 + q];
-            v[q] = from_f32<OT>(gt / (1.0f + __expf(-gt)) * up);
-          }
-          if (full_n) *reinterpret_cast<typename Mfma<OT>::vec4 *>(orow + col) = v;
-          else
-            for (int q = 0; q < 4; ++q) if (col + q < F) orow[col + q] = v[q];
-        }
-      }
-    } else if (EPI == PRISM_EPI_RESIDUAL) {
-      float *orow = reinterpret_cast<float *>(out_) + (int64_t)row * N;      // ragged N only (see above)
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int col0 = n0 + wn * WNT + j * 32 + n_in;
-        for (int g = 0; g < 4; ++g)
-          for (int q = 0; q < 4; ++q)
-            if (col0 + g * 8 + q < N) orow[col0 + g * 8 + q] += acc[i][j][g * 4 + q];
-      }
-    } else if (EPI == kEpiQkv) {
+    for (int i = 0; i < TM; ++i) {
+      const int row = m0 + wm * WMT + i * 32 + m_in;
+      if (row >= M) continue;
+      {
       // The wave's 128 columns are one head.  A row's 128 values sit in lanes l and l ^ 32 (64 each); the rotate-half
       // partner of column d is d + 64 = the same register of accumulator tile j + 2.
       if constexpr (EPI == kEpiQkv) {
@@ -330,31 +298,124 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_16_kernel(const OT *__restri
             }
         }
       }
-    } else {
+      }
+    }
+    return;
+  }
+  __syncthreads();              // every wave's operand loads have landed and nobody reads operands any more
+  const int m_in = lane & 31, n_in = (lane >> 5) * 4;
+  constexpr int SWZ = CPR >= 16 ? 15 : CPR - 1;                     // chunk rotation by row: spreads a column of 16-byte
+                                                                    // writes (one per row) over the banks
+  static_assert(32 * RB <= 2 * (BM + BN) * BK * (int)sizeof(OT) / NW, "staging block must fit the wave's share of LDS");
+  unsigned char *stg = smem + wave * (2 * (BM + BN) * BK * (int)sizeof(OT) / NW);
+  // values for columns n .. n + 3 (n a multiple of 4, within the wave's columns) of staged row m
+  auto put32 = [&](int m, int n, const f32x4 &v) __attribute__((always_inline)) {
+    *reinterpret_cast<f32x4 *>(stg + m * RB + (((n >> 2) ^ (m & SWZ)) << 4)) = v;
+  };
+  auto put16 = [&](int m, int n, const typename Mfma<OT>::vec4 &v) __attribute__((always_inline)) {
+    *reinterpret_cast<typename Mfma<OT>::vec4 *>(stg + m * RB + (((n >> 3) ^ (m & SWZ)) << 4) + (n & 4) * 2) = v;
+  };
+  auto staged = [&](int rr) __attribute__((always_inline)) {
+    const int r = rr * NR + f_row;
+    return *reinterpret_cast<const uint4 *>(stg + r * RB + ((f_chunk ^ (r & SWZ)) << 4));
+  };
+  // Flushes the staged block to rows row0 + r of a row-major destination (row pitch `pitch` bytes, the wave's first
+  // column at byte col_byte0 of a row).
+  auto flush_store = [&](unsigned char *dst, int64_t pitch, int64_t col_byte0, int row0) __attribute__((always_inline)) {
 #pragma unroll
-      for (int j = 0; j < TN; ++j) {
+    for (int rr = 0; rr < NI; ++rr) {
+      const int row = row0 + rr * NR + f_row;
+      const uint4 v = staged(rr);
+      if (row < M) *reinterpret_cast<uint4 *>(dst + (int64_t)row * pitch + col_byte0 + f_chunk * 16) = v;
+    }
+  };
+
+  if (full_n) {
+    load_old(0);
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int col = n0 + wn * WNT + j * 32 + g * 8 + n_in;
-          if (EPI == PRISM_EPI_STORE_F32) {
-            float *o = reinterpret_cast<float *>(out_) + (int64_t)row * N + col;
+    for (int i = 0; i < TM; ++i) {
+      const int row0 = m0 + wm * WMT + i * 32;                       // first row of the block
+      if (EPI == PRISM_EPI_SWIGLU) {
+#pragma unroll
+        for (int j = 0; j < TN / 2; ++j)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            typename Mfma<OT>::vec4 v;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const float gt = acc[i][j][g * 4 + q], up = acc[i][j + TN / 2][g * 4 + q];
+              v[q] = from_f32<OT>(gt / (1.0f + __expf(-gt)) * up);
+            }
+            put16(m_in, j * 32 + g * 8 + n_in, v);
+          }
+        flush_store(reinterpret_cast<unsigned char *>(out_), (int64_t)F * 2, (int64_t)(n0 + wn * OUTW) * 2, row0);
+      } else if (EPI == PRISM_EPI_RESIDUAL) {
+        // read-modify-write of the fp32 stream, whole lines per instruction; the loads of the next block are requested
+        // before this block is staged, so the tile pays the memory latency once, not per block
+        if (i + 1 < TM) load_old(i + 1);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
             f32x4 v;
 #pragma unroll
             for (int q = 0; q < 4; ++q) v[q] = acc[i][j][g * 4 + q];
-            if (full_n) *reinterpret_cast<f32x4 *>(o) = v;
-            else
-              for (int q = 0; q < 4; ++q) if (col + q < N) o[q] = v[q];
-          } else {
-            OT *o = reinterpret_cast<OT *>(out_) + (int64_t)row * N + col;
-            typename Mfma<OT>::vec4 v;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) v[q] = from_f32<OT>(acc[i][j][g * 4 + q]);
-            if (full_n) *reinterpret_cast<typename Mfma<OT>::vec4 *>(o) = v;
-            else
-              for (int q = 0; q < 4; ++q) if (col + q < N) o[q] = v[q];
+            put32(m_in, j * 32 + g * 8 + n_in, v);
           }
+#pragma unroll
+        for (int rr = 0; rr < NI; ++rr) {
+          const int row = row0 + rr * NR + f_row;
+          const uint4 u = staged(rr);
+          f32x4 v = old[i & 1][rr];
+          v[0] += __uint_as_float(u.x); v[1] += __uint_as_float(u.y); v[2] += __uint_as_float(u.z); v[3] += __uint_as_float(u.w);
+          if (row < M) *reinterpret_cast<f32x4 *>(xo + (int64_t)row * N) = v;
         }
+      } else {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            if (EPI == PRISM_EPI_STORE_F32) {
+              f32x4 v;
+#pragma unroll
+              for (int q = 0; q < 4; ++q) v[q] = acc[i][j][g * 4 + q];
+              put32(m_in, j * 32 + g * 8 + n_in, v);
+            } else {
+              typename Mfma<OT>::vec4 v;
+#pragma unroll
+              for (int q = 0; q < 4; ++q) v[q] = from_f32<OT>(acc[i][j][g * 4 + q]);
+              put16(m_in, j * 32 + g * 8 + n_in, v);
+            }
+          }
+        flush_store(reinterpret_cast<unsigned char *>(out_), (int64_t)N * ES, (int64_t)(n0 + wn * OUTW) * ES, row0);
       }
+    }
+    return;
+  }
+
+  // ---- ragged last column tile (N not a multiple of the tile, or rows not 16-byte aligned): element by element
+  if constexpr (EPI != kEpiQkv) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int row = m0 + wm * WMT + i * 32 + m_in;
+      if (row >= M) continue;
+#pragma unroll
+      for (int j = 0; j < (EPI == PRISM_EPI_SWIGLU ? TN / 2 : TN); ++j)
+        for (int g = 0; g < 4; ++g)
+          for (int q = 0; q < 4; ++q) {
+            const int col = n0 + wn * OUTW + j * 32 + g * 8 + n_in + q;
+            if (col >= F) continue;
+            if (EPI == PRISM_EPI_SWIGLU) {
+              const float gt = acc[i][j][g * 4 + q], up = acc[i][j + TN / 2][g * 4 + q];
+              reinterpret_cast<OT *>(out_)[(int64_t)row * F + col] = from_f32<OT>(gt / (1.0f + __expf(-gt)) * up);
+            } else if (EPI == PRISM_EPI_RESIDUAL) {
+              reinterpret_cast<float *>(out_)[(int64_t)row * N + col] += acc[i][j][g * 4 + q];
+            } else if (EPI == PRISM_EPI_STORE_F32) {
+              reinterpret_cast<float *>(out_)[(int64_t)row * N + col] = acc[i][j][g * 4 + q];
+            } else {
+              reinterpret_cast<OT *>(out_)[(int64_t)row * N + col] = from_f32<OT>(acc[i][j][g * 4 + q]);
+            }
+          }
     }
   }
 }
