@@ -80,6 +80,8 @@ def main():
                     help="16-bit type of the matrix-core operands when the weights are bf16")
     ap.add_argument("--checkpoints", default="workload", choices=["workload", "every"],
                     help="pruning checks after the workload's layers (every 4th) or after every layer (Sec. 4.5)")
+    ap.add_argument("--mode", default="drop-only", choices=["drop-only", "three-way"],
+                    help="routing: drop-only (Sec. 7, the headline) or three-way with early termination (Sec. 4.1)")
     ap.add_argument("--tau", type=float, default=None, help="dispersion threshold (default: the workload's, 0)")
     ap.add_argument("--lean", action="store_true",
                     help="hidden-state offload + embedding-table cache (needs a chunked workload, e.g. cfg5_8b_stream)")
@@ -135,7 +137,8 @@ def main():
     t_gen = time.perf_counter() - t_gen
     opts = dict(checkpoints=w.checkpoints, cv_threshold=w.cv_threshold, n_clusters=w.n_clusters, chunk_cands=w.chunk_cands,
                 hbm_cap_bytes=w.hbm_cap_bytes, stream_weights=w.stream_weights, operand=args.operand,
-                offload_hidden=args.lean, embed_on_host=args.lean, w4=args.w4)
+                offload_hidden=args.lean, embed_on_host=args.lean, w4=args.w4,
+                mode=B.MODE_THREE_WAY if args.mode == "three-way" else B.MODE_DROP_ONLY)
     p = B.Prism(m, wt, **opts)
 
     for _ in range(args.warmup):
@@ -192,7 +195,7 @@ def main():
         "config": {"workload": f"{w.name}: {m.n_layers} layers, hidden {m.hidden}, {m.n_q_heads}/{m.n_kv_heads} heads x {m.head_dim}, "
                                f"ffn {m.ffn}, vocab {m.vocab}; query {w.query_len} tok, {w.n_cands} candidates, "
                                f"{int(sum(len(c) + len(q) for c in cands))} tokens in all; K={w.K}; "
-                               f"checkpoints after layers {w.checkpoints}; k={w.n_clusters} clusters, tau={w.cv_threshold}, drop-only; "
+                               f"checkpoints after layers {w.checkpoints}; k={w.n_clusters} clusters, tau={w.cv_threshold}, {args.mode}; "
                                f"weights {'4-bit (groups of 128) expanded to ' + op_t if args.w4 else m.dtype}, matrix-core operands {op_t}, "
                                f"fp32 accumulation and residual",
                    "n_cands": w.n_cands, "K": w.K, "seed": w.seed, "chunk_cands": w.chunk_cands, "stream_weights": w.stream_weights},
@@ -200,7 +203,7 @@ def main():
         "unpruned_latency_ms": None if unpruned_ms is None else round(unpruned_ms, 3),
         "gpu_ms": {"total": round(rep.ms_total, 3), "layers": round(rep.ms_layers, 3), "checks": round(rep.ms_checks, 3)},
         "survivors": {"layer": rep.layer.tolist(), "n_before": rep.n_before.tolist(), "n_after": rep.n_after.tolist()},
-        "token_layers": int(rep.token_layers), "peak_hbm_bytes": int(rep.peak_hbm_bytes), "bytes_streamed": int(rep.bytes_streamed),
+        "layers_run": int(rep.layers_run), "token_layers": int(rep.token_layers), "peak_hbm_bytes": int(rep.peak_hbm_bytes), "bytes_streamed": int(rep.bytes_streamed),
         "topk": idx.tolist(),
         "kernels": kinds,
         "mfma_utilisation": {"layer_gemms": round(gemm_fl / gemm_ms / 1e9 / PEAK_BF16_TFLOPS, 4) if gemm_ms else None,
