@@ -249,7 +249,7 @@ int prism_op_attention(int32_t dtype, const void *QK, const void *Vt, int64_t vt
                        int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, void *out, void *stream);
 
 /* Intermediate scorer (Sec. 4.1): for each sequence c, the last token's state through the final RMSNorm and
- * the yes/no head: scores[c] = z . w_yes - z . w_no.  last_row[c] = row of that token in X. */
+ * the yes/no head: scores[c] = z . w_yes - z . w_no.  last_row[c] = row of that token in X (NULL: row c). */
 int prism_op_score(const float *X, const int32_t *last_row, int32_t n_seqs, int32_t hidden,
                    const void *final_norm, const void *w_yes, const void *w_no, int32_t dtype, float eps,
                    float *scores, void *stream);

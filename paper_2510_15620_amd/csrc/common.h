@@ -102,7 +102,7 @@ static const int kEpiQkv = 4;   // internal epilogue code of launch_gemm_16_qkv
 bool gemm_16_qkv_supported(int M, int nq, int nkv, int hd, int K);
 int launch_gemm_16_qkv(int dtype, const void *Xn, const void *Wqkv, int M, int K, int hd, const QkvEpilogue &e, hipStream_t s);
 
-// dst row dst_idx[i] = src row src_idx[i], i < n; rows of row_bytes (a multiple of 16) bytes.  src may be pinned host
+// dst row dst_idx[i] (i itself if dst_idx is null) = src row src_idx[i], i < n; rows of row_bytes (a multiple of 16) bytes.  src may be pinned host
 // memory (its device-visible address): the embedding-table cache fetches its misses this way (Sec. 4.4).
 int launch_copy_rows(const void *src, const int32_t *src_idx, void *dst, const int32_t *dst_idx, int n, size_t row_bytes,
                      hipStream_t s);

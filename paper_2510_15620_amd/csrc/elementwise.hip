@@ -105,13 +105,13 @@ int launch_rope_table(float2 *tab, int n_pos, int head_dim, float rope_base, hip
 __global__ __launch_bounds__(256) void copy_rows_kernel(const uint4 *__restrict__ src, const int32_t *__restrict__ src_idx,
                                                         uint4 *__restrict__ dst, const int32_t *__restrict__ dst_idx, int vecs) {
   const uint4 *a = src + (int64_t)src_idx[blockIdx.x] * vecs;
-  uint4 *b = dst + (int64_t)dst_idx[blockIdx.x] * vecs;
+  uint4 *b = dst + (int64_t)(dst_idx ? dst_idx[blockIdx.x] : (int)blockIdx.x) * vecs;   // no list: row i -> row i
   for (int i = threadIdx.x; i < vecs; i += 256) b[i] = a[i];
 }
 
 int launch_copy_rows(const void *src, const int32_t *src_idx, void *dst, const int32_t *dst_idx, int n, size_t row_bytes,
                      hipStream_t s) {
-  PRISM_REQUIRE(src && src_idx && dst && dst_idx && n >= 0 && row_bytes % 16 == 0, PRISM_EINVAL, "copy_rows: bad arguments");
+  PRISM_REQUIRE(src && src_idx && dst && n >= 0 && row_bytes % 16 == 0, PRISM_EINVAL, "copy_rows: bad arguments");
   if (n == 0) return PRISM_OK;
   copy_rows_kernel<<<n, 256, 0, s>>>((const uint4 *)src, src_idx, (uint4 *)dst, dst_idx, (int)(row_bytes / 16));
   PRISM_HIP(hipGetLastError());
@@ -225,7 +225,7 @@ __global__ __launch_bounds__(256) void score_kernel(const float *__restrict__ X,
                                                     int hidden, const T *__restrict__ gain, const T *__restrict__ w_yes,
                                                     const T *__restrict__ w_no, float eps, float *__restrict__ scores) {
   __shared__ float red[4];
-  const float *x = X + (int64_t)last_row[blockIdx.x] * hidden;
+  const float *x = X + (int64_t)(last_row ? last_row[blockIdx.x] : (int)blockIdx.x) * hidden;   // no list: state c is row c
   float ss = 0.f, dy = 0.f, dn = 0.f;
   for (int i = threadIdx.x; i < hidden; i += 256) {
     const float v = x[i];
@@ -245,8 +245,7 @@ __global__ __launch_bounds__(256) void score_kernel(const float *__restrict__ X,
 
 int launch_score(const float *X, const int32_t *last_row, int n, int hidden, const void *final_norm,
                  const void *w_yes, const void *w_no, int dtype, float eps, float *scores, hipStream_t s) {
-  PRISM_REQUIRE(X && last_row && final_norm && w_yes && w_no && scores && n >= 0 && hidden > 0, PRISM_EINVAL,
-                "score: bad arguments");
+  PRISM_REQUIRE(X && final_norm && w_yes && w_no && scores && n >= 0 && hidden > 0, PRISM_EINVAL, "score: bad arguments");
   if (n == 0) return PRISM_OK;
   if (dtype == PRISM_DTYPE_FP32)
     score_kernel<float><<<n, 256, 0, s>>>(X, last_row, hidden, (const float *)final_norm, (const float *)w_yes,

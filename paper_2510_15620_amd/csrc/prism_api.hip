@@ -116,6 +116,9 @@ struct prism_ctx {
   float *X[2] = {nullptr, nullptr};
   int64_t x_cap[2] = {0, 0};                      // tokens
   char *Xn = nullptr, *QKV = nullptr, *QK = nullptr, *Vt = nullptr, *AO = nullptr, *S = nullptr;
+  // last layer: only the last token of a sequence is ever looked at again, so everything after the attention runs on
+  // one row per candidate
+  char *AOl = nullptr, *Xnl = nullptr, *Sl = nullptr; float *Xl = nullptr; int64_t last_cap = 0;   // candidates
   int64_t chunk_cap = 0, vt_cap = 0;              // tokens / V^T columns
   int32_t *d_meta = nullptr; int64_t meta_cap = 0;   // int32 words
   int32_t *h_meta = nullptr; int64_t h_meta_cap = 0; // pinned staging
@@ -404,7 +407,7 @@ extern "C" void prism_destroy(prism_ctx *c) {
     for (hipEvent_t e : {c->ev_in[i], c->ev_done[i], c->ev_out[i]}) if (e) (void)hipEventDestroy(e);
   if (c->xin_stream) (void)hipStreamDestroy(c->xin_stream);
   if (c->xout_stream) (void)hipStreamDestroy(c->xout_stream);
-  void *ptrs[] = {c->rope_tab, c->X[0], c->X[1], c->Xn, c->QKV, c->QK, c->Vt, c->AO, c->S, c->d_meta, c->d_scores, c->d_fate,
+  void *ptrs[] = {c->AOl, c->Xnl, c->Sl, c->Xl, c->rope_tab, c->X[0], c->X[1], c->Xn, c->QKV, c->QK, c->Vt, c->AO, c->S, c->d_meta, c->d_scores, c->d_fate,
                   c->d_stats, c->route_ws, c->d_top_pos, c->d_top_scores};
   for (void *p : ptrs) if (p) (void)hipFree(p);
   if (c->h_meta) (void)hipHostFree(c->h_meta);
@@ -458,6 +461,7 @@ struct Plan {
   int64_t T = 0;
   std::vector<Chunk> chunks;
   std::vector<AttnTile> tiles;
+  std::vector<AttnTile> last_tiles;   // per live candidate: the query block that holds its last token
   int64_t max_chunk_tokens = 0, max_vt_cols = 0;
 };
 
@@ -469,6 +473,7 @@ static void build_plan(const prism_ctx *c, Plan &p) {
   p.T = r;
   p.chunks.clear();
   p.tiles.clear();
+  p.last_tiles.assign(n, AttnTile{0, 0, 0, 0});
   p.max_chunk_tokens = p.max_vt_cols = 0;
   const int step = c->opt.chunk_cands > 0 ? c->opt.chunk_cands : std::max(n, 1);
   const bool mfma = is16(c->op);
@@ -483,6 +488,7 @@ static void build_plan(const prism_ctx *c, Plan &p) {
       for (int i = ch.c0; i < ch.c1; ++i) {
         for (int q0 = 0; q0 < p.len[i]; q0 += bq)
           p.tiles.push_back({(int32_t)(p.row0[i] - ch.r0), p.len[i], q0, (int32_t)col});
+        p.last_tiles[i] = {(int32_t)(p.row0[i] - ch.r0), p.len[i], (p.len[i] - 1) / bq * bq, (int32_t)col};
         col += round_up(p.len[i], 64);
       }
       // heavy (late) query blocks first: they loop over the most keys
@@ -497,15 +503,15 @@ static void build_plan(const prism_ctx *c, Plan &p) {
   }
 }
 
-// meta buffer (int32 words): [pos T][vtcol T][lastrow n][src n][dst n][len n][tiles 4*n_tiles][tokens T]
-struct MetaOff { int64_t pos, vtcol, lastrow, src, dst, len, tiles, tokens, words; };
+// meta buffer (int32 words): [pos T][vtcol T][lastrow n][src n][dst n][len n][tiles 4*n_tiles][last tiles 4*n][tokens T]
+struct MetaOff { int64_t pos, vtcol, lastrow, src, dst, len, tiles, ltiles, tokens, words; };
 
 static MetaOff meta_offsets(int64_t T, int n, int64_t n_tiles) {
   MetaOff o;
   int64_t w = 0;
   auto take = [&](int64_t k) { int64_t at = w; w = round_up(w + k, 64); return at; };
   o.pos = take(T); o.vtcol = take(T); o.lastrow = take(n); o.src = take(n); o.dst = take(n); o.len = take(n);
-  o.tiles = take(4 * n_tiles); o.tokens = take(T);
+  o.tiles = take(4 * n_tiles); o.ltiles = take(4 * (int64_t)n); o.tokens = take(T);
   o.words = w;
   return o;
 }
@@ -563,6 +569,18 @@ static int ensure_scratch(prism_ctx *c, const Plan &p, bool need_second_x, int n
     // pad columns are multiplied by exact zeros; they only have to be finite
     PRISM_TRY(launch_fill_zero(c->Vt, (size_t)round_up((size_t)c->vt_cap * Dkv * 2, 256), c->stream));
   }
+  if (n_cands > c->last_cap) {
+    PRISM_HIP(hipStreamSynchronize(c->stream));
+    const int64_t old = c->last_cap;
+    dev_free(c, c->AOl, (size_t)old * Dq * e); dev_free(c, c->Xnl, (size_t)old * m.hidden * e);
+    dev_free(c, c->Sl, (size_t)old * m.ffn * e); dev_free(c, c->Xl, (size_t)old * m.hidden * 4);
+    c->AOl = c->Xnl = c->Sl = nullptr; c->Xl = nullptr; c->last_cap = 0;
+    PRISM_TRY(dev_alloc(c, (void **)&c->AOl, (size_t)n_cands * Dq * e));
+    PRISM_TRY(dev_alloc(c, (void **)&c->Xnl, (size_t)n_cands * m.hidden * e));
+    PRISM_TRY(dev_alloc(c, (void **)&c->Sl, (size_t)n_cands * m.ffn * e));
+    PRISM_TRY(dev_alloc(c, (void **)&c->Xl, (size_t)n_cands * m.hidden * 4));
+    c->last_cap = n_cands;
+  }
   const MetaOff mo = meta_offsets(p.T, n_cands, max_tiles);
   PRISM_TRY(grow(c, &c->d_meta, &c->meta_cap, mo.words, 4));
   if (mo.words > c->h_meta_cap) {
@@ -588,6 +606,7 @@ static int upload_meta(prism_ctx *c, const Plan &p, const MetaOff &mo, bool with
   }
   for (int i = 0; i < n; ++i) h[mo.lastrow + i] = (int32_t)(p.row0[i] + p.len[i] - 1);
   if (!p.tiles.empty()) memcpy(h + mo.tiles, p.tiles.data(), p.tiles.size() * sizeof(AttnTile));
+  if (!p.last_tiles.empty()) memcpy(h + mo.ltiles, p.last_tiles.data(), p.last_tiles.size() * sizeof(AttnTile));
   // one copy for [pos .. tiles], a second for the tokens (first upload only)
   PRISM_HIP(hipMemcpyAsync(c->d_meta, h, (size_t)mo.tokens * 4, hipMemcpyHostToDevice, c->stream));
   if (with_tokens)
@@ -732,8 +751,12 @@ static int retire_chunk(prism_ctx *c, const Plan &p, const Chunk &ch, int slot, 
 // One transformer layer over every chunk.  Offload mode additionally: score_after = score the chunk's candidates while
 // the chunk is on the device (checkpoint layers and the last one); write_back = the layer's output is needed again;
 // next_layer_same_plan = the next layer runs on the same live set, so its first chunk may be prefetched.
+// last_only (the model's last layer): nothing but the final scores is read from this layer's output, and a score needs the
+// last token's state only.  Keys and values are still needed for every token, so the q/k/v projection runs in full; the
+// attention runs for the query block that holds the last token, and the O projection and the whole FFN block run on one
+// gathered row per candidate, whose final scores are taken right there.
 static int run_layer(prism_ctx *c, const Plan &p, const MetaOff &mo, float *X, const char *wbuf, bool score_after = false,
-                     bool write_back = true, bool next_layer_same_plan = false) {
+                     bool write_back = true, bool next_layer_same_plan = false, bool last_only = false) {
   const prism_model &m = c->m;
   const LayerLayout &L = c->lay;
   const int H = m.hidden, Dq = m.n_q_heads * m.head_dim, Dkv = m.n_kv_heads * m.head_dim, F = m.ffn;
@@ -788,6 +811,33 @@ static int run_layer(prism_ctx *c, const Plan &p, const MetaOff &mo, float *X, c
                                   c->d_meta + mo.vtcol + ch.r0, c->vt_cap, s));
       return (int)PRISM_OK;
     }));
+    if (last_only) {
+      const int nc = ch.c1 - ch.c0;
+      const size_t e = dtype_size(m.dtype);
+      double last_attn = 0.0;                                    // one query per head: 2 contractions of length L
+      for (int i = ch.c0; i < ch.c1; ++i) last_attn += 2.0 * m.n_q_heads * m.head_dim * 2.0 * p.len[i];
+      PRISM_TRY(timed_span(c, 4, last_attn, [&] {
+        if (bf)
+          return launch_attention_16(c->op, c->QK, c->Vt, c->vt_cap, (const AttnTile *)(c->d_meta + mo.ltiles) + ch.c0, nc, Tc,
+                                     m.n_q_heads, m.n_kv_heads, m.head_dim, c->AO, s);
+        return launch_attention_fp32((const float *)c->QKV, pos, Tc, m.n_q_heads, m.n_kv_heads, m.head_dim, (float *)c->AO, s);
+      }));
+      // last_row holds rows of the packed pool; this chunk's rows start at ch.r0
+      const int32_t *last_row = c->d_meta + mo.lastrow + ch.c0;
+      char *AOl = c->AOl + (size_t)ch.c0 * Dq * e, *Xnl = c->Xnl + (size_t)ch.c0 * H * e, *Sl = c->Sl + (size_t)ch.c0 * F * e;
+      float *Xl = c->Xl + (size_t)ch.c0 * H;
+      PRISM_TRY(timed_span(c, 5, 0.0, [&] {
+        PRISM_TRY(launch_copy_rows(c->AO - ch.r0 * (int64_t)Dq * (int64_t)e, last_row, AOl, nullptr, nc, (size_t)Dq * e, s));
+        return launch_copy_rows(Xc - ch.r0 * H, last_row, Xl, nullptr, nc, (size_t)H * 4, s);
+      }));
+      const double tl = 2.0 * nc;
+      PRISM_TRY(timed_span(c, 1, tl * H * Dq, [&] { return gemm(PRISM_EPI_RESIDUAL, AOl, wbuf + L.wo, Xl, nc, H, Dq); }));
+      PRISM_TRY(timed_span(c, 5, 0.0, [&] { return launch_rmsnorm(Xl, wbuf + L.ffn_norm, nc, H, m.rms_eps, c->op, Xnl, s); }));
+      PRISM_TRY(timed_span(c, 2, tl * 2 * F * H, [&] { return gemm(PRISM_EPI_SWIGLU, Xnl, wbuf + L.wgu, Sl, nc, 2 * F, H); }));
+      PRISM_TRY(timed_span(c, 3, tl * H * F, [&] { return gemm(PRISM_EPI_RESIDUAL, Sl, wbuf + L.wd, Xl, nc, H, F); }));
+      PRISM_TRY(launch_score(Xl, nullptr, nc, m.hidden, c->final_norm, c->w_yes, c->w_no, m.dtype, m.rms_eps,
+                             c->d_scores + ch.c0, s));
+    } else {
     PRISM_TRY(timed_span(c, 4, attn_flops, [&] {
       if (bf)
         return launch_attention_16(c->op, c->QK, c->Vt, c->vt_cap, (const AttnTile *)(c->d_meta + mo.tiles) + ch.tile0,
@@ -799,8 +849,9 @@ static int run_layer(prism_ctx *c, const Plan &p, const MetaOff &mo, float *X, c
     PRISM_TRY(timed_span(c, 5, 0.0, [&] { return launch_rmsnorm(Xc, wbuf + L.ffn_norm, Tc, H, m.rms_eps, c->op, c->Xn, s); }));
     PRISM_TRY(timed_span(c, 2, tk * 2 * F * H, [&] { return gemm(PRISM_EPI_SWIGLU, c->Xn, wbuf + L.wgu, c->S, Tc, 2 * F, H); }));
     PRISM_TRY(timed_span(c, 3, tk * H * F, [&] { return gemm(PRISM_EPI_RESIDUAL, c->S, wbuf + L.wd, Xc, Tc, H, F); }));
+    }
     if (c->offload) {
-      if (score_after)   // last_row holds rows of the packed pool; this chunk's rows start at ch.r0
+      if (score_after && !last_only)   // last_row holds rows of the packed pool; this chunk's rows start at ch.r0
         PRISM_TRY(launch_score(Xc - ch.r0 * H, c->d_meta + mo.lastrow + ch.c0, ch.c1 - ch.c0, m.hidden, c->final_norm, c->w_yes,
                                c->w_no, m.dtype, m.rms_eps, c->d_scores + ch.c0, s));
       PRISM_TRY(retire_chunk(c, p, ch, slot, write_back));
@@ -940,7 +991,7 @@ extern "C" int prism_select(prism_ctx *c, const int32_t *query_tokens, int32_t q
                              may_prune && (int)p.live.size() > K_rem;
     const bool last_layer = l + 1 == m.n_layers;
     PRISM_TRY(run_layer(c, p, mo, c->X[cur], c->layer_buf[slot], check_after || last_layer, !last_layer,
-                        !last_layer && !check_after));
+                        !last_layer && !check_after, last_layer));
     if (timed) PRISM_HIP(hipEventRecord(c->ev_layer[2 * l + 1], s));
     token_layers += p.T;
     layers_run = l + 1;
@@ -1038,9 +1089,7 @@ extern "C" int prism_select(prism_ctx *c, const int32_t *query_tokens, int32_t q
     // ---- final scoring and top-K (Sec. 2.1)
     const int n_live = (int)p.live.size();
     const int k_out = std::min(K_rem, n_live);
-    if (!c->offload)
-      PRISM_TRY(launch_score(c->X[cur], c->d_meta + mo.lastrow, n_live, m.hidden, c->final_norm, c->w_yes, c->w_no, m.dtype,
-                             m.rms_eps, c->d_scores, s));
+    // (the last layer has scored every candidate from its gathered last-token state)
     PRISM_TRY(launch_topk(c->d_scores, n_live, k_out, c->d_top_pos, c->d_top_scores, s));
     PRISM_HIP(hipMemcpyAsync(h_scores, c->d_scores, (size_t)n_live * 4, hipMemcpyDeviceToHost, s));
     PRISM_HIP(hipMemcpyAsync(h_top_pos, c->d_top_pos, (size_t)k_out * 4, hipMemcpyDeviceToHost, s));
