@@ -143,7 +143,8 @@ typedef struct {
   int32_t  layers_run;      /* out */
   /* out: per-kernel-kind totals over the call, from HIP events around each launch on the compute stream.
    * kinds: 0 fused QKV GEMM, 1 O-projection GEMM, 2 gate/up GEMM with SwiGLU, 3 down GEMM, 4 attention,
-   * 5 the elementwise steps of a layer (RMSNorm, q/k norm + RoPE, V transposition).
+   * 5 the elementwise steps of a layer (RMSNorm, q/k norm + RoPE, V transposition where not fused) and the last layer's
+ * one-row-per-candidate tail.
    * kind_flops is the ALGORITHMIC work: 2*M*N*K per GEMM (live tokens only), 2*nq*hd*L*(L+1) per sequence
    * of attention (causal triangle only); 0 for kind 5. */
   int32_t  kind_launches[PRISM_N_KINDS];

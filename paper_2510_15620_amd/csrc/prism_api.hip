@@ -830,11 +830,14 @@ static int run_layer(prism_ctx *c, const Plan &p, const MetaOff &mo, float *X, c
         PRISM_TRY(launch_copy_rows(c->AO - ch.r0 * (int64_t)Dq * (int64_t)e, last_row, AOl, nullptr, nc, (size_t)Dq * e, s));
         return launch_copy_rows(Xc - ch.r0 * H, last_row, Xl, nullptr, nc, (size_t)H * 4, s);
       }));
-      const double tl = 2.0 * nc;
-      PRISM_TRY(timed_span(c, 1, tl * H * Dq, [&] { return gemm(PRISM_EPI_RESIDUAL, AOl, wbuf + L.wo, Xl, nc, H, Dq); }));
-      PRISM_TRY(timed_span(c, 5, 0.0, [&] { return launch_rmsnorm(Xl, wbuf + L.ffn_norm, nc, H, m.rms_eps, c->op, Xnl, s); }));
-      PRISM_TRY(timed_span(c, 2, tl * 2 * F * H, [&] { return gemm(PRISM_EPI_SWIGLU, Xnl, wbuf + L.wgu, Sl, nc, 2 * F, H); }));
-      PRISM_TRY(timed_span(c, 3, tl * H * F, [&] { return gemm(PRISM_EPI_RESIDUAL, Sl, wbuf + L.wd, Xl, nc, H, F); }));
+      // (timed with the elementwise kind: these launches are a different, tiny kernel configuration and would blur the
+      // per-launch figures of the layer GEMMs)
+      PRISM_TRY(timed_span(c, 5, 0.0, [&] {
+        PRISM_TRY(gemm(PRISM_EPI_RESIDUAL, AOl, wbuf + L.wo, Xl, nc, H, Dq));
+        PRISM_TRY(launch_rmsnorm(Xl, wbuf + L.ffn_norm, nc, H, m.rms_eps, c->op, Xnl, s));
+        PRISM_TRY(gemm(PRISM_EPI_SWIGLU, Xnl, wbuf + L.wgu, Sl, nc, 2 * F, H));
+        return gemm(PRISM_EPI_RESIDUAL, Sl, wbuf + L.wd, Xl, nc, H, F);
+      }));
       PRISM_TRY(launch_score(Xl, nullptr, nc, m.hidden, c->final_norm, c->w_yes, c->w_no, m.dtype, m.rms_eps,
                              c->d_scores + ch.c0, s));
     } else {
