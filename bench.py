@@ -25,8 +25,8 @@ KIND_NAMES = ["gemm_qkv", "gemm_o", "gemm_gate_up_swiglu", "gemm_down", "attenti
 
 
 def cpu_baseline(w, wt_dev, q, cands, token_layers_job: int, n_cands: int):
-    """The oracle as it stands, timed on a bounded sample: a few candidates through the first few layers
-    plus their scoring, extrapolated by token-layers to the job the GPU ran (same pruning schedule)."""
+    """The oracle as it stands, timed on a bounded sample (about 15 s): eight candidates of median length through the
+    first four layers plus their scoring, extrapolated by token-layers to the job the GPU ran (same pruning schedule)."""
     import numpy as np
     from oracle import prism_oracle as O
     from tests.helpers import oracle_model, to_f64
@@ -37,7 +37,7 @@ def cpu_baseline(w, wt_dev, q, cands, token_layers_job: int, n_cands: int):
         cores = os.cpu_count() or 1
     n_layers = min(4, w.model.n_layers)
     med = np.median([len(y) for y in cands])
-    picks = [int(i) for i in np.argsort([abs(len(x) - med) for x in cands])[:4]]
+    picks = [int(i) for i in np.argsort([abs(len(x) - med) for x in cands])[:8]]
     ow = {"embed": None, "final_norm": to_f64(wt_dev.final_norm), "w_yes": to_f64(wt_dev.w_yes), "w_no": to_f64(wt_dev.w_no),
           "layers": [{k: to_f64(v) for k, v in wt_dev.layers[l].items()} for l in range(n_layers)]}
     toks = [np.concatenate([q, cands[c]]) for c in picks]
