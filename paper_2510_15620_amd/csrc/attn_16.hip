@@ -157,9 +157,10 @@ __global__ __launch_bounds__(512) void attention_16_kernel(const OT *__restrict_
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const float p = __builtin_amdgcn_exp2f(s[kb][e] * c_exp - mb);
-          psum += p;
-          pf[kb * 2 + (e >> 3)][e & 7] = (f16)p;      // p <= 1: no overflow
+          const f16 ph = (f16)__builtin_amdgcn_exp2f(s[kb][e] * c_exp - mb);   // p <= 1: no overflow
+          psum += (float)ph;     // the denominator sums the ROUNDED weights the numerator uses: the output stays an
+                                 // exactly normalised average of V rows and the rounding of p cancels to first order
+          pf[kb * 2 + (e >> 3)][e & 7] = ph;
         }
       l_run = l_run * alpha + psum;
       m_run = m_new;

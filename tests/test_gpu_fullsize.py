@@ -169,7 +169,7 @@ def test_cfg3_sampled_oracle_parity_and_properties():
 
 def test_cfg4_headline_sampled_oracle_parity_and_properties(weights_8b):
     w = W.WORKLOADS["cfg4_8b"]
-    idx, scores, rep, traj = _sampled_check(w, weights_8b)
+    idx, scores, rep, traj = _sampled_check(w, weights_8b, n_survivors=2)
     idx0, s0, rep0 = _run_gpu(w, weights_8b, B.MODE_NO_PRUNING)
     live = ~np.isnan(rep.scores[-1])
     assert np.array_equal(rep.scores[-1][live], rep0.scores[-1][live])
