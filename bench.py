@@ -85,6 +85,7 @@ def main():
     ap.add_argument("--tau", type=float, default=None, help="dispersion threshold (default: the workload's, 0)")
     ap.add_argument("--lean", action="store_true",
                     help="hidden-state offload + embedding-table cache (needs a chunked workload, e.g. cfg5_8b_stream)")
+    ap.add_argument("--stream-slots", type=int, default=0, help="layer buffers of the streaming ring (default 2, as in the paper)")
     ap.add_argument("--w4", action="store_true", help="4-bit layer weights (quantised on the device before the timed region)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unpruned", action="store_true")
@@ -137,7 +138,7 @@ def main():
     t_gen = time.perf_counter() - t_gen
     opts = dict(checkpoints=w.checkpoints, cv_threshold=w.cv_threshold, n_clusters=w.n_clusters, chunk_cands=w.chunk_cands,
                 hbm_cap_bytes=w.hbm_cap_bytes, stream_weights=w.stream_weights, operand=args.operand,
-                offload_hidden=args.lean, embed_on_host=args.lean, w4=args.w4,
+                offload_hidden=args.lean, embed_on_host=args.lean, w4=args.w4, stream_slots=args.stream_slots,
                 mode=B.MODE_THREE_WAY if args.mode == "three-way" else B.MODE_DROP_ONLY)
     p = B.Prism(m, wt, **opts)
 

@@ -115,6 +115,9 @@ typedef struct {
                                          library-owned pinned host memory and at most three chunks of it are on the
                                          device (computing / being written back / being prefetched); needs chunk_cands > 0 */
   int32_t embed_cache_rows;           /* embed_residency == 1: rows of the device LRU cache; 0 -> vocab / 10 */
+  int32_t stream_slots;               /* streamed or 4-bit layers: layer buffers in the ring, 0 or 2 = the paper's double
+                                         buffer (Sec. 4.2); more lets the stream run ahead while the pool is large, which
+                                         pays back after pruning, when a layer computes faster than it arrives */
 } prism_options;
 
 /* Optional per-call record.  The caller allocates every array ([host]); an "event" is one

@@ -52,7 +52,7 @@ class prism_weights(C.Structure):
 class prism_options(C.Structure):
     _fields_ = [("checkpoint_layers", C.POINTER(C.c_int32)), ("n_checkpoints", C.c_int32), ("cv_threshold", C.c_float),
                 ("n_clusters", C.c_int32), ("mode", C.c_int32), ("chunk_cands", C.c_int32), ("hbm_cap_bytes", C.c_int64),
-                ("stream", C.c_void_p), ("operand", C.c_int32), ("offload_hidden", C.c_int32), ("embed_cache_rows", C.c_int32)]
+                ("stream", C.c_void_p), ("operand", C.c_int32), ("offload_hidden", C.c_int32), ("embed_cache_rows", C.c_int32), ("stream_slots", C.c_int32)]
 
 
 class prism_report(C.Structure):
@@ -164,7 +164,7 @@ class Prism:
     def __init__(self, model, weights, *, checkpoints: Sequence[int] = (), cv_threshold: float = 0.0, n_clusters: int = 3,
                  mode: int = MODE_DROP_ONLY, chunk_cands: int = 0, hbm_cap_bytes: int = 0, stream_weights: bool = False,
                  stream: Optional[int] = None, operand: str = "f16", offload_hidden: bool = False, embed_on_host: bool = False,
-                 embed_cache_rows: int = 0, w4: bool = False):
+                 embed_cache_rows: int = 0, w4: bool = False, stream_slots: int = 0):
         """model: object with n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, rms_eps, rope_base,
         qk_norm, dtype ("fp32" | "bf16": storage type of the weights).  operand ("f16" | "bf16"): 16-bit type of the
         matrix-core operands when the weights are bf16.  weights: object with embed, final_norm, w_yes, w_no (device tensors) and
@@ -186,7 +186,7 @@ class Prism:
         ck, ckp = _i32_array(list(checkpoints))
         o = prism_options(ckp, len(ck), cv_threshold, n_clusters, mode, chunk_cands, hbm_cap_bytes,
                           _stream() if stream is None else stream, DTYPE_BF16 if operand == "bf16" else DTYPE_F16,
-                          int(offload_hidden), embed_cache_rows)
+                          int(offload_hidden), embed_cache_rows, stream_slots)
         self.n_checkpoints = len(ck)
         _check(lib().prism_create(C.byref(m), C.byref(w), C.byref(o), C.byref(self._ctx)))
 

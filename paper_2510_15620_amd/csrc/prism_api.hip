@@ -102,7 +102,8 @@ struct prism_ctx {
   std::vector<char *> layer_buf;                  // n_layers slots (resident) or 2 (streamed)
   hipStream_t stream = nullptr, copy_stream = nullptr;
   bool own_stream = false;
-  hipEvent_t ev_ready[2] = {nullptr, nullptr}, ev_free[2] = {nullptr, nullptr};
+  int ring = 2;                                   // layer slots of the streaming ring (two_slot); 2 is the paper's double buffer
+  std::vector<hipEvent_t> ev_ready, ev_free;      // per ring slot
   hipEvent_t ev_t[4] = {nullptr, nullptr, nullptr, nullptr};
   std::vector<hipEvent_t> ev_layer;               // 2 per layer, for the report
   // per-launch spans for the report: events come from a pool that only grows
@@ -281,6 +282,7 @@ extern "C" int prism_create(const prism_model *model, const prism_weights *weigh
   PRISM_REQUIRE(!options->offload_hidden || options->chunk_cands > 0, PRISM_EINVAL,
                 "prism_create: offload_hidden needs chunked execution (chunk_cands > 0)");
   PRISM_REQUIRE(options->embed_cache_rows >= 0, PRISM_EINVAL, "prism_create: embed_cache_rows");
+  PRISM_REQUIRE(options->stream_slots >= 0, PRISM_EINVAL, "prism_create: stream_slots");
   const void *embed_alias = nullptr;
   if (weights->embed_residency == 1) {
     // kernels read the table in place, so it has to be pinned memory that is mapped into the device's address space
@@ -338,13 +340,16 @@ extern "C" int prism_create(const prism_model *model, const prism_weights *weigh
   if (options->stream) c->stream = (hipStream_t)options->stream;
   else { CREATE_HIP(hipStreamCreateWithFlags(&c->stream, hipStreamNonBlocking)); c->own_stream = true; }
   CREATE_HIP(hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking));
-  for (int i = 0; i < 2; ++i) {
+  c->ring = std::min(std::max(options->stream_slots, 2), model->n_layers > 1 ? model->n_layers : 2);
+  c->ev_ready.assign(c->ring, nullptr);
+  c->ev_free.assign(c->ring, nullptr);
+  for (int i = 0; i < c->ring; ++i) {
     CREATE_HIP(hipEventCreateWithFlags(&c->ev_ready[i], hipEventDisableTiming));
     CREATE_HIP(hipEventCreateWithFlags(&c->ev_free[i], hipEventDisableTiming));
   }
   for (int i = 0; i < 4; ++i) CREATE_HIP(hipEventCreate(&c->ev_t[i]));
 
-  const int n_slots = c->two_slot ? std::min(2, model->n_layers) : model->n_layers;
+  const int n_slots = c->two_slot ? std::min(c->ring, model->n_layers) : model->n_layers;
   c->layer_buf.assign(n_slots, nullptr);
   for (int s = 0; s < n_slots; ++s) CREATE_TRY(dev_alloc(c, (void **)&c->layer_buf[s], c->lay.bytes));
   if (c->w4 && c->streamed) {
@@ -412,10 +417,8 @@ extern "C" void prism_destroy(prism_ctx *c) {
   for (void *p : ptrs) if (p) (void)hipFree(p);
   if (c->h_meta) (void)hipHostFree(c->h_meta);
   if (c->h_res) (void)hipHostFree(c->h_res);
-  for (int i = 0; i < 2; ++i) {
-    if (c->ev_ready[i]) (void)hipEventDestroy(c->ev_ready[i]);
-    if (c->ev_free[i]) (void)hipEventDestroy(c->ev_free[i]);
-  }
+  for (hipEvent_t e : c->ev_ready) if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : c->ev_free) if (e) (void)hipEventDestroy(e);
   for (int i = 0; i < 4; ++i) if (c->ev_t[i]) (void)hipEventDestroy(c->ev_t[i]);
   for (hipEvent_t e : c->ev_layer) if (e) (void)hipEventDestroy(e);
   for (hipEvent_t e : c->ev_pool) if (e) (void)hipEventDestroy(e);
@@ -945,8 +948,9 @@ extern "C" int prism_select(prism_ctx *c, const int32_t *query_tokens, int32_t q
 
   int64_t bytes_streamed = 0, token_layers = 0;
   if (c->two_slot) {
-    // Sec. 4.2: two buffers; layer l computes from slot l % 2 while layer l + 1 arrives (or is expanded) in the other
-    for (int l = 0; l < std::min(2, m.n_layers); ++l) {
+    // Sec. 4.2: a ring of layer buffers (two in the paper); layer l computes from slot l % ring while the layers
+    // after it arrive (or are expanded) in the others
+    for (int l = 0; l < std::min(c->ring, m.n_layers); ++l) {
       PRISM_TRY(issue_layer_copy(c, l, l, c->copy_stream, hipMemcpyHostToDevice, &bytes_streamed));
       PRISM_HIP(hipEventRecord(c->ev_ready[l], c->copy_stream));
     }
@@ -985,7 +989,7 @@ extern "C" int prism_select(prism_ctx *c, const int32_t *query_tokens, int32_t q
   };
 
   for (int l = 0; l < m.n_layers && !terminated; ++l) {
-    const int slot = c->two_slot ? l % 2 : l;
+    const int slot = c->two_slot ? l % c->ring : l;
     if (c->two_slot) PRISM_HIP(hipStreamWaitEvent(s, c->ev_ready[slot], 0));
     if (timed) PRISM_HIP(hipEventRecord(c->ev_layer[2 * l], s));
     // known before the layer runs: will its output be scored for pruning, and is it the last one
@@ -998,10 +1002,10 @@ extern "C" int prism_select(prism_ctx *c, const int32_t *query_tokens, int32_t q
     if (timed) PRISM_HIP(hipEventRecord(c->ev_layer[2 * l + 1], s));
     token_layers += p.T;
     layers_run = l + 1;
-    if (c->two_slot && l + 2 < m.n_layers) {
+    if (c->two_slot && l + c->ring < m.n_layers) {
       PRISM_HIP(hipEventRecord(c->ev_free[slot], s));
       PRISM_HIP(hipStreamWaitEvent(c->copy_stream, c->ev_free[slot], 0));
-      PRISM_TRY(issue_layer_copy(c, l + 2, slot, c->copy_stream, hipMemcpyHostToDevice, &bytes_streamed));
+      PRISM_TRY(issue_layer_copy(c, l + c->ring, slot, c->copy_stream, hipMemcpyHostToDevice, &bytes_streamed));
       PRISM_HIP(hipEventRecord(c->ev_ready[slot], c->copy_stream));
     }
     const int n_live = (int)p.live.size();

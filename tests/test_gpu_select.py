@@ -105,6 +105,12 @@ def test_chunked_execution_and_streamed_weights_change_nothing(name):
     streamed = run(w, mixed, stream_weights=True, chunk_cands=4)
     assert base[0].tolist() == streamed[0].tolist() and np.array_equal(base[1], streamed[1])
     assert streamed[2].bytes_streamed > 0 and streamed[2].peak_hbm_bytes < base[2].peak_hbm_bytes + (1 << 30)
+    # a deeper ring of layer buffers (the paper's is two) changes when layers arrive, nothing else; more slots than layers
+    # is clamped
+    for slots in (3, 100):
+        deep = run(w, mixed, stream_weights=True, stream_slots=slots)
+        assert base[0].tolist() == deep[0].tolist() and np.array_equal(base[1], deep[1])
+        assert deep[2].bytes_streamed == streamed[2].bytes_streamed
 
 
 def test_three_way_mode_matches_oracle():
