@@ -110,6 +110,29 @@ def test_resident_and_streamed_4bit_agree_bit_for_bit():
     assert np.array_equal(outs[0][2].scores, outs[1][2].scores, equal_nan=True)
 
 
+def test_4bit_layers_with_offload_cache_and_deep_ring_agree_bit_for_bit():
+    """Every memory mode on top of streamed 4-bit layers: hidden-state offload, embedding cache, a ring of three buffers."""
+    w = W.WORKLOADS["mini_bf16"]
+    wt = W.make_weights(w, DEV)
+    q, cands = W.make_tokens(w)
+    ql = [{k: v.cpu().pin_memory() for k, v in l.items()} for l in B.quantize_layers_w4(wt.layers)]
+    p = B.Prism(w.model, _Weights(wt, ql), checkpoints=w.checkpoints, w4=True, stream_weights=True, chunk_cands=3)
+    ref = p.select(q, cands, w.K)
+    p.destroy()
+
+    class Lean(_Weights):
+        def __init__(self, wt, layers):
+            super().__init__(wt, layers)
+            self.embed = wt.embed.cpu().pin_memory()
+            self.w_yes, self.w_no = wt.w_yes.clone(), wt.w_no.clone()
+    p = B.Prism(w.model, Lean(wt, ql), checkpoints=w.checkpoints, w4=True, stream_weights=True, chunk_cands=3,
+                offload_hidden=True, embed_on_host=True, embed_cache_rows=50, stream_slots=3)
+    out = p.select(q, cands, w.K)
+    p.destroy()
+    assert out[0].tolist() == ref[0].tolist() and np.array_equal(out[1], ref[1])
+    assert np.array_equal(out[2].scores, ref[2].scores, equal_nan=True) and np.array_equal(out[2].fate, ref[2].fate)
+
+
 def test_4bit_needs_bf16_model_and_aligned_shapes():
     w = W.WORKLOADS["cfg1_tiny"]                               # fp32 model
     wt = W.make_weights(w, DEV)
