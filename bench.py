@@ -91,7 +91,7 @@ def main():
     ap.add_argument("--no-unpruned", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; --gpus must be 1 (the path shards by candidate, see DESIGN.md)",
+        print("bench.py: this build runs on one GPU; --gpus must be 1 (the path would shard by candidate: sequences never interact)",
               file=sys.stderr)
         sys.exit(2)
 

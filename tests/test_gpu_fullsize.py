@@ -27,8 +27,9 @@ TOL = 2e-2
 
 
 def _progress(msg):
-    """Long oracle loops leave a trace so that a quiet run is not mistaken for a hung one."""
-    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    """Long oracle loops leave a trace so that a quiet run is not mistaken for a hung one (PRISM_PROGRESS_DIR, else a
+    scratch folder beside the tests)."""
+    d = os.environ.get("PRISM_PROGRESS_DIR") or os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
     try:
         os.makedirs(d, exist_ok=True)
         with open(os.path.join(d, "progress.log"), "a") as f:
