@@ -127,7 +127,7 @@ int launch_v_finish(int dtype, const float *QKV, int T, int nq, int nkv, int hd,
 int launch_attention_fp32(const float *QKV, const int32_t *pos, int T, int nq, int nkv, int hd, float *out,
                           hipStream_t s);
 // matrix-core attention (hd == 128).  tiles: per work item {first token row of the sequence, sequence length,
-// first query of the tile, column of the sequence's first key in Vt}; see attn_bf16.hip.
+// first query of the tile, column of the sequence's first key in Vt}; see attn_16.hip.
 struct AttnTile { int32_t seq_row0, seq_len, q0, vt_col0; };
 int launch_attention_16(int dtype, const void *QK, const void *Vt, int64_t vt_stride, const AttnTile *tiles, int n_tiles,
                         int T, int nq, int nkv, int hd, void *out, hipStream_t s);

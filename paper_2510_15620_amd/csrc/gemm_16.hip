@@ -20,6 +20,7 @@
 // Workgroup ids are remapped so that each XCD (ids are dealt round-robin over the 8 XCDs) owns a
 // contiguous range of tiles, walked in groups of 8 (4 for the residual epilogue) row-tiles, to keep the operand panels in its L2.
 #include <algorithm>
+#include <mutex>
 
 #include "common.h"
 #include "gemm_16_kloop.inc"
@@ -431,12 +432,13 @@ static int launch_cfg(const OT *A, const OT *W, void *out, int M, int N, int K, 
                       const QkvEpilogue &qe = QkvEpilogue{}) {
   constexpr size_t lds = 2 * (size_t)(BM + BN) * BK * sizeof(OT);
   auto kern = gemm_16_kernel<OT, BM, BN, WM, WN, EPI>;
-  static bool attr_set = false;   // the attribute is per function; set it once per process
-  if (!attr_set) {
-    PRISM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)lds));
-    attr_set = true;
-  }
+  // the attribute is per function: set once per process, also when several contexts launch from different threads
+  static std::once_flag attr_once;
+  static hipError_t attr_rc = hipSuccess;
+  std::call_once(attr_once, [&] {
+    attr_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  });
+  PRISM_HIP(attr_rc);
   const int ncols = EPI == PRISM_EPI_SWIGLU ? N / 2 : N, bn_out = EPI == PRISM_EPI_SWIGLU ? BN / 2 : BN;
   const int nM = cdiv(M, BM), nN = cdiv(ncols, bn_out);
   const int grid = cdiv((int64_t)nM * nN, 8) * 8;

@@ -157,6 +157,8 @@ def main():
         emit(f"PRISM_KLOOP4_{tname}_PLAIN", kloop(mn, plain))
         emit(f"PRISM_KLOOP4_{tname}_SWIGLU", kloop(mn, swiglu))
     regs = ", ".join(f'"v{r}"' for r in CLOBBER_V) + ", " + ", ".join(f'"s{r}"' for r in CLOBBER_S)
+    # m0 (written before every direct-to-LDS load) is not listed: the compiler reserves it, sets it right before each of
+    # its own uses and never keeps a value in it across a statement; hipcc diagnoses it in a clobber list
     print(f"#define PRISM_KLOOP4_CLOBBERS {regs}, \"scc\", \"memory\"")
 
 

@@ -81,6 +81,16 @@ def gaussian(seed: int, name: str, shape, mean: float, std: float, dtype: torch.
     return out.view(*shape)
 
 
+def gaussian_rows(seed: int, name: str, rows, row_len: int, mean: float, std: float, dtype: torch.dtype) -> torch.Tensor:
+    """Rows `rows` of the [*, row_len] tensor that gaussian() draws for (seed, name), without drawing the rest (a value
+    depends on its element index only).  CPU."""
+    table = torch.from_numpy(mean + std * normal_quantiles()).to(torch.float32).to(dtype)
+    out = torch.empty(len(rows), row_len, dtype=dtype)
+    for i, r in enumerate(rows):
+        out[i] = table[hash_u32(seed, name, int(r) * row_len, row_len) >> 16]
+    return out
+
+
 def uniform_int(seed: int, name: str, count: int, lo: int, hi: int) -> np.ndarray:
     """count integers i.i.d. uniform on the closed range [lo, hi] (host side)."""
     h = hash_u32(seed, name, 0, count).numpy()

@@ -88,6 +88,45 @@ def test_gemm(dtype, epi, shape):
         np.testing.assert_allclose(_f64(out), ref, rtol=EPS16[dtype] * 1.01, atol=2e-3 * EPS16[dtype] * 256)    # one 16-bit rounding of the result
 
 
+def _gemm_16_case(dtype, epi, M, N, K):
+    A = _rand((M, K), dtype, 10 + M + K, 1.0)
+    Wt = _rand((N, K), dtype, 20 + N + K, 1.0 / math.sqrt(K))
+    ref = _f64(A) @ _f64(Wt).T
+    if epi == B.EPI_RESIDUAL:
+        X0 = _rand((M, N), torch.float32, 30, 1.0)
+        out = X0.to(DEV).clone()
+        ref = _f64(X0) + ref
+    elif epi == B.EPI_SWIGLU:
+        out = torch.zeros(M, N // 2, dtype=dtype, device=DEV)
+        ref = O.silu(ref[:, :N // 2]) * ref[:, N // 2:]
+    else:
+        out = torch.zeros(M, N, dtype=dtype, device=DEV)
+    B.op_gemm(epi, A.to(DEV), Wt.to(DEV), out)
+    torch.cuda.synchronize()
+    if epi == B.EPI_RESIDUAL:
+        np.testing.assert_allclose(_f64(out), ref, rtol=1e-4, atol=1e-4)
+    else:
+        np.testing.assert_allclose(_f64(out), ref, rtol=EPS16[dtype] * 1.01, atol=2e-3 * EPS16[dtype] * 256)
+
+
+@pytest.mark.parametrize("dtype", SIXTEEN)
+@pytest.mark.parametrize("epi", [B.EPI_STORE, B.EPI_RESIDUAL, B.EPI_SWIGLU])
+@pytest.mark.parametrize("K", [64, 128, 192, 320, 448])
+def test_gemm_16_big_tile_with_few_and_odd_slice_counts(dtype, epi, K):
+    """4100 x 6144 outputs are 17 x 24 tiles of 256 x 256 (SwiGLU: 17 x 24 of 256 x 128), enough for the launcher to pick
+    the big tile, whose K loop is scheduled by hand two 64-deep slices per iteration: 1, 2, 3, 5 and 7 slices exercise
+    its prologue-only, single-iteration and mid-iteration exits."""
+    _gemm_16_case(dtype, epi, 4100, 6144, K)
+
+
+@pytest.mark.parametrize("dtype", SIXTEEN)
+@pytest.mark.parametrize("epi", [B.EPI_STORE, B.EPI_RESIDUAL, B.EPI_SWIGLU])
+def test_gemm_16_big_tile_with_a_ragged_last_column_tile(dtype, epi):
+    """N = 6144 + 128: the last column tile of the 256 x 256 path is half outside the matrix (SwiGLU: N / 2 = 3136 =
+    24.5 tiles of 128 output columns)."""
+    _gemm_16_case(dtype, epi, 4100, 6144 + 128, 320)
+
+
 @pytest.mark.parametrize("dtype", SIXTEEN)
 def test_gemm_16_fp32_output(dtype):
     M, N, K = 700, 6144, 1024

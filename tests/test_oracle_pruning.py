@@ -66,6 +66,33 @@ def test_contiguous_optimum_is_the_global_kmeans_optimum(seed):
     assert abs(got - best) < 1e-12
 
 
+@pytest.mark.parametrize("seed,n,spread", [(0, 200, 50), (1, 237, 9), (2, 160, 3), (3, 64, 1)])
+def test_kmeans_at_working_sizes_against_exact_rational_enumeration(seed, n, spread):
+    """k = 3 at the pool sizes the checks run at (hundreds of scores, many exact duplicates): every one of the
+    C(n-1, 2) contiguous partitions is costed in exact rational arithmetic from integer scores (within-cluster sum of
+    squares = sum x^2 - (sum x)^2 / size), the minimum taken, and among exactly tied partitions the lexicographically
+    smallest pair of split positions.  Integer scores keep the oracle's fp64 prefix sums exact, so its tie rule is
+    exercised on true ties."""
+    from fractions import Fraction
+    r = np.random.default_rng(100 + seed)
+    x = np.sort(r.integers(-spread, spread + 1, size=n))[::-1].astype(np.int64)      # rank order: descending
+    P = [0] * (n + 1)
+    Q = [0] * (n + 1)
+    for i, v in enumerate(x):
+        P[i + 1] = P[i] + int(v)
+        Q[i + 1] = Q[i] + int(v) * int(v)
+    cost = lambda i, j: Fraction(Q[j] - Q[i]) - Fraction((P[j] - P[i]) ** 2, j - i)
+    head = [cost(0, s) for s in range(n + 1) if s > 0]                                # head[s - 1] = cost(0, s)
+    tail = [cost(s, n) for s in range(n)]                                             # tail[s] = cost(s, n)
+    best, best_splits = None, None
+    for s1 in range(1, n - 1):
+        for s2 in range(s1 + 1, n):
+            c = head[s1 - 1] + cost(s1, s2) + tail[s2]
+            if best is None or c < best:                                              # strict: the first (smallest) pair wins ties
+                best, best_splits = c, [s1, s2]
+    assert O.kmeans_1d_splits(x.astype(np.float64), 3) == best_splits
+
+
 def test_kmeans_two_blobs_split_at_the_gap_and_tie_rule():
     x = np.array([10.2, 10.1, 9.9, 9.8, 1.2, 1.0, 0.9])
     assert O.kmeans_1d_splits(x, 2) == [4]
