@@ -265,6 +265,16 @@ int prism_op_score(const float *X, const int32_t *last_row, int32_t n_seqs, int3
 int prism_op_route(const float *scores, int32_t n, int32_t K_rem, int32_t n_clusters, float tau,
                    int8_t *fate, double *stats, void *stream);
 
+/* prism_op_route for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernel, same results as prism_op_route; the kernel's workspace
+ * (328 192 bytes, enough for n = PRISM_MAX_CANDS and n_clusters = PRISM_MAX_CLUSTERS; larger requests are rejected with
+ * PRISM_EINVAL) is a static device array of the library, one copy per device, held until the process ends.  The call
+ * allocates and frees nothing and does NOT synchronise: fate and stats are ready when `stream` has drained.  Every
+ * call on a device uses that device's one workspace, so calls that overlap on a device (different streams or threads)
+ * race; the kernel overwrites every workspace entry before reading it, so consecutive calls need no clearing. */
+int prism_op_route_static(const float *scores, int32_t n, int32_t K_rem, int32_t n_clusters, float tau,
+                          int8_t *fate, double *stats, void *stream);
+
 /* Stream compaction of the packed residual (Sec. 4.1: continue only on the remaining candidates):
  * rows [src_start[c], src_start[c]+len[c]) of X_src go to rows starting at dst_start[c] of X_dst for
  * each of the n_keep kept sequences; the arrays are [device]; X_dst must not alias X_src. */

@@ -23,7 +23,7 @@ MAX_CANDS, MAX_CLUSTERS, MAX_SEQ = 4096, 8, 8192
 
 EXPORTS = ["prism_create", "prism_select", "prism_set_forced_keep", "prism_destroy", "prism_strerror",
            "prism_last_error", "prism_op_embed", "prism_op_rmsnorm", "prism_op_gemm", "prism_op_qkv_finish", "prism_op_qkv_project", "prism_w4_bytes", "prism_op_quantize_w4", "prism_op_dequantize_w4",
-           "prism_op_attention", "prism_op_score", "prism_op_route", "prism_op_compact", "prism_op_topk"]
+           "prism_op_attention", "prism_op_score", "prism_op_route", "prism_op_route_static", "prism_op_compact", "prism_op_topk"]
 
 
 class PrismError(RuntimeError):
@@ -102,6 +102,7 @@ def lib() -> C.CDLL:
         _lib.prism_op_attention.argtypes = [i32, vp, vp, C.c_int64, C.POINTER(i32), C.POINTER(i32), i32, i32, i32, i32, vp, vp]
         _lib.prism_op_score.argtypes = [vp, vp, i32, i32, vp, vp, vp, i32, f32, vp, vp]
         _lib.prism_op_route.argtypes = [vp, i32, i32, i32, f32, vp, vp, vp]
+        _lib.prism_op_route_static.argtypes = [vp, i32, i32, i32, f32, vp, vp, vp]
         _lib.prism_op_compact.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp]
         _lib.prism_op_topk.argtypes = [vp, i32, i32, vp, vp, vp]
         _lib.prism_w4_bytes.restype = C.c_int64
@@ -317,6 +318,11 @@ def op_score(X, last_row, final_norm, w_yes, w_no, eps, scores):
 
 def op_route(scores, K_rem, n_clusters, tau, fate, stats):
     _check(lib().prism_op_route(_ptr(scores), scores.numel(), K_rem, n_clusters, tau, _ptr(fate), _ptr(stats), _stream()))
+
+
+def op_route_static(scores, K_rem, n_clusters, tau, fate, stats):
+    """prism_op_route on the library's static workspace: allocates nothing and does not synchronise."""
+    _check(lib().prism_op_route_static(_ptr(scores), scores.numel(), K_rem, n_clusters, tau, _ptr(fate), _ptr(stats), _stream()))
 
 
 def op_compact(X_src, X_dst, src_start, dst_start, length):

@@ -10,6 +10,8 @@
 // All decisions are taken in fp64 with a fixed operation order (sequential sums, no fused
 // multiply-add: this file is compiled with -ffp-contract=off), so that a host implementation that
 // follows the same order reaches the same bits.
+#include <mutex>
+
 #include "common.h"
 
 namespace prism {
@@ -198,4 +200,48 @@ int launch_route(const float *scores, int n, int K_rem, int n_clusters, float ta
   return PRISM_OK;
 }
 
+// ---- the same check for callers that cannot allocate --------------------------------------------------------------
+// The kernel's workspace (ranked scores, prefix sums, two cost rows, rank order, the argmin table) lives in a
+// file-scope device array sized for the largest check the library accepts.  Every device that loads the library holds
+// its own copy at its own address, looked up once per device.  The kernel writes every workspace entry before it reads
+// it, so nothing has to be cleared between calls; calls that overlap on one device share the array and race.
+static constexpr size_t up256(size_t v) { return (v + 255) / 256 * 256; }
+static constexpr size_t kRouteScratchBytes =
+    5 * up256((PRISM_MAX_CANDS + 1) * sizeof(double)) + up256((PRISM_MAX_CANDS + 1) * sizeof(int32_t)) +
+    up256((size_t)(PRISM_MAX_CLUSTERS + 1) * (PRISM_MAX_CANDS + 1) * sizeof(int32_t));
+static __device__ __align__(256) unsigned char scratch[kRouteScratchBytes];
+
+static constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static void *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (the array's name is only a host-side handle).
+static int scratch_of_current_device(void **out) {
+  int dev = -1;
+  PRISM_HIP(hipGetDevice(&dev));
+  PRISM_REQUIRE(dev >= 0 && dev < kMaxDevices, PRISM_EUNSUPPORTED, "route: device ordinal %d not supported", dev);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    PRISM_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    PRISM_REQUIRE(p, PRISM_EHIP, "route: the static workspace has no device address");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return PRISM_OK;
+}
+
 }  // namespace prism
+
+extern "C" int prism_op_route_static(const float *scores, int32_t n, int32_t K_rem, int32_t n_clusters, float tau,
+                                     int8_t *fate, double *stats, void *stream) {
+  using namespace prism;
+  PRISM_REQUIRE(n >= 1 && n <= PRISM_MAX_CANDS, PRISM_EINVAL, "route (static workspace): n = %d outside 1..%d", n, PRISM_MAX_CANDS);
+  PRISM_REQUIRE(n_clusters >= 2 && n_clusters <= PRISM_MAX_CLUSTERS, PRISM_EINVAL,
+                "route (static workspace): n_clusters = %d outside 2..%d", n_clusters, PRISM_MAX_CLUSTERS);
+  PRISM_REQUIRE(route_workspace_bytes(n, n_clusters) <= kRouteScratchBytes, PRISM_EINVAL,
+                "route (static workspace): the check needs more than the %zu bytes of the static workspace", kRouteScratchBytes);
+  void *ws = nullptr;
+  PRISM_TRY(scratch_of_current_device(&ws));
+  return launch_route(scores, n, K_rem, n_clusters, tau, fate, stats, ws, (hipStream_t)stream);
+}
