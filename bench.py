@@ -58,16 +58,88 @@ def cpu_baseline(w, wt_dev, q, cands, token_layers_job: int, n_cands: int):
 
 
 def stored_traffic(workload: str, kernel: str):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, if the
-    summary is for this workload and kernel; None otherwise (bench.py cannot run the profiler itself)."""
-    path = os.path.join(ROOT, "profiles", f"{workload}_gate_up_gemm_traffic.txt")
+    """HBM-side bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, if the summary is
+    for this workload and kernel; (None, reason) otherwise.  bench.py cannot run the profiler itself, so this is a STORED
+    figure: the second return value says where it comes from."""
+    rel = os.path.join("profiles", f"{workload}_gate_up_gemm_traffic.txt")
+    path = os.path.join(ROOT, rel)
     if not os.path.exists(path):
-        return None
+        return None, f"no stored counter summary ({rel})"
     kv = dict(l.split(":", 1) for l in open(path) if ":" in l and not l.startswith("#"))
     kv = {k.strip(): v.strip() for k, v in kv.items()}
     if kv.get("kernel") != kernel or kv.get("workload") != workload:
+        return None, f"{rel} is for {kv.get('kernel')} on {kv.get('workload')}"
+    return int(kv["fetch_bytes_per_launch"]) + int(kv["write_bytes_per_launch"]), \
+        f"stored, not measured in this run: {rel} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of {kv.get('measured', 'unknown date')})"
+
+
+def golden_scores(workload: str, mode: str):
+    """Every scoring event of the oracle's complete run of this workload (tests/golden/, written by the oracle alone):
+    {layer: {candidate: fp64 score}}, or None if no such run is stored."""
+    path = os.path.join(ROOT, "tests", "golden", f"fullsize_{workload}_{mode}.json")
+    if not os.path.exists(path):
         return None
-    return int(kv["fetch_bytes_per_launch"]) + int(kv["write_bytes_per_launch"])
+    d = json.load(open(path))
+    return {e["layer"]: {c: float(x) for c, x in zip(e["live"], e["scores"])} for e in d["events"]}, d["idx"]
+
+
+def parity_record(rep, idx, gold):
+    """Worst |device - oracle| over every score of every event that both runs took, and whether the top-K agrees."""
+    if gold is None:
+        return None
+    by_layer, gold_idx = gold
+    import numpy as np
+    worst, n = 0.0, 0
+    for e, layer in enumerate(rep.layer.tolist()):
+        for c, ref in by_layer.get(layer, {}).items():
+            g = rep.scores[e][c]
+            if not np.isnan(g):
+                worst = max(worst, abs(float(g) - ref))
+                n += 1
+    return {"worst_abs_score_err_vs_oracle": round(worst, 5), "scores_compared": n,
+            "topk_equals_oracle": [int(i) for i in idx] == [int(i) for i in gold_idx],
+            "oracle": "complete fp64 run stored under tests/golden/"}
+
+
+def kind_table(reps):
+    kinds = {}
+    for k, name in enumerate(KIND_NAMES):
+        ms = sum(r.kind_ms[k] for r in reps)
+        fl = sum(r.kind_flops[k] for r in reps)
+        n = sum(r.kind_launches[k] for r in reps)
+        kinds[name] = {"launches": n, "ms": round(ms, 3), "tflops": round(fl / ms / 1e9, 1) if ms > 0 and fl > 0 else None}
+    return kinds
+
+
+def utilisation(reps):
+    gemm_ms = sum(r.kind_ms[k] for r in reps for k in range(4))
+    gemm_fl = sum(r.kind_flops[k] for r in reps for k in range(4))
+    attn_ms = sum(r.kind_ms[4] for r in reps)
+    attn_fl = sum(r.kind_flops[4] for r in reps)
+    return {"layer_gemms": round(gemm_fl / gemm_ms / 1e9 / PEAK_BF16_TFLOPS, 4) if gemm_ms else None,
+            "attention": round(attn_fl / attn_ms / 1e9 / PEAK_BF16_TFLOPS, 4) if attn_ms else None}
+
+
+def by_pool_size(reps, tokens_per_cand=None):
+    """Per-kind TFLOP/s of the layer kernels split by the rows (live tokens) a launch covered: the pool shrinks at every
+    pruning event, so the same kernel runs at several sizes within one call."""
+    import numpy as np
+    out = {}
+    for k in range(5):
+        rows = {}
+        for r in reps:
+            sp = r.spans
+            if sp is None:
+                continue
+            for m in np.unique(sp.rows[(sp.kind == k) & (sp.rows > 0)]):
+                sel = (sp.kind == k) & (sp.rows == m) & (sp.flops > 0)
+                if sel.any():
+                    a = rows.setdefault(int(m), [0, 0.0, 0.0])
+                    a[0] += int(sel.sum()); a[1] += float(sp.ms[sel].sum()); a[2] += float(sp.flops[sel].sum())
+        out[KIND_NAMES[k]] = {(f"{m} rows" if not tokens_per_cand else f"{m // tokens_per_cand} candidates"):
+                              {"launches": v[0], "avg_us": round(v[1] / v[0] * 1e3, 1), "tflops": round(v[2] / v[1] / 1e9, 1)}
+                              for m, v in sorted(rows.items(), reverse=True) if v[1] > 0}
+    return out
 
 
 def main():
@@ -89,6 +161,8 @@ def main():
     ap.add_argument("--w4", action="store_true", help="4-bit layer weights (quantised on the device before the timed region)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unpruned", action="store_true")
+    ap.add_argument("--no-bf16", action="store_true", help="skip the bf16-operand sub-record")
+    ap.add_argument("--no-cfg5", action="store_true", help="skip the streamed + chunked 500-candidate sub-record (cfg4_8b only)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (the path would shard by candidate: sequences never interact)",
@@ -148,7 +222,7 @@ def main():
     reps = []
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        idx, scores, rep = p.select(q, cands, w.K, report=True)      # synchronous: results are on the host
+        idx, scores, rep = p.select(q, cands, w.K, report=True, spans=4096)      # synchronous: results are on the host
         reps.append(rep)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -165,26 +239,71 @@ def main():
         p0.destroy()
 
     # per-kernel-kind totals over the timed steps (HIP events around each launch on the compute stream)
-    kinds = {}
-    for k, name in enumerate(KIND_NAMES):
-        ms = sum(r.kind_ms[k] for r in reps)
-        fl = sum(r.kind_flops[k] for r in reps)
-        n = sum(r.kind_launches[k] for r in reps)
-        kinds[name] = {"launches": n, "ms": round(ms, 3), "tflops": round(fl / ms / 1e9, 1) if ms > 0 and fl > 0 else None}
+    kinds = kind_table(reps)
     dom = 2        # the gate/up GEMM with the SwiGLU epilogue carries more than half of all flops
     dom_ms = sum(r.kind_ms[dom] for r in reps)
     dom_fl = sum(r.kind_flops[dom] for r in reps)
     dom_n = sum(r.kind_launches[dom] for r in reps)
     achieved = dom_fl / dom_ms / 1e9
     op_t = "float" if m.dtype == "fp32" else args.operand
+    traffic, traffic_source = stored_traffic(w.name, f"gemm_16_kernel<{op_t},256,256,2,2,2>")
     roofline = {"bound": "mfma", "kernel": f"gemm_16_kernel<{op_t},256,256,2,2,SWIGLU>", "achieved": round(achieved, 1),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                "traffic": stored_traffic(w.name, f"gemm_16_kernel<{op_t},256,256,2,2,2>"),
+                "traffic": traffic, "traffic_source": traffic_source,
                 "flops_per_launch": dom_fl / dom_n, "avg_launch_ms": round(dom_ms / dom_n, 4), "launches": dom_n}
-    gemm_ms = sum(r.kind_ms[k] for r in reps for k in range(4))
-    gemm_fl = sum(r.kind_flops[k] for r in reps for k in range(4))
-    attn_ms = sum(r.kind_ms[4] for r in reps)
-    attn_fl = sum(r.kind_flops[4] for r in reps)
+    mode_name = "three_way" if args.mode == "three-way" else "drop_only"
+    plain_run = not args.w4 and args.checkpoints == "workload" and args.tau is None
+    gold = golden_scores(w.name, mode_name) if plain_run else None
+    const_len = len(set(len(c) for c in cands)) == 1
+
+    # ---- the same workload with bf16 matrix-core operands (the headline runs IEEE half operands)
+    bf16_rec = None
+    if not args.no_bf16 and m.dtype != "fp32" and args.operand != "bf16":
+        pb = B.Prism(m, wt, **{**opts, "operand": "bf16"})
+        pb.select(q, cands, w.K, report=False)
+        torch.cuda.synchronize()
+        tb = time.perf_counter()
+        breps = []
+        for _ in range(2):
+            bidx, bscores, brep = pb.select(q, cands, w.K, report=True, spans=4096)
+            breps.append(brep)
+        torch.cuda.synchronize()
+        b_ms = (time.perf_counter() - tb) / 2 * 1e3
+        pb.destroy()
+        bf16_rec = {"topk_latency_ms": round(b_ms, 3), "candidates_per_s": round(w.n_cands / (b_ms / 1e3), 2), "steps": 2,
+                    "kernels": kind_table(breps), "mfma_utilisation": utilisation(breps),
+                    "survivors": brep.n_after.tolist(), "topk": bidx.tolist(), "parity": parity_record(brep, bidx, gold)}
+
+    # ---- cfg 5: the same model streamed from pinned host memory, 500 candidates in chunks of 64, 24 GB cap
+    cfg5_rec = None
+    if args.workload == "cfg4_8b" and not args.no_cfg5 and plain_run and not args.lean:
+        w5 = W.WORKLOADS["cfg5_8b_stream"]
+        host_layers = [{k: v.to("cpu").pin_memory() for k, v in l.items()} for l in wt_for_oracle.layers]
+        wt5 = W.Weights(wt_for_oracle.embed, host_layers, wt_for_oracle.final_norm)
+        q5, cands5 = W.make_tokens(w5)
+        p5 = B.Prism(w5.model, wt5, checkpoints=w5.checkpoints, cv_threshold=w5.cv_threshold, n_clusters=w5.n_clusters,
+                     chunk_cands=w5.chunk_cands, hbm_cap_bytes=w5.hbm_cap_bytes, stream_weights=True, operand=args.operand)
+        p5.select(q5, cands5, w5.K, report=False)
+        torch.cuda.synchronize()
+        t5 = time.perf_counter()
+        reps5 = []
+        for _ in range(2):
+            idx5, scores5, rep5 = p5.select(q5, cands5, w5.K, report=True)
+            reps5.append(rep5)
+        torch.cuda.synchronize()
+        ms5 = (time.perf_counter() - t5) / 2 * 1e3
+        p5.destroy()
+        caller = int(wt_for_oracle.embed.numel() * 2 + wt_for_oracle.final_norm.numel() * 2)
+        cfg5_rec = {"workload": f"cfg5_8b_stream: {w5.n_cands} candidates, {int(sum(len(c) + len(q5) for c in cands5))} tokens, "
+                                f"layers streamed from pinned host memory ({'2' if not args.stream_slots else args.stream_slots} "
+                                f"buffers), chunks of {w5.chunk_cands} candidates, K={w5.K}",
+                    "topk_latency_ms": round(ms5, 3), "candidates_per_s": round(w5.n_cands / (ms5 / 1e3), 2), "steps": 2,
+                    "stream_GBps": round(rep5.bytes_streamed / rep5.ms_total / 1e6, 1), "bytes_streamed": int(rep5.bytes_streamed),
+                    "peak_hbm_bytes_library": int(rep5.peak_hbm_bytes), "caller_device_bytes": caller,
+                    "hbm_cap_bytes": int(w5.hbm_cap_bytes), "under_cap": bool(rep5.peak_hbm_bytes + caller <= w5.hbm_cap_bytes),
+                    "survivors": rep5.n_after.tolist(), "kernels": kind_table(reps5), "mfma_utilisation": utilisation(reps5),
+                    "parity": parity_record(rep5, idx5, golden_scores(w5.name, "drop_only"))}
+        del host_layers, wt5
 
     out = {
         "metric": "candidates/sec + top-K latency (ms), 8B-shaped reranker, 100 cands x 1024 tok"
@@ -207,9 +326,12 @@ def main():
         "layers_run": int(rep.layers_run), "token_layers": int(rep.token_layers), "peak_hbm_bytes": int(rep.peak_hbm_bytes), "bytes_streamed": int(rep.bytes_streamed),
         "topk": idx.tolist(),
         "kernels": kinds,
-        "mfma_utilisation": {"layer_gemms": round(gemm_fl / gemm_ms / 1e9 / PEAK_BF16_TFLOPS, 4) if gemm_ms else None,
-                             "attention": round(attn_fl / attn_ms / 1e9 / PEAK_BF16_TFLOPS, 4) if attn_ms else None},
+        "kernels_by_pool_size": by_pool_size(reps, len(q) + len(cands[0]) if const_len else None),
+        "mfma_utilisation": utilisation(reps),
         "roofline": roofline,
+        "parity": parity_record(rep, idx, gold),
+        "bf16_operands": bf16_rec,
+        "cfg5": cfg5_rec,
         "weights_gen_s": round(t_gen, 1),
     }
     if args.lean:

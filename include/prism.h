@@ -18,7 +18,12 @@
  *     (down to 2^-17 in magnitude, below that to within 2^-25) and round activations 8x finer than
  *     bf16, at the same matrix-core rate; bf16 operands trade that precision for range.
  *   - All entry points return PRISM_OK (0) or a negative PRISM_E* code; nothing throws,
- *     aborts or exits; outputs are untouched on error.  prism_last_error() gives detail.
+ *     aborts or exits; outputs are untouched on error (of a prism_report only n_events is defined then: 0; its
+ *     arrays may hold events recorded before the failure).  prism_last_error() gives detail.
+ *   - Conversions to IEEE half saturate at +-65504 (no infinity is ever produced, and nothing is counted or
+ *     reported): the default half operands suit activations within that range - true of the synthetic N(0, 0.02)
+ *     models here by orders of magnitude - and a model whose normalised inputs, q/k/v, attention output or SwiGLU output
+ *     can exceed it should run with prism_options.operand = PRISM_DTYPE_BF16, which has fp32's range.
  *   - A context is single-caller.  Different contexts may run concurrently.
  */
 #ifndef PRISM_H_
@@ -141,7 +146,9 @@ typedef struct {
   double   ms_layers;       /* out: GPU time inside transformer layers */
   double   ms_checks;       /* out: GPU time in scoring + pruning + compaction */
   int64_t  token_layers;    /* out: sum over executed layers of live tokens */
-  int64_t  peak_hbm_bytes;  /* out: library-owned device memory at its peak */
+  int64_t  peak_hbm_bytes;  /* out: library-owned device memory at its peak (what hbm_cap_bytes caps); the caller's own
+                               device buffers - a device-resident embedding table, final_norm, the head rows - are
+                               not in it */
   int64_t  bytes_streamed;  /* out: host->device weight bytes copied during the call */
   int32_t  layers_run;      /* out */
   /* out: per-kernel-kind totals over the call, from HIP events around each launch on the compute stream.
@@ -156,6 +163,14 @@ typedef struct {
   int64_t  bytes_hidden_moved;  /* out: residual-stream bytes copied device->host and host->device (offload_hidden) */
   int64_t  embed_rows_hit;      /* out: token occurrences whose embedding row was in the device cache (embed_residency 1) */
   int64_t  embed_rows_missed;   /* out: token occurrences whose row was fetched from the host table during the call */
+  /* Optional per-launch detail behind the kind_* totals, in launch order: the caller sets span_cap and the four arrays
+   * ([host], span_cap entries each), or span_cap = 0 and NULL pointers.  rows = tokens (GEMM rows) the launch covered. */
+  int32_t  span_cap;            /* in */
+  int32_t  n_spans;             /* out: spans recorded (the first span_cap of the call) */
+  int32_t *span_kind;           /* out */
+  int32_t *span_rows;           /* out */
+  float   *span_ms;             /* out */
+  double  *span_flops;          /* out */
 } prism_report;
 
 /* Build a context.  Device-resident layer weights are repacked once into library-owned HBM

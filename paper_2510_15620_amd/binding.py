@@ -66,7 +66,9 @@ class prism_report(C.Structure):
                 ("token_layers", C.c_int64), ("peak_hbm_bytes", C.c_int64), ("bytes_streamed", C.c_int64),
                 ("layers_run", C.c_int32), ("kind_launches", C.c_int32 * 6), ("kind_ms", C.c_double * 6),
                 ("kind_flops", C.c_double * 6), ("bytes_hidden_moved", C.c_int64), ("embed_rows_hit", C.c_int64),
-                ("embed_rows_missed", C.c_int64)]
+                ("embed_rows_missed", C.c_int64), ("span_cap", C.c_int32), ("n_spans", C.c_int32),
+                ("span_kind", C.POINTER(C.c_int32)), ("span_rows", C.POINTER(C.c_int32)), ("span_ms", C.POINTER(C.c_float)),
+                ("span_flops", C.POINTER(C.c_double))]
 
 
 _lib = None
@@ -157,6 +159,7 @@ class Report:
     bytes_hidden_moved: int = 0
     embed_rows_hit: int = 0
     embed_rows_missed: int = 0
+    spans: Optional[np.ndarray] = None   # per launch, in order: structured array (kind, rows, ms, flops); None unless asked for
 
 
 class Prism:
@@ -191,7 +194,8 @@ class Prism:
         self.n_checkpoints = len(ck)
         _check(lib().prism_create(C.byref(m), C.byref(w), C.byref(o), C.byref(self._ctx)))
 
-    def select(self, query_tokens, cand_tokens: Sequence, K: int, report: bool = True):
+    def select(self, query_tokens, cand_tokens: Sequence, K: int, report: bool = True, spans: int = 0):
+        """spans: capacity of the per-launch detail of the report (0 = none)."""
         q, qp = _i32_array(query_tokens)
         cands = [np.ascontiguousarray(c, dtype=np.int32) for c in cand_tokens]
         n = len(cands)
@@ -213,6 +217,12 @@ class Prism:
                                P(arrs["n_after"], C.c_int32), P(arrs["tokens_after"], C.c_int32), P(arrs["gate"], C.c_int32),
                                P(arrs["n_clusters"], C.c_int32), P(arrs["mean"], C.c_double), P(arrs["std"], C.c_double),
                                P(arrs["scores"], C.c_float), P(arrs["fate"], C.c_int8))
+            if spans > 0:
+                sp = {"kind": np.zeros(spans, np.int32), "rows": np.zeros(spans, np.int32), "ms": np.zeros(spans, np.float32),
+                      "flops": np.zeros(spans, np.float64)}
+                rep.span_cap = spans
+                rep.span_kind, rep.span_rows = P(sp["kind"], C.c_int32), P(sp["rows"], C.c_int32)
+                rep.span_ms, rep.span_flops = P(sp["ms"], C.c_float), P(sp["flops"], C.c_double)
         _check(lib().prism_select(self._ctx, qp, len(q), cptrs, lp, n, K, out_idx.ctypes.data_as(C.POINTER(C.c_int32)),
                                   out_scores.ctypes.data_as(C.POINTER(C.c_float)), C.byref(count),
                                   C.byref(rep) if rep is not None else None))
@@ -226,6 +236,10 @@ class Prism:
                        rep.token_layers, rep.peak_hbm_bytes, rep.bytes_streamed, rep.layers_run,
                        list(rep.kind_launches), list(rep.kind_ms), list(rep.kind_flops), rep.bytes_hidden_moved,
                        rep.embed_rows_hit, rep.embed_rows_missed)
+            if spans > 0:
+                n = rep.n_spans
+                r.spans = np.rec.fromarrays([sp["kind"][:n], sp["rows"][:n], sp["ms"][:n], sp["flops"][:n]],
+                                            names="kind,rows,ms,flops")
         return out_idx[:k].copy(), out_scores[:k].copy(), r
 
     def set_forced_keep(self, masks: Optional[np.ndarray]):

@@ -91,7 +91,8 @@ bool gemm_16_supported(int epilogue, int N, int K);
 struct QkvEpilogue {
   const int32_t *pos, *vt_col;
   const void *q_gain, *k_gain;
-  const float2 *rope_tab;
+  const float2 *rope_tab_t;   // transposed table: (cos, sin) of (pos, i) at [i * rope_stride + pos]
+  int rope_stride;            // positions the table was built for
   void *QK;
   void *Vt;
   int64_t vt_stride;
@@ -113,8 +114,9 @@ int launch_quantize_w4(const void *W_bf16, int N, int K, void *blob, hipStream_t
 int launch_dequantize_w4(const void *blob, int N, int K, int dtype, void *out, hipStream_t s);
 int launch_convert_bf16(const void *src, int64_t n, int dtype, void *dst, hipStream_t s);
 
-// cos/sin table for RoPE: tab[pos * (hd/2) + i] = (cos, sin)(pos * base^(-2i/hd)), evaluated in fp64
-int launch_rope_table(float2 *tab, int n_pos, int head_dim, float rope_base, hipStream_t s);
+// cos/sin table for RoPE: tab[pos * (hd/2) + i] = (cos, sin)(pos * base^(-2i/hd)), evaluated in fp64; transposed:
+// tab[i * n_pos + pos]
+int launch_rope_table(float2 *tab, int n_pos, int head_dim, float rope_base, hipStream_t s, bool transposed = false);
 // q/k per-head RMSNorm + RoPE from the fp32 projection.  fp32 mode: in place (QK == nullptr).  bf16 mode:
 // q,k -> QK [T, (nq+nkv)*hd] bf16.
 int launch_qk_finish(int dtype, float *QKV, const int32_t *pos, const void *q_gain, const void *k_gain, int T,

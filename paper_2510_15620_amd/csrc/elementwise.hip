@@ -83,20 +83,21 @@ int launch_rmsnorm(const float *X, const void *gain, int T, int hidden, float ep
 }
 
 // ------------------------------------------------------------------------------------------------
-// RoPE table, evaluated in fp64 and rounded once: tab[pos][i] = (cos, sin)(pos * base^(-2 i / hd)).
-__global__ void rope_table_kernel(float2 *tab, int n_pos, int half, double log2_base) {
+// RoPE table, evaluated in fp64 and rounded once: (cos, sin)(pos * base^(-2 i / hd)) at tab[pos * half + i], or, transposed,
+// at tab[i * n_pos + pos] (the layout the fused q/k/v epilogue reads: consecutive tokens of a sequence are then neighbours).
+__global__ void rope_table_kernel(float2 *tab, int n_pos, int half, double log2_base, int transposed) {
   const int idx = blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= n_pos * half) return;
-  const int pos = idx / half, i = idx % half;
+  const int pos = transposed ? idx % n_pos : idx / half, i = transposed ? idx / n_pos : idx % half;
   const double theta = exp2(-(double)i / (double)half * log2_base);
   const double a = (double)pos * theta;
   tab[idx] = make_float2((float)cos(a), (float)sin(a));
 }
 
-int launch_rope_table(float2 *tab, int n_pos, int head_dim, float rope_base, hipStream_t s) {
+int launch_rope_table(float2 *tab, int n_pos, int head_dim, float rope_base, hipStream_t s, bool transposed) {
   PRISM_REQUIRE(tab && n_pos > 0 && head_dim > 0 && head_dim % 2 == 0 && rope_base > 0, PRISM_EINVAL, "rope table: bad arguments");
   const int half = head_dim / 2, n = n_pos * half;
-  rope_table_kernel<<<cdiv(n, 256), 256, 0, s>>>(tab, n_pos, half, log2((double)rope_base));
+  rope_table_kernel<<<cdiv(n, 256), 256, 0, s>>>(tab, n_pos, half, log2((double)rope_base), transposed ? 1 : 0);
   PRISM_HIP(hipGetLastError());
   return PRISM_OK;
 }

@@ -161,6 +161,262 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_16_kernel(const OT *__restri
   };
 
 
+  // ---- epilogue.  The W fragment was the instruction's first operand, so the 32x32 accumulator tile is
+  //      transposed: a lane holds ONE row of A, m = lane % 32, and the output columns
+  //      n = (e / 4) * 8 + (lane / 32) * 4 + e % 4, e = 0..15: four runs of 4 consecutive columns.
+  //      Written straight from that layout, one store instruction touches 32 rows with 16-32 bytes in each, and
+  //      the number of cache lines an instruction touches - not the bytes - is what the memory path charges for
+  //      (measured: 12-29 us per 256 x 256 tile, a tenth to a fifth of the tile's time).  So every block of 32 rows goes
+  //      through LDS, which is free once the K loop is done: lanes write their row's values, then read back 16 bytes
+  //      each along the rows, so that an instruction reads or writes whole lines (2-8 complete rows of the wave's
+  //      columns).  LDS requests of one wave are served in order, so no barrier is needed between the two phases.
+  //      The epilogue is a lambda expanded after EACH of the two K loops below rather than once behind their join: the
+  //      accumulators then stay wherever the loop left them (with one copy behind the join the register allocator parks
+  //      dozens of them in scratch memory to reconcile the two loops' assignments).
+  auto epilogue = [&]() __attribute__((always_inline)) {
+  // Accumulator element (i, j, e), fetched from its accumulation register when it is needed: behind the hand-scheduled
+  // loop all 256 of them sit in AGPRs, and read as plain values the compiler would copy the whole set into vector
+  // registers at once, leaving none for the epilogue's own arithmetic.
+  // (The compiler does not look inside these statements, so the wait between a matrix instruction and the first read
+  // of its result is spelled out: every accumulator tile passes through an empty statement, which puts all matrix
+  // instructions before it, then 32 idle cycles - more than the deepest instruction needs to retire.  All of these are
+  // volatile, which keeps them in this order.)
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) asm volatile("" : "+a"(acc[i][j]));
+  asm volatile("s_nop 15\n\ts_nop 15");
+  auto AC = [&](int i, int j, int e) __attribute__((always_inline)) {
+    float r;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(r) : "a"(acc[i][j][e]));
+    return r;
+  };
+  __syncthreads();              // every wave's operand loads have landed and nobody reads operands any more
+  const int m_in = lane & 31, n_in = (lane >> 5) * 4;
+  constexpr int SWZ = CPR >= 16 ? 15 : CPR - 1;                     // chunk rotation by row: spreads a column of 16-byte
+                                                                    // writes (one per row) over the banks
+  static_assert(32 * RB <= 2 * (BM + BN) * BK * (int)sizeof(OT) / NW, "staging block must fit the wave's share of LDS");
+  unsigned char *stg = smem + wave * (2 * (BM + BN) * BK * (int)sizeof(OT) / NW);
+  // values for columns n .. n + 3 (n a multiple of 4, within the wave's columns) of staged row m
+  auto put32 = [&](int m, int n, const f32x4 &v) __attribute__((always_inline)) {
+    *reinterpret_cast<f32x4 *>(stg + m * RB + (((n >> 2) ^ (m & SWZ)) << 4)) = v;
+  };
+  auto put16 = [&](int m, int n, const typename Mfma<OT>::vec4 &v) __attribute__((always_inline)) {
+    *reinterpret_cast<typename Mfma<OT>::vec4 *>(stg + m * RB + (((n >> 3) ^ (m & SWZ)) << 4) + (n & 4) * 2) = v;
+  };
+  auto staged = [&](int rr) __attribute__((always_inline)) {
+    const int r = rr * NR + f_row;
+    return *reinterpret_cast<const uint4 *>(stg + r * RB + ((f_chunk ^ (r & SWZ)) << 4));
+  };
+  // Flushes the staged block to rows row0 + r of a row-major destination (row pitch `pitch` bytes, the wave's first
+  // column at byte col_byte0 of a row).
+  auto flush_store = [&](unsigned char *dst, int64_t pitch, int64_t col_byte0, int row0) __attribute__((always_inline)) {
+#pragma unroll
+    for (int rr = 0; rr < NI; ++rr) {
+      const int row = row0 + rr * NR + f_row;
+      const uint4 v = staged(rr);
+      if (row < M) *reinterpret_cast<uint4 *>(dst + (int64_t)row * pitch + col_byte0 + f_chunk * 16) = v;
+    }
+  };
+
+  if constexpr (EPI == kEpiQkv) {
+    // The wave's 128 columns are one head.  A row's 128 values sit in lanes l and l ^ 32 (64 each); the rotate-half
+    // partner of column d is d + 64 = the same register of accumulator tile j + 2, so the per-head RMSNorm (one
+    // cross-lane add), the rotation and the single rounding all happen on the accumulators.  What the memory path
+    // charges for is cache lines touched per instruction, so the cos/sin pairs come from the TRANSPOSED table (the 32
+    // tokens of a row block are consecutive positions of a sequence almost always: two to four lines per load instead of
+    // one or two per lane) and the finished q / k rows go through the staging block like the other epilogues' outputs.
+    static_assert(WNT == 128 && TN == 4, "one head per wavefront");
+    typedef typename Mfma<OT>::vec4 vec4;
+    const int head = (n0 + wn * WNT) >> 7;                 // wave-uniform
+    if (head < qe.nq + qe.nkv) {
+      const OT *gain = reinterpret_cast<const OT *>(head < qe.nq ? qe.q_gain : qe.k_gain);
+      vec4 ga[2][4], gb[2][4];
+      if (qe.qk_norm) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            ga[j][g] = *reinterpret_cast<const vec4 *>(gain + j * 32 + g * 8 + n_in);
+            gb[j][g] = *reinterpret_cast<const vec4 *>(gain + j * 32 + g * 8 + n_in + 64);
+          }
+      }
+      const int64_t pitch = (int64_t)(qe.nq + qe.nkv) * 128 * 2;
+      // (cos, sin) of (pos, d) sits at [d * stride + pos]: a wave-uniform base per column plus one 32-bit lane offset.
+      // The positions of all four row blocks are fetched first and the 32 pairs of block i + 1 are requested before
+      // block i is worked on, so the tile pays the two memory latencies once, not once per block.
+      unsigned lane_off[TM];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int row = m0 + wm * WMT + i * 32 + m_in;
+        lane_off[i] = (unsigned)n_in * (unsigned)qe.rope_stride + (unsigned)qe.pos[row < M ? row : M - 1];
+      }
+      float2 cs[2][2][4][4];
+      auto load_cs = [&](int i) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+              cs[i & 1][j][g][q] = (qe.rope_tab_t + (int64_t)(j * 32 + g * 8 + q) * qe.rope_stride)[lane_off[i]];
+      };
+      load_cs(0);
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int row0 = m0 + wm * WMT + i * 32;
+        if (i + 1 < TM) load_cs(i + 1);
+        float r = 1.f;
+        if (qe.qk_norm) {
+          float ss = 0.f;
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+              const float v = AC(i, j, e);
+              ss += v * v;
+            }
+          ss += __shfl_xor(ss, 32);
+          r = 1.0f / sqrtf(ss / 128.f + qe.eps);
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int d = j * 32 + g * 8 + n_in;
+            vec4 lo, hi;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const float2 c = cs[i & 1][j][g][q];
+              float a = AC(i, j, g * 4 + q), b = AC(i, j + 2, g * 4 + q);
+              if (qe.qk_norm) {
+                a = a * r * to_f32(ga[j][g][q]);
+                b = b * r * to_f32(gb[j][g][q]);
+              }
+              lo[q] = from_f32<OT>(a * c.x - b * c.y);
+              hi[q] = from_f32<OT>(b * c.x + a * c.y);
+            }
+            put16(m_in, d, lo);
+            put16(m_in, d + 64, hi);
+          }
+        }
+        flush_store(reinterpret_cast<unsigned char *>(qe.QK), pitch, (int64_t)head * 128 * 2, row0);
+      }
+    } else {
+      // v head: rounded to the operand type, stored as half, transposed (32 consecutive tokens of one d are contiguous)
+      int vcol[TM];                                          // all four blocks' columns first: one memory latency, not four
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int row = m0 + wm * WMT + i * 32 + m_in;
+        vcol[i] = qe.vt_col[row < M ? row : M - 1];
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int row = m0 + wm * WMT + i * 32 + m_in;
+        if (row >= M) continue;
+        f16 *vt = reinterpret_cast<f16 *>(qe.Vt) + (int64_t)(head - qe.nq - qe.nkv) * 128 * qe.vt_stride + vcol[i];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int d = j * 32 + (e >> 2) * 8 + n_in + (e & 3);
+            vt[(int64_t)d * qe.vt_stride] = from_f32<f16>(to_f32(from_f32<OT>(AC(i, j, e))));
+          }
+      }
+    }
+    return;
+  }
+
+  if (full_n) {
+    load_old(0);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int row0 = m0 + wm * WMT + i * 32;                       // first row of the block
+      if (EPI == PRISM_EPI_SWIGLU) {
+#pragma unroll
+        for (int j = 0; j < TN / 2; ++j)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            typename Mfma<OT>::vec4 v;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const float gt = AC(i, j, g * 4 + q), up = AC(i, j + TN / 2, g * 4 + q);
+              v[q] = from_f32<OT>(gt / (1.0f + __expf(-gt)) * up);
+            }
+            put16(m_in, j * 32 + g * 8 + n_in, v);
+          }
+        flush_store(reinterpret_cast<unsigned char *>(out_), (int64_t)F * 2, (int64_t)(n0 + wn * OUTW) * 2, row0);
+      } else if (EPI == PRISM_EPI_RESIDUAL) {
+        // read-modify-write of the fp32 stream, whole lines per instruction; the loads of the next block are requested
+        // before this block is staged, so the tile pays the memory latency once, not per block
+        if (i + 1 < TM) load_old(i + 1);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            f32x4 v;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[q] = AC(i, j, g * 4 + q);
+            put32(m_in, j * 32 + g * 8 + n_in, v);
+          }
+#pragma unroll
+        for (int rr = 0; rr < NI; ++rr) {
+          const int row = row0 + rr * NR + f_row;
+          const uint4 u = staged(rr);
+          f32x4 v = old[i & 1][rr];
+          v[0] += __uint_as_float(u.x); v[1] += __uint_as_float(u.y); v[2] += __uint_as_float(u.z); v[3] += __uint_as_float(u.w);
+          if (row < M) *reinterpret_cast<f32x4 *>(xo + (int64_t)row * N) = v;
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            if (EPI == PRISM_EPI_STORE_F32) {
+              f32x4 v;
+#pragma unroll
+              for (int q = 0; q < 4; ++q) v[q] = AC(i, j, g * 4 + q);
+              put32(m_in, j * 32 + g * 8 + n_in, v);
+            } else {
+              typename Mfma<OT>::vec4 v;
+#pragma unroll
+              for (int q = 0; q < 4; ++q) v[q] = from_f32<OT>(AC(i, j, g * 4 + q));
+              put16(m_in, j * 32 + g * 8 + n_in, v);
+            }
+          }
+        flush_store(reinterpret_cast<unsigned char *>(out_), (int64_t)N * ES, (int64_t)(n0 + wn * OUTW) * ES, row0);
+      }
+    }
+    return;
+  }
+
+  // ---- ragged last column tile (N not a multiple of the tile, or rows not 16-byte aligned): element by element
+  if constexpr (EPI != kEpiQkv) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int row = m0 + wm * WMT + i * 32 + m_in;
+      if (row >= M) continue;
+#pragma unroll
+      for (int j = 0; j < (EPI == PRISM_EPI_SWIGLU ? TN / 2 : TN); ++j)
+        for (int g = 0; g < 4; ++g)
+          for (int q = 0; q < 4; ++q) {
+            const int col = n0 + wn * OUTW + j * 32 + g * 8 + n_in + q;
+            if (col >= F) continue;
+            if (EPI == PRISM_EPI_SWIGLU) {
+              const float gt = AC(i, j, g * 4 + q), up = AC(i, j + TN / 2, g * 4 + q);
+              reinterpret_cast<OT *>(out_)[(int64_t)row * F + col] = from_f32<OT>(gt / (1.0f + __expf(-gt)) * up);
+            } else if (EPI == PRISM_EPI_RESIDUAL) {
+              reinterpret_cast<float *>(out_)[(int64_t)row * N + col] += AC(i, j, g * 4 + q);
+            } else if (EPI == PRISM_EPI_STORE_F32) {
+              reinterpret_cast<float *>(out_)[(int64_t)row * N + col] = AC(i, j, g * 4 + q);
+            } else {
+              reinterpret_cast<OT *>(out_)[(int64_t)row * N + col] = from_f32<OT>(AC(i, j, g * 4 + q));
+            }
+          }
+    }
+  }
+  };
+
   // The 256x256 / 2x2-wave configuration runs the hand-scheduled loop; other shapes take the compiler's schedule.
   constexpr bool kHandScheduled = BM == 256 && BN == 256 && WM == 2 && WN == 2;
   // interior tiles only: the hand-scheduled loop assumes that the tile's rows of A and W all exist
@@ -192,6 +448,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_16_kernel(const OT *__restri
         else PRISM_RUN_KLOOP(PRISM_KLOOP4_BF16_PLAIN);
       }
 #undef PRISM_RUN_KLOOP
+      epilogue();
     }
   } else {
     vec8 af[2][TM], bfr[2][TN];
@@ -221,203 +478,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_16_kernel(const OT *__restri
       }
       __syncthreads();                                         // next slice landed (vmcnt) and everyone is done with this one
     }
-  }
-
-  // ---- epilogue.  The W fragment was the instruction's first operand, so the 32x32 accumulator tile is
-  //      transposed: a lane holds ONE row of A, m = lane % 32, and the output columns
-  //      n = (e / 4) * 8 + (lane / 32) * 4 + e % 4, e = 0..15: four runs of 4 consecutive columns.
-  //      Written straight from that layout, one store instruction touches 32 rows with 16-32 bytes in each, and
-  //      the number of cache lines an instruction touches - not the bytes - is what the memory path charges for
-  //      (measured: 12-29 us per 256 x 256 tile, a tenth to a fifth of the tile's time).  So every block of 32 rows goes
-  //      through LDS, which is free once the K loop is done: lanes write their row's values, then read back 16 bytes
-  //      each along the rows, so that an instruction reads or writes whole lines (2-8 complete rows of the wave's
-  //      columns).  LDS requests of one wave are served in order, so no barrier is needed between the two phases.
-  if constexpr (EPI == kEpiQkv) {
-    // The q/k/v epilogue writes straight from the accumulator layout: it is bound by its arithmetic (norm, rotation,
-    // conversions: about 7 instructions per value), not by its stores (measured: staging it through LDS costs 4 %).
-    const int m_in = lane & 31, n_in = (lane >> 5) * 4;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const int row = m0 + wm * WMT + i * 32 + m_in;
-      if (row >= M) continue;
-      {
-      // The wave's 128 columns are one head.  A row's 128 values sit in lanes l and l ^ 32 (64 each); the rotate-half
-      // partner of column d is d + 64 = the same register of accumulator tile j + 2.
-      if constexpr (EPI == kEpiQkv) {
-        static_assert(WNT == 128 && TN == 4, "one head per wavefront");
-        typedef typename Mfma<OT>::vec4 vec4;
-        const int head = (n0 + wn * WNT) >> 7;                 // wave-uniform
-        if (head < qe.nq + qe.nkv) {
-          float r = 1.f;
-          if (qe.qk_norm) {
-            float ss = 0.f;
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-              for (int e = 0; e < 16; ++e) ss += acc[i][j][e] * acc[i][j][e];
-            ss += __shfl_xor(ss, 32);
-            r = 1.0f / sqrtf(ss / 128.f + qe.eps);
-          }
-          const OT *gain = reinterpret_cast<const OT *>(head < qe.nq ? qe.q_gain : qe.k_gain);
-          const float2 *tab = qe.rope_tab + (int64_t)qe.pos[row] * 64;
-          OT *orow = reinterpret_cast<OT *>(qe.QK) + (int64_t)row * ((qe.nq + qe.nkv) * 128) + head * 128;
-#pragma unroll
-          for (int j = 0; j < 2; ++j) {
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-              const int d = j * 32 + g * 8 + n_in;
-              const f32x4 cs01 = *reinterpret_cast<const f32x4 *>(tab + d), cs23 = *reinterpret_cast<const f32x4 *>(tab + d + 2);
-              const float cs[8] = {cs01[0], cs01[1], cs01[2], cs01[3], cs23[0], cs23[1], cs23[2], cs23[3]};
-              vec4 ga, gb, lo, hi;
-              if (qe.qk_norm) {
-                ga = *reinterpret_cast<const vec4 *>(gain + d);
-                gb = *reinterpret_cast<const vec4 *>(gain + d + 64);
-              }
-#pragma unroll
-              for (int q = 0; q < 4; ++q) {
-                float a = acc[i][j][g * 4 + q], b = acc[i][j + 2][g * 4 + q];
-                if (qe.qk_norm) {
-                  a = a * r * to_f32(ga[q]);
-                  b = b * r * to_f32(gb[q]);
-                }
-                lo[q] = from_f32<OT>(a * cs[2 * q] - b * cs[2 * q + 1]);
-                hi[q] = from_f32<OT>(b * cs[2 * q] + a * cs[2 * q + 1]);
-              }
-              *reinterpret_cast<vec4 *>(orow + d) = lo;
-              *reinterpret_cast<vec4 *>(orow + d + 64) = hi;
-            }
-          }
-        } else {
-          // v head: rounded to the operand type, stored as half, transposed (32 consecutive tokens of one d are contiguous)
-          f16 *vt = reinterpret_cast<f16 *>(qe.Vt) + (int64_t)(head - qe.nq - qe.nkv) * 128 * qe.vt_stride + qe.vt_col[row];
-#pragma unroll
-          for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-              const int d = j * 32 + (e >> 2) * 8 + n_in + (e & 3);
-              vt[(int64_t)d * qe.vt_stride] = from_f32<f16>(to_f32(from_f32<OT>(acc[i][j][e])));
-            }
-        }
-      }
-      }
-    }
-    return;
-  }
-  __syncthreads();              // every wave's operand loads have landed and nobody reads operands any more
-  const int m_in = lane & 31, n_in = (lane >> 5) * 4;
-  constexpr int SWZ = CPR >= 16 ? 15 : CPR - 1;                     // chunk rotation by row: spreads a column of 16-byte
-                                                                    // writes (one per row) over the banks
-  static_assert(32 * RB <= 2 * (BM + BN) * BK * (int)sizeof(OT) / NW, "staging block must fit the wave's share of LDS");
-  unsigned char *stg = smem + wave * (2 * (BM + BN) * BK * (int)sizeof(OT) / NW);
-  // values for columns n .. n + 3 (n a multiple of 4, within the wave's columns) of staged row m
-  auto put32 = [&](int m, int n, const f32x4 &v) __attribute__((always_inline)) {
-    *reinterpret_cast<f32x4 *>(stg + m * RB + (((n >> 2) ^ (m & SWZ)) << 4)) = v;
-  };
-  auto put16 = [&](int m, int n, const typename Mfma<OT>::vec4 &v) __attribute__((always_inline)) {
-    *reinterpret_cast<typename Mfma<OT>::vec4 *>(stg + m * RB + (((n >> 3) ^ (m & SWZ)) << 4) + (n & 4) * 2) = v;
-  };
-  auto staged = [&](int rr) __attribute__((always_inline)) {
-    const int r = rr * NR + f_row;
-    return *reinterpret_cast<const uint4 *>(stg + r * RB + ((f_chunk ^ (r & SWZ)) << 4));
-  };
-  // Flushes the staged block to rows row0 + r of a row-major destination (row pitch `pitch` bytes, the wave's first
-  // column at byte col_byte0 of a row).
-  auto flush_store = [&](unsigned char *dst, int64_t pitch, int64_t col_byte0, int row0) __attribute__((always_inline)) {
-#pragma unroll
-    for (int rr = 0; rr < NI; ++rr) {
-      const int row = row0 + rr * NR + f_row;
-      const uint4 v = staged(rr);
-      if (row < M) *reinterpret_cast<uint4 *>(dst + (int64_t)row * pitch + col_byte0 + f_chunk * 16) = v;
-    }
-  };
-
-  if (full_n) {
-    load_old(0);
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const int row0 = m0 + wm * WMT + i * 32;                       // first row of the block
-      if (EPI == PRISM_EPI_SWIGLU) {
-#pragma unroll
-        for (int j = 0; j < TN / 2; ++j)
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            typename Mfma<OT>::vec4 v;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              const float gt = acc[i][j][g * 4 + q], up = acc[i][j + TN / 2][g * 4 + q];
-              v[q] = from_f32<OT>(gt / (1.0f + __expf(-gt)) * up);
-            }
-            put16(m_in, j * 32 + g * 8 + n_in, v);
-          }
-        flush_store(reinterpret_cast<unsigned char *>(out_), (int64_t)F * 2, (int64_t)(n0 + wn * OUTW) * 2, row0);
-      } else if (EPI == PRISM_EPI_RESIDUAL) {
-        // read-modify-write of the fp32 stream, whole lines per instruction; the loads of the next block are requested
-        // before this block is staged, so the tile pays the memory latency once, not per block
-        if (i + 1 < TM) load_old(i + 1);
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            f32x4 v;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) v[q] = acc[i][j][g * 4 + q];
-            put32(m_in, j * 32 + g * 8 + n_in, v);
-          }
-#pragma unroll
-        for (int rr = 0; rr < NI; ++rr) {
-          const int row = row0 + rr * NR + f_row;
-          const uint4 u = staged(rr);
-          f32x4 v = old[i & 1][rr];
-          v[0] += __uint_as_float(u.x); v[1] += __uint_as_float(u.y); v[2] += __uint_as_float(u.z); v[3] += __uint_as_float(u.w);
-          if (row < M) *reinterpret_cast<f32x4 *>(xo + (int64_t)row * N) = v;
-        }
-      } else {
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            if (EPI == PRISM_EPI_STORE_F32) {
-              f32x4 v;
-#pragma unroll
-              for (int q = 0; q < 4; ++q) v[q] = acc[i][j][g * 4 + q];
-              put32(m_in, j * 32 + g * 8 + n_in, v);
-            } else {
-              typename Mfma<OT>::vec4 v;
-#pragma unroll
-              for (int q = 0; q < 4; ++q) v[q] = from_f32<OT>(acc[i][j][g * 4 + q]);
-              put16(m_in, j * 32 + g * 8 + n_in, v);
-            }
-          }
-        flush_store(reinterpret_cast<unsigned char *>(out_), (int64_t)N * ES, (int64_t)(n0 + wn * OUTW) * ES, row0);
-      }
-    }
-    return;
-  }
-
-  // ---- ragged last column tile (N not a multiple of the tile, or rows not 16-byte aligned): element by element
-  if constexpr (EPI != kEpiQkv) {
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const int row = m0 + wm * WMT + i * 32 + m_in;
-      if (row >= M) continue;
-#pragma unroll
-      for (int j = 0; j < (EPI == PRISM_EPI_SWIGLU ? TN / 2 : TN); ++j)
-        for (int g = 0; g < 4; ++g)
-          for (int q = 0; q < 4; ++q) {
-            const int col = n0 + wn * OUTW + j * 32 + g * 8 + n_in + q;
-            if (col >= F) continue;
-            if (EPI == PRISM_EPI_SWIGLU) {
-              const float gt = acc[i][j][g * 4 + q], up = acc[i][j + TN / 2][g * 4 + q];
-              reinterpret_cast<OT *>(out_)[(int64_t)row * F + col] = from_f32<OT>(gt / (1.0f + __expf(-gt)) * up);
-            } else if (EPI == PRISM_EPI_RESIDUAL) {
-              reinterpret_cast<float *>(out_)[(int64_t)row * N + col] += acc[i][j][g * 4 + q];
-            } else if (EPI == PRISM_EPI_STORE_F32) {
-              reinterpret_cast<float *>(out_)[(int64_t)row * N + col] = acc[i][j][g * 4 + q];
-            } else {
-              reinterpret_cast<OT *>(out_)[(int64_t)row * N + col] = from_f32<OT>(acc[i][j][g * 4 + q]);
-            }
-          }
-    }
+    epilogue();
   }
 }
 
@@ -498,7 +559,7 @@ bool gemm_16_qkv_supported(int M, int nq, int nkv, int hd, int K) {
 }
 
 int launch_gemm_16_qkv(int dtype, const void *Xn, const void *Wqkv, int M, int K, int hd, const QkvEpilogue &e, hipStream_t s) {
-  PRISM_REQUIRE(Xn && Wqkv && M >= 0 && is16(dtype) && e.pos && e.vt_col && e.rope_tab && e.QK && e.Vt, PRISM_EINVAL,
+  PRISM_REQUIRE(Xn && Wqkv && M >= 0 && is16(dtype) && e.pos && e.vt_col && e.rope_tab_t && e.rope_stride > 0 && e.QK && e.Vt, PRISM_EINVAL,
                 "qkv gemm: bad arguments");
   PRISM_REQUIRE(!e.qk_norm || (e.q_gain && e.k_gain), PRISM_EINVAL, "qkv gemm: gains missing");
   PRISM_REQUIRE(gemm_16_qkv_supported(M, e.nq, e.nkv, hd, K), PRISM_EUNSUPPORTED, "qkv gemm: shape not supported by the fused epilogue");

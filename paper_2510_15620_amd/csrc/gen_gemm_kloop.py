@@ -86,7 +86,9 @@ def slice_body(mn, cur, b_off):
     free and the A half of slice t+2 is requested into it."""
     nxt = 1 - cur
     out = []
-    order = [(i, j) for i in range(4) for j in range(4)]
+    # boustrophedon over the 4 x 4 accumulator tiles: consecutive matrix instructions differ in ONE operand fragment, also
+    # where a row of tiles ends (fewer operand-bus toggles for the same arithmetic; the part runs at its power limit)
+    order = [(i, j if i % 2 == 0 else 3 - j) for i in range(4) for j in range(4)]
     for k in range(4):
         fs = k & 1
         behind_odd = reads(1 - fs, k + 1, cur, b_off) if k < 3 else []          # behind MFMAs 1,3,..,15

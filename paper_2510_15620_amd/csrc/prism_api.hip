@@ -107,11 +107,11 @@ struct prism_ctx {
   hipEvent_t ev_t[4] = {nullptr, nullptr, nullptr, nullptr};
   std::vector<hipEvent_t> ev_layer;               // 2 per layer, for the report
   // per-launch spans for the report: events come from a pool that only grows
-  struct Span { int kind; hipEvent_t a, b; double flops; };
+  struct Span { int kind; hipEvent_t a, b; double flops; int rows; };
   std::vector<hipEvent_t> ev_pool; size_t ev_used = 0;
   std::vector<Span> spans;
   bool profiling = false;
-  float2 *rope_tab = nullptr;
+  float2 *rope_tab = nullptr, *rope_tab_t = nullptr;   // [pos][i] for the stand-alone finishing kernel, [i][pos] for the fused epilogue
 
   // scratch, grown on demand
   float *X[2] = {nullptr, nullptr};
@@ -362,6 +362,8 @@ extern "C" int prism_create(const prism_model *model, const prism_weights *weigh
   }
   CREATE_TRY(dev_alloc(c, (void **)&c->rope_tab, (size_t)PRISM_MAX_SEQ * (model->head_dim / 2) * sizeof(float2)));
   CREATE_TRY(launch_rope_table(c->rope_tab, PRISM_MAX_SEQ, model->head_dim, model->rope_base, c->stream));
+  CREATE_TRY(dev_alloc(c, (void **)&c->rope_tab_t, (size_t)PRISM_MAX_SEQ * (model->head_dim / 2) * sizeof(float2)));
+  CREATE_TRY(launch_rope_table(c->rope_tab_t, PRISM_MAX_SEQ, model->head_dim, model->rope_base, c->stream, true));
   CREATE_TRY(dev_alloc(c, (void **)&c->d_scores, PRISM_MAX_CANDS * sizeof(float)));
   CREATE_TRY(dev_alloc(c, (void **)&c->d_fate, PRISM_MAX_CANDS));
   CREATE_TRY(dev_alloc(c, (void **)&c->d_stats, 4 * sizeof(double)));
@@ -412,7 +414,7 @@ extern "C" void prism_destroy(prism_ctx *c) {
     for (hipEvent_t e : {c->ev_in[i], c->ev_done[i], c->ev_out[i]}) if (e) (void)hipEventDestroy(e);
   if (c->xin_stream) (void)hipStreamDestroy(c->xin_stream);
   if (c->xout_stream) (void)hipStreamDestroy(c->xout_stream);
-  void *ptrs[] = {c->AOl, c->Xnl, c->Sl, c->Xl, c->rope_tab, c->X[0], c->X[1], c->Xn, c->QKV, c->QK, c->Vt, c->AO, c->S, c->d_meta, c->d_scores, c->d_fate,
+  void *ptrs[] = {c->AOl, c->Xnl, c->Sl, c->Xl, c->rope_tab, c->rope_tab_t, c->X[0], c->X[1], c->Xn, c->QKV, c->QK, c->Vt, c->AO, c->S, c->d_meta, c->d_scores, c->d_fate,
                   c->d_stats, c->route_ws, c->d_top_pos, c->d_top_scores};
   for (void *p : ptrs) if (p) (void)hipFree(p);
   if (c->h_meta) (void)hipHostFree(c->h_meta);
@@ -630,9 +632,9 @@ static int span_event(prism_ctx *c, hipEvent_t *e) {
 
 // Times the launches issued by `body` as one span of the given kind (only when a report was asked for).
 template <typename Fn>
-static int timed_span(prism_ctx *c, int kind, double flops, Fn body) {
+static int timed_span(prism_ctx *c, int kind, double flops, Fn body, int rows = 0) {
   if (!c->profiling) return body();
-  prism_ctx::Span sp{kind, nullptr, nullptr, flops};
+  prism_ctx::Span sp{kind, nullptr, nullptr, flops, rows};
   PRISM_TRY(span_event(c, &sp.a));
   PRISM_TRY(body());
   PRISM_TRY(span_event(c, &sp.b));
@@ -800,12 +802,12 @@ static int run_layer(prism_ctx *c, const Plan &p, const MetaOff &mo, float *X, c
         QkvEpilogue e;
         e.pos = pos; e.vt_col = c->d_meta + mo.vtcol + ch.r0;
         e.q_gain = wbuf + L.q_norm; e.k_gain = wbuf + L.k_norm;
-        e.rope_tab = c->rope_tab; e.QK = c->QK; e.Vt = c->Vt; e.vt_stride = c->vt_cap;
+        e.rope_tab_t = c->rope_tab_t; e.rope_stride = PRISM_MAX_SEQ; e.QK = c->QK; e.Vt = c->Vt; e.vt_stride = c->vt_cap;
         e.nq = m.n_q_heads; e.nkv = m.n_kv_heads; e.qk_norm = m.qk_norm; e.eps = m.rms_eps;
         return launch_gemm_16_qkv(c->op, c->Xn, wbuf + L.wqkv, Tc, H, m.head_dim, e, s);
       }
       return gemm(bf ? PRISM_EPI_STORE_F32 : PRISM_EPI_STORE, c->Xn, wbuf + L.wqkv, c->QKV, Tc, Dq + 2 * Dkv, H);
-    }));
+    }, Tc));
     if (!fused_qkv) PRISM_TRY(timed_span(c, 5, 0.0, [&] {
       PRISM_TRY(launch_qk_finish(c->op, (float *)c->QKV, pos, wbuf + L.q_norm, wbuf + L.k_norm, Tc, m.n_q_heads,
                                  m.n_kv_heads, m.head_dim, m.rms_eps, m.qk_norm, c->rope_tab, c->QK, s));
@@ -849,12 +851,12 @@ static int run_layer(prism_ctx *c, const Plan &p, const MetaOff &mo, float *X, c
         return launch_attention_16(c->op, c->QK, c->Vt, c->vt_cap, (const AttnTile *)(c->d_meta + mo.tiles) + ch.tile0,
                                    ch.n_tiles, Tc, m.n_q_heads, m.n_kv_heads, m.head_dim, c->AO, s);
       return launch_attention_fp32((const float *)c->QKV, pos, Tc, m.n_q_heads, m.n_kv_heads, m.head_dim, (float *)c->AO, s);
-    }));
-    PRISM_TRY(timed_span(c, 1, tk * H * Dq, [&] { return gemm(PRISM_EPI_RESIDUAL, c->AO, wbuf + L.wo, Xc, Tc, H, Dq); }));
+    }, Tc));
+    PRISM_TRY(timed_span(c, 1, tk * H * Dq, [&] { return gemm(PRISM_EPI_RESIDUAL, c->AO, wbuf + L.wo, Xc, Tc, H, Dq); }, Tc));
     // ---- FFN block: X += (silu(Xn Wg^T) * (Xn Wu^T)) Wd^T
     PRISM_TRY(timed_span(c, 5, 0.0, [&] { return launch_rmsnorm(Xc, wbuf + L.ffn_norm, Tc, H, m.rms_eps, c->op, c->Xn, s); }));
-    PRISM_TRY(timed_span(c, 2, tk * 2 * F * H, [&] { return gemm(PRISM_EPI_SWIGLU, c->Xn, wbuf + L.wgu, c->S, Tc, 2 * F, H); }));
-    PRISM_TRY(timed_span(c, 3, tk * H * F, [&] { return gemm(PRISM_EPI_RESIDUAL, c->S, wbuf + L.wd, Xc, Tc, H, F); }));
+    PRISM_TRY(timed_span(c, 2, tk * 2 * F * H, [&] { return gemm(PRISM_EPI_SWIGLU, c->Xn, wbuf + L.wgu, c->S, Tc, 2 * F, H); }, Tc));
+    PRISM_TRY(timed_span(c, 3, tk * H * F, [&] { return gemm(PRISM_EPI_RESIDUAL, c->S, wbuf + L.wd, Xc, Tc, H, F); }, Tc));
     }
     if (c->offload) {
       if (score_after && !last_only)   // last_row holds rows of the packed pool; this chunk's rows start at ch.r0
@@ -870,9 +872,30 @@ static int run_layer(prism_ctx *c, const Plan &p, const MetaOff &mo, float *X, c
 
 }  // namespace prism
 
+static int select_impl(prism_ctx *c, const int32_t *query_tokens, int32_t query_len,
+                       const int32_t *const *cand_tokens, const int32_t *cand_lens, int32_t n_cands, int32_t K,
+                       int32_t *out_idx, float *out_scores, int32_t *out_count, prism_report *rep);
+
 extern "C" int prism_select(prism_ctx *c, const int32_t *query_tokens, int32_t query_len,
                             const int32_t *const *cand_tokens, const int32_t *cand_lens, int32_t n_cands, int32_t K,
                             int32_t *out_idx, float *out_scores, int32_t *out_count, prism_report *rep) {
+  const int rc = select_impl(c, query_tokens, query_len, cand_tokens, cand_lens, n_cands, K, out_idx, out_scores, out_count, rep);
+  if (rc != PRISM_OK && c) {
+    // A call that failed midway leaves work queued on the library's streams and a half-filled report: drain the
+    // streams (errors here are secondary to rc), restart the offload pipeline from a clean state, and hand back an
+    // empty report.  out_idx / out_scores / out_count are only written by a call that succeeds.
+    for (hipStream_t st : {c->stream, c->copy_stream, c->xin_stream, c->xout_stream})
+      if (st && hipStreamSynchronize(st) != hipSuccess) (void)hipGetLastError();
+    c->primed = false;
+    c->profiling = false;
+    if (rep) rep->n_events = 0;
+  }
+  return rc;
+}
+
+static int select_impl(prism_ctx *c, const int32_t *query_tokens, int32_t query_len,
+                       const int32_t *const *cand_tokens, const int32_t *cand_lens, int32_t n_cands, int32_t K,
+                       int32_t *out_idx, float *out_scores, int32_t *out_count, prism_report *rep) {
   PRISM_REQUIRE(c && query_tokens && cand_tokens && cand_lens && out_idx && out_scores && out_count, PRISM_EINVAL,
                 "prism_select: null argument");
   PRISM_REQUIRE(query_len > 0 && n_cands > 0 && K > 0, PRISM_EINVAL, "prism_select: query_len, n_cands and K must be positive");
@@ -1139,11 +1162,17 @@ extern "C" int prism_select(prism_ctx *c, const int32_t *query_tokens, int32_t q
     rep->embed_rows_hit = c->embed_hit;
     rep->embed_rows_missed = c->embed_miss;
     for (int k = 0; k < PRISM_N_KINDS; ++k) { rep->kind_launches[k] = 0; rep->kind_ms[k] = 0.0; rep->kind_flops[k] = 0.0; }
+    const bool detail = rep->span_cap > 0 && rep->span_kind && rep->span_rows && rep->span_ms && rep->span_flops;
+    rep->n_spans = 0;
     for (const prism_ctx::Span &sp : c->spans) {
       PRISM_HIP(hipEventElapsedTime(&ms, sp.a, sp.b));
       rep->kind_launches[sp.kind] += 1;
       rep->kind_ms[sp.kind] += ms;
       rep->kind_flops[sp.kind] += sp.flops;
+      if (detail && rep->n_spans < rep->span_cap) {
+        const int i = rep->n_spans++;
+        rep->span_kind[i] = sp.kind; rep->span_rows[i] = sp.rows; rep->span_ms[i] = ms; rep->span_flops[i] = sp.flops;
+      }
     }
   }
   return PRISM_OK;
@@ -1209,9 +1238,9 @@ extern "C" int prism_op_qkv_project(int32_t dtype, const void *Xn, const void *W
   hipStream_t s = (hipStream_t)stream;
   TmpDev tab;
   PRISM_TRY(tab.alloc((size_t)max_pos * (head_dim / 2) * sizeof(float2)));
-  PRISM_TRY(launch_rope_table((float2 *)tab.p, max_pos, head_dim, rope_base, s));
+  PRISM_TRY(launch_rope_table((float2 *)tab.p, max_pos, head_dim, rope_base, s, true));
   QkvEpilogue e;
-  e.pos = pos; e.vt_col = vt_col; e.q_gain = q_gain; e.k_gain = k_gain; e.rope_tab = (const float2 *)tab.p;
+  e.pos = pos; e.vt_col = vt_col; e.q_gain = q_gain; e.k_gain = k_gain; e.rope_tab_t = (const float2 *)tab.p; e.rope_stride = max_pos;
   e.QK = QK; e.Vt = Vt; e.vt_stride = vt_stride; e.nq = n_q_heads; e.nkv = n_kv_heads; e.qk_norm = qk_norm; e.eps = eps;
   PRISM_TRY(launch_gemm_16_qkv(dtype, Xn, Wqkv, T, hidden, head_dim, e, s));
   PRISM_HIP(hipStreamSynchronize(s));   // the table is freed on return
