@@ -28,7 +28,6 @@ namespace prism {
 
 static constexpr int HD = 128;           // head_dim served by this kernel
 static constexpr int BKV = 64;           // keys per staged tile
-static constexpr float kLazy = 8.0f;     // doublings the running maximum may gain before the exponentials are re-referenced
 
 template <typename OT, int G>
 __global__ __launch_bounds__(512) void attention_16_kernel(const OT *__restrict__ QK, const f16 *__restrict__ Vt,
@@ -148,14 +147,10 @@ __global__ __launch_bounds__(512) void attention_16_kernel(const OT *__restrict_
           }
           mx = fmaxf(mx, s[kb][e]);
         }
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c_exp;              // in the exponent's units (powers of two)
-      // The reference point of the exponentials follows the running maximum only when that has moved by more than kLazy
-      // doublings.  Any reference point gives the same quotient sum(p v) / sum(p); p stays below 2^kLazy, far inside the
-      // range of half and of the fp32 sums; and the output accumulators are rescaled on a sequence's first tiles only
-      // instead of whenever one of the wave's 32 rows sees a new maximum, which is nearly every tile.
-      const float m_new = mx > m_run + kLazy ? mx : m_run;
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-      const float mb = m_new;
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c_exp);
+      const float mb = m_new * c_exp;
       float psum = 0.f;
       f16x8 pf[4];                                    // P^T as B operands: 4 contraction steps of 16 keys
       typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
@@ -165,7 +160,7 @@ __global__ __launch_bounds__(512) void attention_16_kernel(const OT *__restrict_
 #pragma unroll
         for (int e = 0; e < 16; e += 2) {
           f16x2 ph;
-          ph[0] = (f16)__builtin_amdgcn_exp2f(s[kb][e] * c_exp - mb);       // p < 2^kLazy: no overflow
+          ph[0] = (f16)__builtin_amdgcn_exp2f(s[kb][e] * c_exp - mb);       // p <= 1: no overflow
           ph[1] = (f16)__builtin_amdgcn_exp2f(s[kb][e + 1] * c_exp - mb);
           // the denominator sums the ROUNDED weights the numerator uses (one dot-product instruction per pair): the output
           // stays an exactly normalised average of V rows and the rounding of p cancels to first order
