@@ -27,6 +27,7 @@
 
 namespace prism {
 
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4_t;
 static constexpr int BK = 64;            // K-slice per stage (elements)
 static constexpr int kChunks = BK / 8;   // 16-byte chunks per tile row
 
@@ -155,7 +156,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_16_kernel(const OT *__restri
 #pragma unroll
       for (int rr = 0; rr < NI; ++rr) {
         const int row = m0 + wm * WMT + i * 32 + rr * NR + f_row;
-        old[i & 1][rr] = *reinterpret_cast<const f32x4 *>(xo + (int64_t)(row < M ? row : M - 1) * N);
+        old[i & 1][rr] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(xo + (int64_t)(row < M ? row : M - 1) * N));
       }
     }
   };
@@ -215,7 +216,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_16_kernel(const OT *__restri
     for (int rr = 0; rr < NI; ++rr) {
       const int row = row0 + rr * NR + f_row;
       const uint4 v = staged(rr);
-      if (row < M) *reinterpret_cast<uint4 *>(dst + (int64_t)row * pitch + col_byte0 + f_chunk * 16) = v;
+      if (row < M) __builtin_nontemporal_store(__builtin_bit_cast(u32x4_t, v), reinterpret_cast<u32x4_t *>(dst + (int64_t)row * pitch + col_byte0 + f_chunk * 16));
     }
   };
 
@@ -365,7 +366,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_16_kernel(const OT *__restri
           const uint4 u = staged(rr);
           f32x4 v = old[i & 1][rr];
           v[0] += __uint_as_float(u.x); v[1] += __uint_as_float(u.y); v[2] += __uint_as_float(u.z); v[3] += __uint_as_float(u.w);
-          if (row < M) *reinterpret_cast<f32x4 *>(xo + (int64_t)row * N) = v;
+          if (row < M) __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(xo + (int64_t)row * N));
         }
       } else {
 #pragma unroll
