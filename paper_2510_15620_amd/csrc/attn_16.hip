@@ -1,8 +1,8 @@
 // Causal GQA attention on the gfx950 matrix cores (16-bit operands), varlen-packed: no token attends across
 // sequences (paper Sec. 2.2) and the work list is rebuilt whenever pruning shrinks the batch.
 //
-// A work item is (one sequence, one block of queries, one KV head).  The workgroup has 8
-// wavefronts; wavefront w serves query head kvh*G + w % G (G = query heads per KV head) and the
+// A work item is (one sequence, one block of queries, one KV head).  The workgroup has NW = 4
+// wavefronts (8 when G = 8); wavefront w serves query head kvh*G + w % G (G = query heads per KV head) and the
 // 32-query block w / G of the item, so one K/V tile staged in LDS is shared by all G heads.
 //
 // Everything is computed transposed so that a lane owns ONE query:
@@ -12,14 +12,15 @@
 // The 32x32 accumulator layout gives lane l the column l % 32 and rows (e/4)*8 + (l/32)*4 + e%4;
 // those rows, read as the 16 contraction slots of the next MFMA, are keys {0-3, 8-11} for the low
 // half-wave and {4-7, 12-15} for the high one.  The V^T tile is stored in LDS with the keys of every group of
-// 16 in exactly that order (0-3, 8-11, 4-7, 12-15), so a lane's operand is ONE 16-byte chunk, and the chunks
-// are XOR-swizzled by bits 1..3 of the row, which spreads the 16 lanes served per cycle over all 64 banks.
+// 16 in exactly that order (0-3, 8-11, 4-7, 12-15), so a lane's operand is ONE 16-byte chunk; rows are padded by 16
+// bytes, which spreads the 16 lanes served per cycle over all 64 banks.
 // Online softmax needs one cross-lane exchange (l <-> l ^ 32) per K/V tile.
 // q and k come from the finished [T, (nq + nkv) * hd] buffer in the operand type OT (bf16 or IEEE half).
 // V^T comes from the [kv head][d][column] buffer of the V finishing step, always IEEE half: the
 // second contraction runs on the f16 MFMA in both modes so that the probabilities keep 11
 // significand bits.  A sequence's columns
 // start at a multiple of 64 so every 16-byte chunk is aligned.
+#include <mutex>
 #include <type_traits>
 
 #include "common.h"
@@ -28,20 +29,30 @@ namespace prism {
 
 static constexpr int HD = 128;           // head_dim served by this kernel
 static constexpr int BKV = 64;           // keys per staged tile
+// LDS rows carry 16 bytes of padding: 16 lanes that read the same chunk of 16 consecutive rows then start 4 banks apart
+// (K rows: 272 bytes = 68 banks; V^T rows: 144 bytes = 36 banks, 16 multiples of which are distinct multiples of 4 mod 64),
+// so the 16-byte reads are conflict-free and a lane's addresses differ by compile-time constants only
+static constexpr int KP = HD + 8, VP = BKV + 8;
+static constexpr size_t kAttnLds = 2 * (size_t)(BKV * KP + HD * VP) * 2;
 
-template <typename OT, int G>
-__global__ __launch_bounds__(512) void attention_16_kernel(const OT *__restrict__ QK, const f16 *__restrict__ Vt,
+template <typename OT, int G, int NW>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attention_16_kernel(const OT *__restrict__ QK, const f16 *__restrict__ Vt,
                                                            int64_t vt_stride, const AttnTile *__restrict__ tiles,
                                                            int nq, int nkv, OT *__restrict__ out) {
   typedef typename Mfma<OT>::vec8 vec8;
   typedef typename Mfma<OT>::vec4 vec4;
-  constexpr int QB = 8 / G;              // 32-query blocks per item
+  constexpr int QB = NW / G;             // 32-query blocks per item
+  constexpr int NT = NW * 64;            // threads
+  constexpr int NCH = 1024 / NT;         // 16-byte chunks of K (and of V^T) a thread stages per tile
   constexpr int BQ = 32 * QB;
-  __shared__ __align__(16) OT lK[2][BKV * HD];       // [key][d], 16 chunks per row, swizzled
-  __shared__ __align__(16) f16 lV[2][HD * BKV];      // [d][key, permuted within groups of 16], 8 chunks per row, swizzled
+  extern __shared__ __align__(16) unsigned char smem[];
+  OT (*lK)[BKV * KP] = reinterpret_cast<OT (*)[BKV * KP]>(smem);                             // [2][key][d + pad]
+  f16 (*lV)[HD * VP] = reinterpret_cast<f16 (*)[HD * VP]>(smem + 2 * BKV * KP * sizeof(OT));  // [2][d][key, permuted + pad]
 
-  const AttnTile it = tiles[blockIdx.x];
-  const int kvh = blockIdx.y;
+  // consecutive workgroup ids go to consecutive XCDs: with the KV head in the low digits of the id, all query blocks
+  // of one (sequence, KV head) run on one XCD when nkv is a multiple of 8, one after the other, so its L2 holds their K/V
+  const int kvh = blockIdx.x % nkv;
+  const AttnTile it = tiles[blockIdx.x / nkv];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int hq = kvh * G + wave % G, qb = wave / G;
   const int row_elems = (nq + nkv) * HD;
@@ -60,40 +71,33 @@ __global__ __launch_bounds__(512) void attention_16_kernel(const OT *__restrict_
     for (int kk = 0; kk < HD / 16; ++kk) qf[kk] = *reinterpret_cast<const vec8 *>(qp + kk * 16);
   }
 
-  // ---- staging addresses: 1024 chunks of K and 1024 of V^T per tile, 2 + 2 per thread
-  const OT *gK[2];
-  const f16 *gV[2];
-  int sK[2], sV[2], krow[2];
+  // ---- staging: 1024 chunks of K and 1024 of V^T per tile, NCH + NCH per thread.  Thread t takes chunk t % 16 of key rows
+  // t / 16 + i * (NT / 16) and chunk t % 8 of d rows t / 8 + i * (NT / 8): the row steps are multiples of 16, which the
+  // swizzles do not see, so one LDS address per operand serves all i with constant offsets
+  const int kr0 = tid / 16, kc = tid % 16, vr0 = tid / 8, vc = tid % 8;
+  const OT *const gK = QK + (int64_t)(nq + kvh) * HD + kc * 8;                    // + (seq_row0 + key) * row_elems
+  const f16 *const gV = Vt + ((int64_t)kvh * HD + vr0) * vt_stride + it.vt_col0 + vc * 8;
+  const int sK = kr0 * KP + kc * 8;
+  // keys 0-3 of the 8 go to chunk 2*(vc/2), keys 4-7 to chunk 2*(vc/2)+1, both at half vc % 2
+  const int sV = vr0 * VP + (vc & ~1) * 8 + (vc & 1) * 4;
+  auto load_tile = [&](int kt, vec8 (&rk)[NCH], f16x8 (&rv)[NCH]) {
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int c = tid + i * 512;
-    const int kr = c / 16, kc = c % 16;                            // K: key row, chunk
-    krow[i] = kr;
-    gK[i] = QK + (int64_t)(nq + kvh) * HD + kc * 8;               // + (seq_row0 + key) * row_elems later
-    sK[i] = kr * HD + ((kc ^ (kr & 15)) * 8);
-    const int vr = c / 8, vc = c % 8;                              // V^T: d row, 8 consecutive keys
-    gV[i] = Vt + ((int64_t)kvh * HD + vr) * vt_stride + it.vt_col0 + vc * 8;
-    // keys 0-3 of the 8 go to chunk 2*(vc/2), keys 4-7 to chunk 2*(vc/2)+1, both at half vc % 2
-    sV[i] = vr * BKV + ((((vc & ~1)) ^ ((vr >> 1) & 7)) * 8) + (vc & 1) * 4;
-  }
-  auto load_tile = [&](int kt, vec8 (&rk)[2], f16x8 (&rv)[2]) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      int key = kt * BKV + krow[i];
+    for (int i = 0; i < NCH; ++i) {
+      int key = kt * BKV + kr0 + i * (NT / 16);
       key = key < L ? key : L - 1;
-      rk[i] = *reinterpret_cast<const vec8 *>(gK[i] + (int64_t)(it.seq_row0 + key) * row_elems);
-      rv[i] = *reinterpret_cast<const f16x8 *>(gV[i] + kt * BKV);
+      rk[i] = *reinterpret_cast<const vec8 *>(gK + (int64_t)(it.seq_row0 + key) * row_elems);
+      rv[i] = *reinterpret_cast<const f16x8 *>(gV + (int64_t)(i * (NT / 8)) * vt_stride + kt * BKV);
     }
   };
-  auto store_tile = [&](int buf, const vec8 (&rk)[2], const f16x8 (&rv)[2]) {
+  auto store_tile = [&](int buf, const vec8 (&rk)[NCH], const f16x8 (&rv)[NCH]) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      *reinterpret_cast<vec8 *>(&lK[buf][sK[i]]) = rk[i];
+    for (int i = 0; i < NCH; ++i) {
+      *reinterpret_cast<vec8 *>(&lK[buf][sK + i * (NT / 16) * KP]) = rk[i];
       f16x4 lo4, hi4;
       lo4[0] = rv[i][0]; lo4[1] = rv[i][1]; lo4[2] = rv[i][2]; lo4[3] = rv[i][3];
       hi4[0] = rv[i][4]; hi4[1] = rv[i][5]; hi4[2] = rv[i][6]; hi4[3] = rv[i][7];
-      *reinterpret_cast<f16x4 *>(&lV[buf][sV[i]]) = lo4;
-      *reinterpret_cast<f16x4 *>(&lV[buf][sV[i] ^ 8]) = hi4;          // the neighbouring chunk (chunk index ^ 1)
+      *reinterpret_cast<f16x4 *>(&lV[buf][sV + i * (NT / 8) * VP]) = lo4;
+      *reinterpret_cast<f16x4 *>(&lV[buf][sV + 8 + i * (NT / 8) * VP]) = hi4;          // the next chunk
     }
   };
 
@@ -105,13 +109,16 @@ __global__ __launch_bounds__(512) void attention_16_kernel(const OT *__restrict_
   float m_run = -INFINITY, l_run = 0.f;
   const float c_exp = 1.4426950408889634f / sqrtf((float)HD);      // log2(e) / sqrt(hd)
 
-  vec8 rk[2];
-  f16x8 rv[2];
+  vec8 rk[NCH];
+  f16x8 rv[NCH];
   load_tile(0, rk, rv);
   store_tile(0, rk, rv);
   __syncthreads();
 
   const int q_hi_wave = q_lo + 31;
+  // a lane reads row lane % 32 of a 32-row block and the 16-byte chunk lane / 32 of each pair: one address per operand,
+  // everything else is a constant offset
+  const int rdK = (lane & 31) * KP + (lane >> 5) * 8, rdV = (lane & 31) * VP + (lane >> 5) * 8;
   for (int kt = 0; kt < n_kt; ++kt) {
     const int cur = kt & 1;
     const bool more = kt + 1 < n_kt;
@@ -127,11 +134,9 @@ __global__ __launch_bounds__(512) void attention_16_kernel(const OT *__restrict_
       for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) s[kb][e] = 0.f;
-        const int r = kb * 32 + (lane & 31);
 #pragma unroll
         for (int kk = 0; kk < HD / 16; ++kk) {
-          const int ch = kk * 2 + (lane >> 5);
-          const vec8 kf = *reinterpret_cast<const vec8 *>(&lK[cur][r * HD + ((ch ^ (r & 15)) * 8)]);
+          const vec8 kf = *reinterpret_cast<const vec8 *>(&lK[cur][rdK + kb * 32 * KP + kk * 16]);
           s[kb] = Mfma<OT>::mma(kf, qf[kk], s[kb]);
         }
       }
@@ -183,12 +188,10 @@ __global__ __launch_bounds__(512) void attention_16_kernel(const OT *__restrict_
       // ---- O^T += V^T P^T
 #pragma unroll
       for (int t = 0; t < HD / 32; ++t) {
-        const int r = t * 32 + (lane & 31);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
           // contraction slots 0-3 <- keys ks*16 + (lane/32)*4 .. +4 ; slots 4-7 <- the same + 8: chunk 2 ks + lane/32
-          const int ch = ks * 2 + (lane >> 5);
-          const f16x8 vf = *reinterpret_cast<const f16x8 *>(&lV[cur][r * BKV + ((ch ^ ((r >> 1) & 7)) * 8)]);
+          const f16x8 vf = *reinterpret_cast<const f16x8 *>(&lV[cur][rdV + t * 32 * VP + ks * 16]);
           o[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf[ks], o[t], 0, 0, 0);
         }
       }
@@ -224,14 +227,37 @@ bool attention_16_supported(int nq, int nkv, int hd) {
   return g == 1 || g == 2 || g == 4 || g == 8;
 }
 
+// Waves per workgroup: 4 wherever the head grouping allows it, so that two workgroups share a compute unit (64 KiB of
+// LDS and two waves per SIMD each) and one's matrix work overlaps the other's softmax and its start-up and drain.
+static int waves_per_group(int g) { return g <= 4 ? 4 : 8; }
+
+int attention_16_block_queries(int nq, int nkv) {
+  const int g = nq / nkv;
+  return 32 * (waves_per_group(g) / g);
+}
+
+template <typename OT, int G, int NW>
+static hipError_t launch_one(int n_groups, const OT *QK, const f16 *Vt, int64_t vt_stride, const AttnTile *tiles, int nq, int nkv,
+                             OT *out, hipStream_t s) {
+  auto kern = attention_16_kernel<OT, G, NW>;
+  static std::once_flag attr_once;                   // more than 64 KiB of LDS needs the per-function attribute
+  static hipError_t attr_rc = hipSuccess;
+  std::call_once(attr_once, [&] {
+    attr_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAttnLds);
+  });
+  if (attr_rc != hipSuccess) return attr_rc;
+  kern<<<n_groups, NW * 64, kAttnLds, s>>>(QK, Vt, vt_stride, tiles, nq, nkv, out);
+  return hipGetLastError();
+}
+
 template <typename OT>
-static void launch_typed(dim3 grid, int g, const OT *QK, const f16 *Vt, int64_t vt_stride, const AttnTile *tiles, int nq,
-                         int nkv, OT *out, hipStream_t s) {
+static hipError_t launch_typed(int n_groups, int g, const OT *QK, const f16 *Vt, int64_t vt_stride, const AttnTile *tiles, int nq,
+                               int nkv, OT *out, hipStream_t s) {
   switch (g) {
-    case 1: attention_16_kernel<OT, 1><<<grid, 512, 0, s>>>(QK, Vt, vt_stride, tiles, nq, nkv, out); break;
-    case 2: attention_16_kernel<OT, 2><<<grid, 512, 0, s>>>(QK, Vt, vt_stride, tiles, nq, nkv, out); break;
-    case 4: attention_16_kernel<OT, 4><<<grid, 512, 0, s>>>(QK, Vt, vt_stride, tiles, nq, nkv, out); break;
-    default: attention_16_kernel<OT, 8><<<grid, 512, 0, s>>>(QK, Vt, vt_stride, tiles, nq, nkv, out); break;
+    case 1: return launch_one<OT, 1, 4>(n_groups, QK, Vt, vt_stride, tiles, nq, nkv, out, s);
+    case 2: return launch_one<OT, 2, 4>(n_groups, QK, Vt, vt_stride, tiles, nq, nkv, out, s);
+    case 4: return launch_one<OT, 4, 4>(n_groups, QK, Vt, vt_stride, tiles, nq, nkv, out, s);
+    default: return launch_one<OT, 8, 8>(n_groups, QK, Vt, vt_stride, tiles, nq, nkv, out, s);
   }
 }
 
@@ -241,13 +267,13 @@ int launch_attention_16(int dtype, const void *QK, const void *Vt, int64_t vt_st
   PRISM_REQUIRE(attention_16_supported(nq, nkv, hd), PRISM_EUNSUPPORTED,
                 "attention: 16-bit modes need head_dim 128 and 1, 2, 4 or 8 query heads per KV head (got hd %d, %d/%d)", hd, nq, nkv);
   PRISM_REQUIRE(vt_stride % 8 == 0, PRISM_EINVAL, "attention: V^T row stride must be a multiple of 8");
+  PRISM_REQUIRE((int64_t)n_tiles * nkv < (int64_t)1 << 31, PRISM_EINVAL, "attention: too many work items (%d x %d)", n_tiles, nkv);
   if (n_tiles == 0) return PRISM_OK;
-  dim3 grid(n_tiles, nkv);
+  const int n_groups = n_tiles * nkv;
   if (dtype == PRISM_DTYPE_BF16)
-    launch_typed<bf16>(grid, nq / nkv, (const bf16 *)QK, (const f16 *)Vt, vt_stride, tiles, nq, nkv, (bf16 *)out, s);
+    PRISM_HIP(launch_typed<bf16>(n_groups, nq / nkv, (const bf16 *)QK, (const f16 *)Vt, vt_stride, tiles, nq, nkv, (bf16 *)out, s));
   else
-    launch_typed<f16>(grid, nq / nkv, (const f16 *)QK, (const f16 *)Vt, vt_stride, tiles, nq, nkv, (f16 *)out, s);
-  PRISM_HIP(hipGetLastError());
+    PRISM_HIP(launch_typed<f16>(n_groups, nq / nkv, (const f16 *)QK, (const f16 *)Vt, vt_stride, tiles, nq, nkv, (f16 *)out, s));
   return PRISM_OK;
 }
 

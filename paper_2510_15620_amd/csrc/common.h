@@ -134,6 +134,7 @@ struct AttnTile { int32_t seq_row0, seq_len, q0, vt_col0; };
 int launch_attention_16(int dtype, const void *QK, const void *Vt, int64_t vt_stride, const AttnTile *tiles, int n_tiles,
                         int T, int nq, int nkv, int hd, void *out, hipStream_t s);
 bool attention_16_supported(int nq, int nkv, int hd);
+int attention_16_block_queries(int nq, int nkv);   // queries per AttnTile for this head grouping
 static const int kAttnBQ = 64;   // query rows per attention work item
 
 int launch_score(const float *X, const int32_t *last_row, int n, int hidden, const void *final_norm,

@@ -482,7 +482,7 @@ static void build_plan(const prism_ctx *c, Plan &p) {
   p.max_chunk_tokens = p.max_vt_cols = 0;
   const int step = c->opt.chunk_cands > 0 ? c->opt.chunk_cands : std::max(n, 1);
   const bool mfma = is16(c->op);
-  const int bq = mfma ? 32 * (8 / (c->m.n_q_heads / c->m.n_kv_heads)) : 0;
+  const int bq = mfma ? attention_16_block_queries(c->m.n_q_heads, c->m.n_kv_heads) : 0;
   for (int c0 = 0; c0 < n; c0 += step) {
     Chunk ch;
     ch.c0 = c0; ch.c1 = std::min(n, c0 + step);
@@ -491,14 +491,13 @@ static void build_plan(const prism_ctx *c, Plan &p) {
     int64_t col = 0;
     if (mfma) {
       for (int i = ch.c0; i < ch.c1; ++i) {
-        for (int q0 = 0; q0 < p.len[i]; q0 += bq)
+        // a sequence's query blocks stay together (they share its K/V in one XCD's L2), the late ones, which loop
+        // over the most keys, first
+        for (int q0 = p.len[i] > 0 ? (p.len[i] - 1) / bq * bq : -1; q0 >= 0; q0 -= bq)
           p.tiles.push_back({(int32_t)(p.row0[i] - ch.r0), p.len[i], q0, (int32_t)col});
         p.last_tiles[i] = {(int32_t)(p.row0[i] - ch.r0), p.len[i], (p.len[i] - 1) / bq * bq, (int32_t)col};
         col += round_up(p.len[i], 64);
       }
-      // heavy (late) query blocks first: they loop over the most keys
-      std::stable_sort(p.tiles.begin() + ch.tile0, p.tiles.end(),
-                       [](const AttnTile &a, const AttnTile &b) { return a.q0 > b.q0; });
     }
     ch.n_tiles = (int)p.tiles.size() - ch.tile0;
     ch.vt_cols = col;
@@ -1281,12 +1280,12 @@ extern "C" int prism_op_attention(int32_t dtype, const void *QK, const void *Vt,
   PRISM_REQUIRE(attention_16_supported(nq, nkv, hd), PRISM_EUNSUPPORTED, "attention bf16: unsupported head shape");
   PRISM_REQUIRE(Vt && vt_col0 && vt_stride > 0, PRISM_EINVAL, "attention bf16: Vt / vt_col0 missing");
   std::vector<AttnTile> tiles;
-  const int bq = 32 * (8 / (nq / nkv));
+  const int bq = attention_16_block_queries(nq, nkv);
   for (int i = 0; i < n_seqs; ++i) {
     const int L = cu[i + 1] - cu[i];
     PRISM_REQUIRE(vt_col0[i] >= 0 && vt_col0[i] % 64 == 0 && vt_col0[i] + round_up(L, 64) <= vt_stride, PRISM_EINVAL,
                   "attention bf16: sequence %d: V^T columns must start at a multiple of 64 and fit the row stride", i);
-    for (int q0 = 0; q0 < L; q0 += bq) tiles.push_back({cu[i], L, q0, vt_col0[i]});
+    for (int q0 = L > 0 ? (L - 1) / bq * bq : -1; q0 >= 0; q0 -= bq) tiles.push_back({cu[i], L, q0, vt_col0[i]});
   }
   TmpDev d_tiles;
   PRISM_TRY(d_tiles.alloc(tiles.size() * sizeof(AttnTile)));
