@@ -231,8 +231,12 @@ int prism_op_gemm(int32_t dtype, int32_t epilogue, const void *A, const void *W,
  *   BF16 / F16: q and k go to QK [T, (nq+nkv)*hd] in that type; v is rounded to that type and written
  *     transposed to Vt [nkv][hd][vt_stride], always in IEEE half format (the operand type of the P V
  *     contraction; it holds bf16 values exactly) at column vt_col[t] [device].  The caller lays the sequences out so that
- *     each starts at a multiple of 64 columns, and zero-fills Vt once (pad columns must be finite).
+ *     each starts at a multiple of 64 columns, and zero-fills Vt once (pad columns must be finite).  For
+ *     prism_op_attention, the token at position p of a sequence belongs at column
+ *     first column + prism_vt_column_of_key(p): within every group of 16 positions the order is 0-3, 8-11, 4-7, 12-15,
+ *     the order in which the matrix cores hand the attention weights to the P V contraction.
  * Synchronises the stream before returning. */
+static inline int32_t prism_vt_column_of_key(int32_t p) { return (p & ~12) | ((p & 4) << 1) | ((p & 8) >> 1); }
 int prism_op_qkv_finish(int32_t dtype, void *QKV, const int32_t *pos, int32_t max_pos, const void *q_gain,
                         const void *k_gain, int32_t T, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
                         float eps, float rope_base, int32_t qk_norm, void *QK, void *Vt, const int32_t *vt_col,
@@ -261,7 +265,8 @@ int prism_op_dequantize_w4(const void *blob, int32_t N, int32_t K, int32_t dtype
  * cu_seqlens [n_seqs+1] [host]: token offsets of the sequences; out [T, nq*hd] [device] in dtype.
  *   fp32 mode: QK = the finished QKV buffer [T, (nq+2nkv)*hd] (fp32); Vt, vt_col0 ignored.
  *   BF16 / F16: QK [T, (nq+nkv)*hd] in that type and Vt / vt_stride as written by prism_op_qkv_finish;
- *     vt_col0 [n_seqs] [host]: first Vt column of each sequence (multiples of 64).
+ *     vt_col0 [n_seqs] [host]: first Vt column of each sequence (multiples of 64); the key at position p of sequence
+ *     i is read from column vt_col0[i] + prism_vt_column_of_key(p).
  * Synchronises the stream before returning. */
 int prism_op_attention(int32_t dtype, const void *QK, const void *Vt, int64_t vt_stride,
                        const int32_t *cu_seqlens_host, const int32_t *vt_col0_host, int32_t n_seqs,

@@ -318,6 +318,12 @@ def quantize_layers_w4(layers):
     return [{k: (quantize_w4(v) if k in MATRICES else v) for k, v in l.items()} for l in layers]
 
 
+def vt_column_of_key(p):
+    """Column, relative to its sequence's first, of the key at position p in the transposed V buffer (the header's
+    prism_vt_column_of_key): bits 2 and 3 of p swapped.  Works on ints and integer arrays."""
+    return (p & ~12) | ((p & 4) << 1) | ((p & 8) >> 1)
+
+
 def op_attention(dtype, QK, Vt, vt_stride, cu_seqlens, vt_col0, nq, nkv, hd, out):
     cu, cup = _i32_array(cu_seqlens)
     c0, c0p = _i32_array(vt_col0 if vt_col0 is not None else np.zeros(len(cu) - 1))

@@ -11,16 +11,17 @@
 //                                 accumulator registers themselves, converted to f16)
 // The 32x32 accumulator layout gives lane l the column l % 32 and rows (e/4)*8 + (l/32)*4 + e%4;
 // those rows, read as the 16 contraction slots of the next MFMA, are keys {0-3, 8-11} for the low
-// half-wave and {4-7, 12-15} for the high one.  The V^T tile is stored in LDS with the keys of every group of
-// 16 in exactly that order (0-3, 8-11, 4-7, 12-15), so a lane's operand is ONE 16-byte chunk; rows are padded by 16
-// bytes, which spreads the 16 lanes served per cycle over all 64 banks.
+// half-wave and {4-7, 12-15} for the high one.  The V^T buffer in memory already holds the keys of every group of
+// 16 in exactly that order (0-3, 8-11, 4-7, 12-15: key p of a sequence sits at column p with bits 2 and 3 swapped), so
+// a lane's operand is ONE 16-byte chunk and a tile is staged as it is.  K and V^T tiles go from memory to LDS without
+// passing through registers; chunks are XOR-swizzled by the row, which spreads the 16 lanes served per cycle over all
+// 64 banks.
 // Online softmax needs one cross-lane exchange (l <-> l ^ 32) per K/V tile.
 // q and k come from the finished [T, (nq + nkv) * hd] buffer in the operand type OT (bf16 or IEEE half).
 // V^T comes from the [kv head][d][column] buffer of the V finishing step, always IEEE half: the
 // second contraction runs on the f16 MFMA in both modes so that the probabilities keep 11
 // significand bits.  A sequence's columns
 // start at a multiple of 64 so every 16-byte chunk is aligned.
-#include <mutex>
 #include <type_traits>
 
 #include "common.h"
@@ -29,11 +30,8 @@ namespace prism {
 
 static constexpr int HD = 128;           // head_dim served by this kernel
 static constexpr int BKV = 64;           // keys per staged tile
-// LDS rows carry 16 bytes of padding: 16 lanes that read the same chunk of 16 consecutive rows then start 4 banks apart
-// (K rows: 272 bytes = 68 banks; V^T rows: 144 bytes = 36 banks, 16 multiples of which are distinct multiples of 4 mod 64),
-// so the 16-byte reads are conflict-free and a lane's addresses differ by compile-time constants only
-static constexpr int KP = HD + 8, VP = BKV + 8;
-static constexpr size_t kAttnLds = 2 * (size_t)(BKV * KP + HD * VP) * 2;
+#define PRISM_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
+#define PRISM_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
 template <typename OT, int G, int NW>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attention_16_kernel(const OT *__restrict__ QK, const f16 *__restrict__ Vt,
@@ -43,11 +41,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   typedef typename Mfma<OT>::vec4 vec4;
   constexpr int QB = NW / G;             // 32-query blocks per item
   constexpr int NT = NW * 64;            // threads
-  constexpr int NCH = 1024 / NT;         // 16-byte chunks of K (and of V^T) a thread stages per tile
   constexpr int BQ = 32 * QB;
-  extern __shared__ __align__(16) unsigned char smem[];
-  OT (*lK)[BKV * KP] = reinterpret_cast<OT (*)[BKV * KP]>(smem);                             // [2][key][d + pad]
-  f16 (*lV)[HD * VP] = reinterpret_cast<f16 (*)[HD * VP]>(smem + 2 * BKV * KP * sizeof(OT));  // [2][d][key, permuted + pad]
+  // Two stages, each its own LDS object and chosen at compile time: the compiler then knows that the loads in flight
+  // towards one stage cannot alias the reads of the other and does not wait for them before those reads.
+  __shared__ __align__(16) OT lK0[BKV * HD], lK1[BKV * HD];   // [key][d]: 16 chunks of 16 bytes per row, XOR-swizzled by the row
+  __shared__ __align__(16) f16 lV0[HD * BKV], lV1[HD * BKV];  // [d][column of the tile]: 8 chunks per row, XOR-swizzled by the row
 
   // consecutive workgroup ids go to consecutive XCDs: with the KV head in the low digits of the id, all query blocks
   // of one (sequence, KV head) run on one XCD when nkv is a multiple of 8, one after the other, so its L2 holds their K/V
@@ -71,34 +69,37 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     for (int kk = 0; kk < HD / 16; ++kk) qf[kk] = *reinterpret_cast<const vec8 *>(qp + kk * 16);
   }
 
-  // ---- staging: 1024 chunks of K and 1024 of V^T per tile, NCH + NCH per thread.  Thread t takes chunk t % 16 of key rows
-  // t / 16 + i * (NT / 16) and chunk t % 8 of d rows t / 8 + i * (NT / 8): the row steps are multiples of 16, which the
-  // swizzles do not see, so one LDS address per operand serves all i with constant offsets
-  const int kr0 = tid / 16, kc = tid % 16, vr0 = tid / 8, vc = tid % 8;
-  const OT *const gK = QK + (int64_t)(nq + kvh) * HD + kc * 8;                    // + (seq_row0 + key) * row_elems
-  const f16 *const gV = Vt + ((int64_t)kvh * HD + vr0) * vt_stride + it.vt_col0 + vc * 8;
-  const int sK = kr0 * KP + kc * 8;
-  // keys 0-3 of the 8 go to chunk 2*(vc/2), keys 4-7 to chunk 2*(vc/2)+1, both at half vc % 2
-  const int sV = vr0 * VP + (vc & ~1) * 8 + (vc & 1) * 4;
-  auto load_tile = [&](int kt, vec8 (&rk)[NCH], f16x8 (&rv)[NCH]) {
+  // ---- staging without registers (global_load_lds_dwordx4): a wave instruction moves 64 chunks of 16 bytes to 1 KiB of
+  // consecutive LDS, i.e. 4 key rows of K or 8 d rows of V^T; the tile takes 16 + 16 of them, NI + NI per wave.  The
+  // swizzle is applied on the source side: LDS slot p of K row r receives chunk p ^ (r % 16), slot p of V^T row r chunk
+  // p ^ ((r / 2) % 8), so that the 16 lanes served per cycle, which read one logical chunk of 16 consecutive rows,
+  // touch all 64 banks.
+  constexpr int NI = 16 / NW;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const OT *gK[NI];                                   // + (seq_row0 + key) * row_elems
+  const f16 *gV[NI];                                  // + kt * BKV
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      int key = kt * BKV + kr0 + i * (NT / 16);
+  for (int j = 0; j < NI; ++j) {
+    const int kr = (wave * NI + j) * 4 + (lane >> 4);
+    gK[j] = QK + (int64_t)(nq + kvh) * HD + (((lane & 15) ^ (kr & 15)) * 8);
+    const int vr = (wave * NI + j) * 8 + (lane >> 3);
+    gV[j] = Vt + ((int64_t)kvh * HD + vr) * vt_stride + it.vt_col0 + (((lane & 7) ^ ((vr >> 1) & 7)) * 8);
+  }
+  auto stage_tile = [&](int kt, auto buf_tag) {
+    constexpr int BUF = decltype(buf_tag)::value;
+    OT *const lK = BUF ? lK1 : lK0;
+    f16 *const lV = BUF ? lV1 : lV0;
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+      int key = kt * BKV + (wave * NI + j) * 4 + (lane >> 4);
       key = key < L ? key : L - 1;
-      rk[i] = *reinterpret_cast<const vec8 *>(gK + (int64_t)(it.seq_row0 + key) * row_elems);
-      rv[i] = *reinterpret_cast<const f16x8 *>(gV + (int64_t)(i * (NT / 8)) * vt_stride + kt * BKV);
+      __builtin_amdgcn_global_load_lds(PRISM_GLOBAL_PTR(gK[j] + (int64_t)(it.seq_row0 + key) * row_elems),
+                                       PRISM_LDS_PTR(&lK[(wave_u * NI + j) * 4 * HD]), 16, 0, 0);
     }
-  };
-  auto store_tile = [&](int buf, const vec8 (&rk)[NCH], const f16x8 (&rv)[NCH]) {
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      *reinterpret_cast<vec8 *>(&lK[buf][sK + i * (NT / 16) * KP]) = rk[i];
-      f16x4 lo4, hi4;
-      lo4[0] = rv[i][0]; lo4[1] = rv[i][1]; lo4[2] = rv[i][2]; lo4[3] = rv[i][3];
-      hi4[0] = rv[i][4]; hi4[1] = rv[i][5]; hi4[2] = rv[i][6]; hi4[3] = rv[i][7];
-      *reinterpret_cast<f16x4 *>(&lV[buf][sV + i * (NT / 8) * VP]) = lo4;
-      *reinterpret_cast<f16x4 *>(&lV[buf][sV + 8 + i * (NT / 8) * VP]) = hi4;          // the next chunk
-    }
+    for (int j = 0; j < NI; ++j)
+      __builtin_amdgcn_global_load_lds(PRISM_GLOBAL_PTR(gV[j] + kt * BKV),
+                                       PRISM_LDS_PTR(&lV[(wave_u * NI + j) * 8 * BKV]), 16, 0, 0);
   };
 
   f32x16 o[HD / 32];
@@ -109,20 +110,20 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   float m_run = -INFINITY, l_run = 0.f;
   const float c_exp = 1.4426950408889634f / sqrtf((float)HD);      // log2(e) / sqrt(hd)
 
-  vec8 rk[NCH];
-  f16x8 rv[NCH];
-  load_tile(0, rk, rv);
-  store_tile(0, rk, rv);
-  __syncthreads();
+  stage_tile(0, std::integral_constant<int, 0>{});
+  __syncthreads();                                   // also waits for this wave's own loads (vmcnt)
 
   const int q_hi_wave = q_lo + 31;
-  // a lane reads row lane % 32 of a 32-row block and the 16-byte chunk lane / 32 of each pair: one address per operand,
-  // everything else is a constant offset
-  const int rdK = (lane & 31) * KP + (lane >> 5) * 8, rdV = (lane & 31) * VP + (lane >> 5) * 8;
-  for (int kt = 0; kt < n_kt; ++kt) {
-    const int cur = kt & 1;
-    const bool more = kt + 1 < n_kt;
-    if (more) load_tile(kt + 1, rk, rv);
+  // a lane reads row lane % 32 of a 32-row block and chunk 2 k + lane / 32 of it: slot (2 k + lane / 32) ^ swizzle(row),
+  // which is the k = 0 address with k's bits flipped
+  const int rdK = (lane & 31) * HD + (((lane >> 5) ^ (lane & 15)) * 8);
+  const int rdV = (lane & 31) * BKV + (((lane >> 5) ^ ((lane >> 1) & 7)) * 8);
+  // one tile: stage CUR holds tile kt, the other stage receives tile kt + 1 meanwhile
+  auto step = [&](int kt, auto cur_tag) {
+    constexpr int CUR = decltype(cur_tag)::value;
+    const OT *const lK = CUR ? lK1 : lK0;
+    const f16 *const lV = CUR ? lV1 : lV0;
+    if (kt + 1 < n_kt) stage_tile(kt + 1, std::integral_constant<int, CUR ^ 1>{});
 
     // One K/V tile for this wave.  MASK: the tile holds keys after some query of the wave (the causal diagonal); the
     // two variants are separate code so that tiles below the diagonal carry no masking arithmetic at all.
@@ -136,7 +137,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
         for (int e = 0; e < 16; ++e) s[kb][e] = 0.f;
 #pragma unroll
         for (int kk = 0; kk < HD / 16; ++kk) {
-          const vec8 kf = *reinterpret_cast<const vec8 *>(&lK[cur][rdK + kb * 32 * KP + kk * 16]);
+          const vec8 kf = *reinterpret_cast<const vec8 *>(&lK[(rdK ^ (kk * 16)) + kb * 32 * HD]);
           s[kb] = Mfma<OT>::mma(kf, qf[kk], s[kb]);
         }
       }
@@ -191,7 +192,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
           // contraction slots 0-3 <- keys ks*16 + (lane/32)*4 .. +4 ; slots 4-7 <- the same + 8: chunk 2 ks + lane/32
-          const f16x8 vf = *reinterpret_cast<const f16x8 *>(&lV[cur][rdV + t * 32 * VP + ks * 16]);
+          const f16x8 vf = *reinterpret_cast<const f16x8 *>(&lV[(rdV ^ (ks * 16)) + t * 32 * BKV]);
           o[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf[ks], o[t], 0, 0, 0);
         }
       }
@@ -200,8 +201,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       if (kt * BKV + BKV - 1 > q_lo) tile_step(std::true_type{});
       else tile_step(std::false_type{});
     }
-    if (more) store_tile(cur ^ 1, rk, rv);
-    __syncthreads();
+    __syncthreads();                                 // next tile landed (vmcnt) and everyone is done with this one
+  };
+  for (int kt = 0; kt < n_kt; kt += 2) {
+    step(kt, std::integral_constant<int, 0>{});
+    if (kt + 1 < n_kt) step(kt + 1, std::integral_constant<int, 1>{});
   }
 
   // ---- normalise and store: lane holds d = t*32 + (e/4)*8 + (lane/32)*4 + e%4 of query qi
@@ -239,14 +243,7 @@ int attention_16_block_queries(int nq, int nkv) {
 template <typename OT, int G, int NW>
 static hipError_t launch_one(int n_groups, const OT *QK, const f16 *Vt, int64_t vt_stride, const AttnTile *tiles, int nq, int nkv,
                              OT *out, hipStream_t s) {
-  auto kern = attention_16_kernel<OT, G, NW>;
-  static std::once_flag attr_once;                   // more than 64 KiB of LDS needs the per-function attribute
-  static hipError_t attr_rc = hipSuccess;
-  std::call_once(attr_once, [&] {
-    attr_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAttnLds);
-  });
-  if (attr_rc != hipSuccess) return attr_rc;
-  kern<<<n_groups, NW * 64, kAttnLds, s>>>(QK, Vt, vt_stride, tiles, nq, nkv, out);
+  attention_16_kernel<OT, G, NW><<<n_groups, NW * 64, 0, s>>>(QK, Vt, vt_stride, tiles, nq, nkv, out);
   return hipGetLastError();
 }
 

@@ -135,6 +135,10 @@ int launch_attention_16(int dtype, const void *QK, const void *Vt, int64_t vt_st
                         int T, int nq, int nkv, int hd, void *out, hipStream_t s);
 bool attention_16_supported(int nq, int nkv, int hd);
 int attention_16_block_queries(int nq, int nkv);   // queries per AttnTile for this head grouping
+// Column of key p of a sequence in the V^T buffer, relative to the sequence's first column: within every group of 16
+// the keys are stored in the order 0-3, 8-11, 4-7, 12-15 (the order in which the matrix cores' accumulator layout hands
+// the probabilities to the second contraction), i.e. bits 2 and 3 of p are swapped.
+inline int vt_column_of_key(int p) { return (p & ~12) | ((p & 4) << 1) | ((p & 8) >> 1); }
 static const int kAttnBQ = 64;   // query rows per attention work item
 
 int launch_score(const float *X, const int32_t *last_row, int n, int hidden, const void *final_norm,

@@ -604,7 +604,7 @@ static int upload_meta(prism_ctx *c, const Plan &p, const MetaOff &mo, bool with
     int64_t col = 0;
     for (int i = ch.c0; i < ch.c1; ++i) {
       int32_t *pos = h + mo.pos + p.row0[i], *vc = h + mo.vtcol + p.row0[i];
-      for (int t = 0; t < p.len[i]; ++t) { pos[t] = t; vc[t] = (int32_t)(col + t); }
+      for (int t = 0; t < p.len[i]; ++t) { pos[t] = t; vc[t] = (int32_t)(col + vt_column_of_key(t)); }
       col += round_up(p.len[i], 64);
     }
   }

@@ -155,9 +155,10 @@ def test_gemm_16_row_panels_beyond_4gib():
 
 
 def _vt_layout(lens):
-    """Column of every token in the transposed V buffer: sequences start at multiples of 64."""
+    """Column of every token in the transposed V buffer: sequences start at multiples of 64; within every group of 16
+    positions the columns follow the order 0-3, 8-11, 4-7, 12-15 (the header's prism_vt_column_of_key)."""
     col0 = np.concatenate([[0], np.cumsum([(l + 63) // 64 * 64 for l in lens])]).astype(np.int32)
-    vt_col = np.concatenate([col0[i] + np.arange(l) for i, l in enumerate(lens)]).astype(np.int32)
+    vt_col = np.concatenate([col0[i] + B.vt_column_of_key(np.arange(l)) for i, l in enumerate(lens)]).astype(np.int32)
     return col0[:-1], vt_col, int(col0[-1])
 
 
