@@ -35,8 +35,7 @@ int launch_embed(const int32_t *tokens, int T, const void *table, int hidden, in
 }
 
 // ------------------------------------------------------------------------------------------------
-// RMSNorm of the fp32 residual into the GEMM operand type.  One workgroup per row; the row is read
-// twice (the second read hits L2).  HBM-bound: T*H*(4 + sizeof(T)) bytes.
+// RMSNorm of the fp32 residual into the GEMM operand type.  One workgroup per row.  HBM-bound: T*H*(4 + sizeof(T)) bytes.
 __device__ __forceinline__ float block_sum_256(float v, float *red) {
   v = wave_sum(v);
   const int w = threadIdx.x >> 6;
@@ -47,37 +46,72 @@ __device__ __forceinline__ float block_sum_256(float v, float *red) {
   return t;
 }
 
-template <typename T>
+template <typename T, int NV>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const float *__restrict__ X, const T *__restrict__ gain,
                                                       int hidden, float eps, T *__restrict__ out) {
+  typedef __attribute__((ext_vector_type(4))) float f32x4_t;
   __shared__ float red[4];
   const float *x = X + (int64_t)blockIdx.x * hidden;
   T *o = out + (int64_t)blockIdx.x * hidden;
+  // NV > 0: the row (at most NV * 1024 values) stays in registers between the two passes; it is not needed again before
+  // the layer's next GEMM epilogue, so the loads bypass the caches' retention.  NV == 0: any width, the row is read twice.
+  f32x4_t keep[NV > 0 ? NV : 1];
   float ss = 0.f;
-  for (int i = threadIdx.x * 4; i < hidden; i += 1024) {
-    float4 v = *reinterpret_cast<const float4 *>(x + i);
-    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  if (NV > 0) {
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      const int i = threadIdx.x * 4 + k * 1024;
+      if (i < hidden) {
+        keep[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(x + i));
+        ss += keep[k][0] * keep[k][0] + keep[k][1] * keep[k][1] + keep[k][2] * keep[k][2] + keep[k][3] * keep[k][3];
+      }
+    }
+  } else {
+    for (int i = threadIdx.x * 4; i < hidden; i += 1024) {
+      float4 v = *reinterpret_cast<const float4 *>(x + i);
+      ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    }
   }
   ss = block_sum_256(ss, red);
   const float r = 1.0f / sqrtf(ss / (float)hidden + eps);
-  for (int i = threadIdx.x * 4; i < hidden; i += 1024) {
-    float4 v = *reinterpret_cast<const float4 *>(x + i);
-    o[i] = from_f32<T>(v.x * r * to_f32(gain[i]));
-    o[i + 1] = from_f32<T>(v.y * r * to_f32(gain[i + 1]));
-    o[i + 2] = from_f32<T>(v.z * r * to_f32(gain[i + 2]));
-    o[i + 3] = from_f32<T>(v.w * r * to_f32(gain[i + 3]));
+  auto emit = [&](int i, float a, float b, float c, float d) {
+    struct alignas(sizeof(T) * 4) Quad { T v[4]; } q, g = *reinterpret_cast<const Quad *>(gain + i);
+    q.v[0] = from_f32<T>(a * r * to_f32(g.v[0]));
+    q.v[1] = from_f32<T>(b * r * to_f32(g.v[1]));
+    q.v[2] = from_f32<T>(c * r * to_f32(g.v[2]));
+    q.v[3] = from_f32<T>(d * r * to_f32(g.v[3]));
+    *reinterpret_cast<Quad *>(o + i) = q;
+  };
+  if (NV > 0) {
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      const int i = threadIdx.x * 4 + k * 1024;
+      if (i < hidden) emit(i, keep[k][0], keep[k][1], keep[k][2], keep[k][3]);
+    }
+  } else {
+    for (int i = threadIdx.x * 4; i < hidden; i += 1024) {
+      float4 v = *reinterpret_cast<const float4 *>(x + i);
+      emit(i, v.x, v.y, v.z, v.w);
+    }
   }
+}
+
+template <typename T>
+static void launch_rmsnorm_typed(const float *X, const void *gain, int T_, int hidden, float eps, void *out, hipStream_t s) {
+  if (hidden <= 4096) rmsnorm_kernel<T, 4><<<T_, 256, 0, s>>>(X, (const T *)gain, hidden, eps, (T *)out);
+  else if (hidden <= 8192) rmsnorm_kernel<T, 8><<<T_, 256, 0, s>>>(X, (const T *)gain, hidden, eps, (T *)out);
+  else rmsnorm_kernel<T, 0><<<T_, 256, 0, s>>>(X, (const T *)gain, hidden, eps, (T *)out);
 }
 
 int launch_rmsnorm(const float *X, const void *gain, int T, int hidden, float eps, int dtype, void *out, hipStream_t s) {
   PRISM_REQUIRE(X && gain && out && T >= 0 && hidden > 0 && hidden % 4 == 0, PRISM_EINVAL, "rmsnorm: bad arguments");
+  const size_t quad = 4 * dtype_size(dtype);        // the kernel moves four values at a time
+  PRISM_REQUIRE((uintptr_t)X % 16 == 0 && (uintptr_t)gain % quad == 0 && (uintptr_t)out % quad == 0, PRISM_EINVAL,
+                "rmsnorm: X must be 16-byte aligned, gain and out %zu-byte aligned", quad);
   if (T == 0) return PRISM_OK;
-  if (dtype == PRISM_DTYPE_FP32)
-    rmsnorm_kernel<float><<<T, 256, 0, s>>>(X, (const float *)gain, hidden, eps, (float *)out);
-  else if (dtype == PRISM_DTYPE_BF16)
-    rmsnorm_kernel<bf16><<<T, 256, 0, s>>>(X, (const bf16 *)gain, hidden, eps, (bf16 *)out);
-  else
-    rmsnorm_kernel<f16><<<T, 256, 0, s>>>(X, (const f16 *)gain, hidden, eps, (f16 *)out);
+  if (dtype == PRISM_DTYPE_FP32) launch_rmsnorm_typed<float>(X, gain, T, hidden, eps, out, s);
+  else if (dtype == PRISM_DTYPE_BF16) launch_rmsnorm_typed<bf16>(X, gain, T, hidden, eps, out, s);
+  else launch_rmsnorm_typed<f16>(X, gain, T, hidden, eps, out, s);
   PRISM_HIP(hipGetLastError());
   return PRISM_OK;
 }
