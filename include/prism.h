@@ -171,6 +171,10 @@ typedef struct {
   int32_t *span_rows;           /* out */
   float   *span_ms;             /* out */
   double  *span_flops;          /* out */
+  /* in: which kinds get HIP-event spans (bit k = kind k); 0 means all.  Every span costs two event records on the
+   * compute stream (about 3 ms per call at 36 layers with all kinds on), so a caller that times the call as a whole
+   * can restrict the spans to the kinds it reads; the other kinds' totals then stay 0. */
+  int32_t  kind_mask;
 } prism_report;
 
 /* Build a context.  Device-resident layer weights are repacked once into library-owned HBM
@@ -236,7 +240,7 @@ int prism_op_gemm(int32_t dtype, int32_t epilogue, const void *A, const void *W,
  *     first column + prism_vt_column_of_key(p): within every group of 16 positions the order is 0-3, 8-11, 4-7, 12-15,
  *     the order in which the matrix cores hand the attention weights to the P V contraction.
  * Synchronises the stream before returning. */
-static inline int32_t prism_vt_column_of_key(int32_t p) { return (p & ~12) | ((p & 4) << 1) | ((p & 8) >> 1); }
+int32_t prism_vt_column_of_key(int32_t p);   /* p with bits 2 and 3 swapped; negative p is returned unchanged */
 int prism_op_qkv_finish(int32_t dtype, void *QKV, const int32_t *pos, int32_t max_pos, const void *q_gain,
                         const void *k_gain, int32_t T, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
                         float eps, float rope_base, int32_t qk_norm, void *QK, void *Vt, const int32_t *vt_col,

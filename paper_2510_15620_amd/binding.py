@@ -23,7 +23,7 @@ MAX_CANDS, MAX_CLUSTERS, MAX_SEQ = 4096, 8, 8192
 
 EXPORTS = ["prism_create", "prism_select", "prism_set_forced_keep", "prism_destroy", "prism_strerror",
            "prism_last_error", "prism_op_embed", "prism_op_rmsnorm", "prism_op_gemm", "prism_op_qkv_finish", "prism_op_qkv_project", "prism_w4_bytes", "prism_op_quantize_w4", "prism_op_dequantize_w4",
-           "prism_op_attention", "prism_op_score", "prism_op_route", "prism_op_route_static", "prism_op_compact", "prism_op_topk"]
+           "prism_op_attention", "prism_op_score", "prism_op_route", "prism_op_route_static", "prism_op_compact", "prism_op_topk", "prism_vt_column_of_key"]
 
 
 class PrismError(RuntimeError):
@@ -68,7 +68,7 @@ class prism_report(C.Structure):
                 ("kind_flops", C.c_double * 6), ("bytes_hidden_moved", C.c_int64), ("embed_rows_hit", C.c_int64),
                 ("embed_rows_missed", C.c_int64), ("span_cap", C.c_int32), ("n_spans", C.c_int32),
                 ("span_kind", C.POINTER(C.c_int32)), ("span_rows", C.POINTER(C.c_int32)), ("span_ms", C.POINTER(C.c_float)),
-                ("span_flops", C.POINTER(C.c_double))]
+                ("span_flops", C.POINTER(C.c_double)), ("kind_mask", C.c_int32)]
 
 
 _lib = None
@@ -194,8 +194,9 @@ class Prism:
         self.n_checkpoints = len(ck)
         _check(lib().prism_create(C.byref(m), C.byref(w), C.byref(o), C.byref(self._ctx)))
 
-    def select(self, query_tokens, cand_tokens: Sequence, K: int, report: bool = True, spans: int = 0):
-        """spans: capacity of the per-launch detail of the report (0 = none)."""
+    def select(self, query_tokens, cand_tokens: Sequence, K: int, report: bool = True, spans: int = 0, kinds=None):
+        """spans: capacity of the per-launch detail of the report (0 = none).  kinds: the kernel kinds that get event spans
+        (iterable of kind numbers; None = all)."""
         q, qp = _i32_array(query_tokens)
         cands = [np.ascontiguousarray(c, dtype=np.int32) for c in cand_tokens]
         n = len(cands)
@@ -223,6 +224,8 @@ class Prism:
                 rep.span_cap = spans
                 rep.span_kind, rep.span_rows = P(sp["kind"], C.c_int32), P(sp["rows"], C.c_int32)
                 rep.span_ms, rep.span_flops = P(sp["ms"], C.c_float), P(sp["flops"], C.c_double)
+            if kinds is not None:
+                rep.kind_mask = sum(1 << int(k) for k in kinds)
         _check(lib().prism_select(self._ctx, qp, len(q), cptrs, lp, n, K, out_idx.ctypes.data_as(C.POINTER(C.c_int32)),
                                   out_scores.ctypes.data_as(C.POINTER(C.c_float)), C.byref(count),
                                   C.byref(rep) if rep is not None else None))
@@ -319,9 +322,12 @@ def quantize_layers_w4(layers):
 
 
 def vt_column_of_key(p):
-    """Column, relative to its sequence's first, of the key at position p in the transposed V buffer (the header's
-    prism_vt_column_of_key): bits 2 and 3 of p swapped.  Works on ints and integer arrays."""
-    return (p & ~12) | ((p & 4) << 1) | ((p & 8) >> 1)
+    """Column, relative to its sequence's first, of the key at position p in the transposed V buffer: the library's
+    prism_vt_column_of_key applied to an int or elementwise to an integer array (its 16 values per group, tiled)."""
+    perm = np.array([lib().prism_vt_column_of_key(i) for i in range(16)], dtype=np.int64)
+    p = np.asarray(p)
+    out = (p & ~15) | perm[p & 15]
+    return int(out) if out.ndim == 0 else out.astype(p.dtype)
 
 
 def op_attention(dtype, QK, Vt, vt_stride, cu_seqlens, vt_col0, nq, nkv, hd, out):

@@ -111,6 +111,7 @@ struct prism_ctx {
   std::vector<hipEvent_t> ev_pool; size_t ev_used = 0;
   std::vector<Span> spans;
   bool profiling = false;
+  int span_mask = ~0;                             // kinds that get event spans while profiling
   float2 *rope_tab = nullptr, *rope_tab_t = nullptr;   // [pos][i] for the stand-alone finishing kernel, [i][pos] for the fused epilogue
 
   // scratch, grown on demand
@@ -632,7 +633,7 @@ static int span_event(prism_ctx *c, hipEvent_t *e) {
 // Times the launches issued by `body` as one span of the given kind (only when a report was asked for).
 template <typename Fn>
 static int timed_span(prism_ctx *c, int kind, double flops, Fn body, int rows = 0) {
-  if (!c->profiling) return body();
+  if (!c->profiling || !((c->span_mask >> kind) & 1)) return body();
   prism_ctx::Span sp{kind, nullptr, nullptr, flops, rows};
   PRISM_TRY(span_event(c, &sp.a));
   PRISM_TRY(body());
@@ -941,6 +942,7 @@ static int select_impl(prism_ctx *c, const int32_t *query_tokens, int32_t query_
   }
   const bool timed = rep != nullptr;
   c->profiling = timed;
+  c->span_mask = timed && rep->kind_mask ? rep->kind_mask : ~0;
   c->spans.clear();
   c->ev_used = 0;
   if (timed && (int)c->ev_layer.size() < 2 * m.n_layers) {
@@ -1176,6 +1178,8 @@ static int select_impl(prism_ctx *c, const int32_t *query_tokens, int32_t query_
   }
   return PRISM_OK;
 }
+
+extern "C" int32_t prism_vt_column_of_key(int32_t p) { return p < 0 ? p : vt_column_of_key(p); }
 
 // ------------------------------------------------------------------------------------------------ kernel-level entry points
 namespace prism {

@@ -38,7 +38,7 @@ def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(binding.prism_layer_weights) == 11 * 8
     assert ctypes.sizeof(binding.prism_weights) == 7 * 8
     assert ctypes.sizeof(binding.prism_options) == 8 + 4 * 6 + 8 + 8 + 4 * 4     # the fourth trailing int32 takes the padding
-    assert ctypes.sizeof(binding.prism_report) == 3 * 4 + 4 + 10 * 8 + 3 * 8 + 3 * 8 + 4 + 6 * 4 + 4 + 6 * 8 + 6 * 8 + 3 * 8 + 2 * 4 + 4 * 8
+    assert ctypes.sizeof(binding.prism_report) == 3 * 4 + 4 + 10 * 8 + 3 * 8 + 3 * 8 + 4 + 6 * 4 + 4 + 6 * 8 + 6 * 8 + 3 * 8 + 2 * 4 + 4 * 8 + 8   # kind_mask (int32) + tail padding
 
 
 def test_strerror_and_argument_errors_without_a_gpu(built):
@@ -59,3 +59,15 @@ def test_generated_gemm_loop_is_in_sync_with_its_generator():
     csrc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2510_15620_amd", "csrc")
     out = subprocess.run([sys.executable, os.path.join(csrc, "gen_gemm_kloop.py")], capture_output=True, text=True, check=True).stdout
     assert out == open(os.path.join(csrc, "gemm_16_kloop.inc")).read()
+
+
+def test_vt_column_mapping_is_the_documented_order(built):
+    """Within every group of 16 key positions the transposed-V columns hold the keys in the order 0-3, 8-11, 4-7, 12-15
+    (a host function: no GPU is touched)."""
+    built.prism_vt_column_of_key.restype = ctypes.c_int32
+    built.prism_vt_column_of_key.argtypes = [ctypes.c_int32]
+    cols = [built.prism_vt_column_of_key(p) for p in range(48)]
+    order = [0, 1, 2, 3, 8, 9, 10, 11, 4, 5, 6, 7, 12, 13, 14, 15]
+    held = [cols.index(c) for c in range(48)]                # key found at column c
+    assert held == [g * 16 + k for g in range(3) for k in order]
+    assert sorted(cols) == list(range(48)) and built.prism_vt_column_of_key(-3) == -3
