@@ -123,6 +123,12 @@ typedef struct {
   int32_t stream_slots;               /* streamed or 4-bit layers: layer buffers in the ring, 0 or 2 = the paper's double
                                          buffer (Sec. 4.2); more lets the stream run ahead while the pool is large, which
                                          pays back after pruning, when a layer computes faster than it arrives */
+  int32_t no_query_sharing;           /* 0 (default): the query's tokens, with which every (query, candidate) sequence
+                                         begins (Sec. 3.3) and whose states under the causal mask do not depend on the
+                                         candidate, are held and computed once per chunk, and every candidate's tokens
+                                         attend to those rows; results are those of the unshared computation.  Applies
+                                         to the 16-bit matrix-core path with a device-resident residual stream.
+                                         1: every sequence carries and computes its own copy of the query */
 } prism_options;
 
 /* Optional per-call record.  The caller allocates every array ([host]); an "event" is one

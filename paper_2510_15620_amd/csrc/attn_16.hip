@@ -64,7 +64,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int qi_ld = qi < L ? qi : L - 1;
   vec8 qf[HD / 16];
   {
-    const OT *qp = QK + (int64_t)(it.seq_row0 + qi_ld) * row_elems + (int64_t)hq * HD + (lane >> 5) * 8;
+    const OT *qp = QK + (int64_t)(it.row_base + qi_ld) * row_elems + (int64_t)hq * HD + (lane >> 5) * 8;   // queries are never prefix positions
 #pragma unroll
     for (int kk = 0; kk < HD / 16; ++kk) qf[kk] = *reinterpret_cast<const vec8 *>(qp + kk * 16);
   }
@@ -93,7 +93,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     for (int j = 0; j < NI; ++j) {
       int key = kt * BKV + (wave * NI + j) * 4 + (lane >> 4);
       key = key < L ? key : L - 1;
-      __builtin_amdgcn_global_load_lds(PRISM_GLOBAL_PTR(gK[j] + (int64_t)(it.seq_row0 + key) * row_elems),
+      __builtin_amdgcn_global_load_lds(PRISM_GLOBAL_PTR(gK[j] + (int64_t)((key < it.pre_len ? it.pre_row0 : it.row_base) + key) * row_elems),
                                        PRISM_LDS_PTR(&lK[(wave_u * NI + j) * 4 * HD]), 16, 0, 0);
     }
 #pragma unroll
@@ -212,7 +212,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   if (qi < L) {
     const float inv = 1.0f / l_tot;
-    OT *op = out + (int64_t)(it.seq_row0 + qi) * nq * HD + (int64_t)hq * HD + (lane >> 5) * 4;
+    OT *op = out + (int64_t)(it.row_base + qi) * nq * HD + (int64_t)hq * HD + (lane >> 5) * 4;
 #pragma unroll
     for (int t = 0; t < HD / 32; ++t)
 #pragma unroll

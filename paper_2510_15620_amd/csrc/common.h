@@ -124,13 +124,21 @@ int launch_qk_finish(int dtype, float *QKV, const int32_t *pos, const void *q_ga
 // v part of the fp32 projection -> Vt [nkv][hd][vt_stride], IEEE half (in bf16-operand mode: bf16-rounded values)
 int launch_v_finish(int dtype, const float *QKV, int T, int nq, int nkv, int hd, void *Vt, const int32_t *vt_col,
                     int64_t vt_stride, hipStream_t s);
+// Copies the V^T columns of a chunk's shared query (positions [0, ql): columns vt_column_of_key(position) of the chunk,
+// whose query sequence starts at column 0) into the column range of each of n_seq sequences (first columns seq_col0[i],
+// [device]); rows = nkv * hd rows of Vt.  Columns of positions >= ql are left alone.
+int launch_vt_prefix_broadcast(void *Vt, int64_t vt_stride, int rows, int ql, const int32_t *seq_col0, int n_seq, hipStream_t s);
 
 // generic fp32 attention: one workgroup per (token, q head); pos[t] = position of t in its sequence
 int launch_attention_fp32(const float *QKV, const int32_t *pos, int T, int nq, int nkv, int hd, float *out,
                           hipStream_t s);
-// matrix-core attention (hd == 128).  tiles: per work item {first token row of the sequence, sequence length,
-// first query of the tile, column of the sequence's first key in Vt}; see attn_16.hip.
-struct AttnTile { int32_t seq_row0, seq_len, q0, vt_col0; };
+// matrix-core attention (hd == 128).  tiles: per work item {row base of the sequence, sequence length, first query of
+// the tile, column of the sequence's first key in Vt, length and first row of a shared prefix}; see attn_16.hip.
+// Positions below pre_len are a prefix whose q/k rows are stored once, at pre_row0 + position, and shared by several
+// sequences (Sec. 3.3 batches (query, candidate) pairs that all begin with the same query; under a causal mask the
+// query tokens' states do not depend on the candidate); position p >= pre_len has row row_base + p.  Without a prefix
+// pre_len = 0 and row_base is the sequence's first row.  V^T columns are per sequence for ALL its positions.
+struct AttnTile { int32_t row_base, seq_len, q0, vt_col0, pre_len, pre_row0, reserved0, reserved1; };
 int launch_attention_16(int dtype, const void *QK, const void *Vt, int64_t vt_stride, const AttnTile *tiles, int n_tiles,
                         int T, int nq, int nkv, int hd, void *out, hipStream_t s);
 bool attention_16_supported(int nq, int nkv, int hd);
@@ -138,7 +146,7 @@ int attention_16_block_queries(int nq, int nkv);   // queries per AttnTile for t
 // Column of key p of a sequence in the V^T buffer, relative to the sequence's first column: within every group of 16
 // the keys are stored in the order 0-3, 8-11, 4-7, 12-15 (the order in which the matrix cores' accumulator layout hands
 // the probabilities to the second contraction), i.e. bits 2 and 3 of p are swapped.
-inline int vt_column_of_key(int p) { return (p & ~12) | ((p & 4) << 1) | ((p & 8) >> 1); }
+__host__ __device__ inline int vt_column_of_key(int p) { return (p & ~12) | ((p & 4) << 1) | ((p & 8) >> 1); }
 static const int kAttnBQ = 64;   // query rows per attention work item
 
 int launch_score(const float *X, const int32_t *last_row, int n, int hidden, const void *final_norm,

@@ -318,6 +318,27 @@ int launch_compact(const float *Xs, float *Xd, const int32_t *src_start, const i
 }
 
 // ------------------------------------------------------------------------------------------------
+// Shared query: its V^T columns, written once per chunk, are copied into every sequence's column range.
+__global__ __launch_bounds__(256) void vt_prefix_broadcast_kernel(f16 *__restrict__ Vt, int64_t vt_stride, int rows, int ql,
+                                                                   const int32_t *__restrict__ seq_col0) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  f16 *v = Vt + (int64_t)row * vt_stride;
+  const int col0 = seq_col0[blockIdx.y];
+  const int ncol = (ql + 15) & ~15;
+  for (int cidx = threadIdx.x & 63; cidx < ncol; cidx += 64)
+    if (vt_column_of_key(cidx) < ql) v[col0 + cidx] = v[cidx];        // the mapping is its own inverse
+}
+
+int launch_vt_prefix_broadcast(void *Vt, int64_t vt_stride, int rows, int ql, const int32_t *seq_col0, int n_seq, hipStream_t s) {
+  PRISM_REQUIRE(Vt && seq_col0 && vt_stride > 0 && rows > 0 && ql > 0 && n_seq >= 0, PRISM_EINVAL, "vt prefix broadcast: bad arguments");
+  if (n_seq == 0) return PRISM_OK;
+  vt_prefix_broadcast_kernel<<<dim3(cdiv(rows, 4), n_seq), 256, 0, s>>>((f16 *)Vt, vt_stride, rows, ql, seq_col0);
+  PRISM_HIP(hipGetLastError());
+  return PRISM_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
 // Final top-K (Sec. 2.1): rank by counting (score descending, lower position first on ties).
 __global__ __launch_bounds__(1024) void topk_kernel(const float *__restrict__ scores, const int8_t *__restrict__ tag,
                                                     int want, int n, int K, int32_t *__restrict__ out_pos,

@@ -462,9 +462,15 @@ struct Chunk { int c0, c1; int64_t r0, r1; int tile0, n_tiles; int64_t vt_cols; 
 // Per-call host state: the live set and the metadata derived from it.
 struct Plan {
   std::vector<int> live;           // original candidate indices, batch order
-  std::vector<int> len;            // sequence length per live candidate
-  std::vector<int64_t> row0;       // first row per live candidate
-  int64_t T = 0;
+  std::vector<int> len;            // sequence length per live candidate (query + document)
+  std::vector<int64_t> row0;       // first row per live candidate: of its sequence, or of its document when the query is shared
+  // Shared query (ql > 0): under the causal mask the query tokens' states do not depend on the candidate, so every chunk
+  // holds the query's rows ONCE, in front (rows [chunk.r0, chunk.r0 + ql)), followed by the candidates' document rows;
+  // attention reads keys below ql from the chunk's query rows.  ql = 0: every sequence carries its own copy of the query.
+  int ql = 0;
+  int own(int i) const { return len[i] - ql; }   // rows candidate i owns
+  int64_t seq_tokens = 0;          // sum of the live sequences' lengths (what the paper counts as live tokens)
+  int64_t T = 0;                   // rows actually held and computed
   std::vector<Chunk> chunks;
   std::vector<AttnTile> tiles;
   std::vector<AttnTile> last_tiles;   // per live candidate: the query block that holds its last token
@@ -474,49 +480,65 @@ struct Plan {
 static void build_plan(const prism_ctx *c, Plan &p) {
   const int n = (int)p.live.size();
   p.row0.resize(n);
-  int64_t r = 0;
-  for (int i = 0; i < n; ++i) { p.row0[i] = r; r += p.len[i]; }
-  p.T = r;
   p.chunks.clear();
   p.tiles.clear();
-  p.last_tiles.assign(n, AttnTile{0, 0, 0, 0});
+  p.last_tiles.assign(n, AttnTile{0, 0, 0, 0, 0, 0, 0, 0});
   p.max_chunk_tokens = p.max_vt_cols = 0;
+  p.seq_tokens = 0;
   const int step = c->opt.chunk_cands > 0 ? c->opt.chunk_cands : std::max(n, 1);
   const bool mfma = is16(c->op);
   const int bq = mfma ? attention_16_block_queries(c->m.n_q_heads, c->m.n_kv_heads) : 0;
+  const int ql = p.ql;
+  int64_t r = 0;
   for (int c0 = 0; c0 < n; c0 += step) {
     Chunk ch;
     ch.c0 = c0; ch.c1 = std::min(n, c0 + step);
-    ch.r0 = p.row0[c0]; ch.r1 = ch.c1 < n ? p.row0[ch.c1] : p.T;
+    ch.r0 = r;
     ch.tile0 = (int)p.tiles.size();
     int64_t col = 0;
-    if (mfma) {
-      for (int i = ch.c0; i < ch.c1; ++i) {
+    if (ql > 0) {
+      // the shared query: an ordinary sequence of its own (rows [0, ql) of the chunk, columns [0, round_up(ql, 64)))
+      for (int q0 = (ql - 1) / bq * bq; q0 >= 0; q0 -= bq) p.tiles.push_back({0, ql, q0, 0, 0, 0, 0, 0});
+      col = round_up(ql, 64);
+      r += ql;
+    }
+    for (int i = ch.c0; i < ch.c1; ++i) {
+      p.row0[i] = r;
+      r += p.own(i);
+      p.seq_tokens += p.len[i];
+      if (mfma) {
+        // rows relative to the chunk; position t >= ql of the sequence is row row_base + t
+        const int32_t row_base = (int32_t)(p.row0[i] - ch.r0) - ql;
         // a sequence's query blocks stay together (they share its K/V in one XCD's L2), the late ones, which loop
         // over the most keys, first
-        for (int q0 = p.len[i] > 0 ? (p.len[i] - 1) / bq * bq : -1; q0 >= 0; q0 -= bq)
-          p.tiles.push_back({(int32_t)(p.row0[i] - ch.r0), p.len[i], q0, (int32_t)col});
-        p.last_tiles[i] = {(int32_t)(p.row0[i] - ch.r0), p.len[i], (p.len[i] - 1) / bq * bq, (int32_t)col};
+        for (int q0 = p.own(i) > 0 ? ql + (p.own(i) - 1) / bq * bq : -1; q0 >= ql; q0 -= bq)
+          p.tiles.push_back({row_base, p.len[i], q0, (int32_t)col, ql, 0, 0, 0});
+        p.last_tiles[i] = {row_base, p.len[i], ql + (p.own(i) - 1) / bq * bq, (int32_t)col, ql, 0, 0, 0};
         col += round_up(p.len[i], 64);
       }
     }
+    ch.r1 = r;
     ch.n_tiles = (int)p.tiles.size() - ch.tile0;
     ch.vt_cols = col;
     p.chunks.push_back(ch);
     p.max_chunk_tokens = std::max(p.max_chunk_tokens, ch.r1 - ch.r0);
     p.max_vt_cols = std::max(p.max_vt_cols, col);
   }
+  p.T = r;
 }
 
-// meta buffer (int32 words): [pos T][vtcol T][lastrow n][src n][dst n][len n][tiles 4*n_tiles][last tiles 4*n][tokens T]
-struct MetaOff { int64_t pos, vtcol, lastrow, src, dst, len, tiles, ltiles, tokens, words; };
+// meta buffer (int32 words): [pos T][vtcol T][lastrow n][seqcol n][src 2n][dst 2n][len 2n][tiles][last tiles][tokens T]
+// (src/dst/len: one compaction entry per kept candidate plus one per chunk for the shared query's rows)
+struct MetaOff { int64_t pos, vtcol, lastrow, seqcol, src, dst, len, tiles, ltiles, tokens, words; };
 
 static MetaOff meta_offsets(int64_t T, int n, int64_t n_tiles) {
   MetaOff o;
   int64_t w = 0;
   auto take = [&](int64_t k) { int64_t at = w; w = round_up(w + k, 64); return at; };
-  o.pos = take(T); o.vtcol = take(T); o.lastrow = take(n); o.src = take(n); o.dst = take(n); o.len = take(n);
-  o.tiles = take(4 * n_tiles); o.ltiles = take(4 * (int64_t)n); o.tokens = take(T);
+  constexpr int64_t tw = sizeof(AttnTile) / 4;
+  o.pos = take(T); o.vtcol = take(T); o.lastrow = take(n); o.seqcol = take(n);
+  o.src = take(2 * (int64_t)n); o.dst = take(2 * (int64_t)n); o.len = take(2 * (int64_t)n);
+  o.tiles = take(tw * n_tiles); o.ltiles = take(tw * (int64_t)n); o.tokens = take(T);
   o.words = w;
   return o;
 }
@@ -601,15 +623,22 @@ static int ensure_scratch(prism_ctx *c, const Plan &p, bool need_second_x, int n
 static int upload_meta(prism_ctx *c, const Plan &p, const MetaOff &mo, bool with_tokens) {
   int32_t *h = c->h_meta;
   const int n = (int)p.live.size();
+  const int ql = p.ql;
   for (const Chunk &ch : p.chunks) {
     int64_t col = 0;
+    if (ql > 0) {
+      int32_t *pos = h + mo.pos + ch.r0, *vc = h + mo.vtcol + ch.r0;
+      for (int t = 0; t < ql; ++t) { pos[t] = t; vc[t] = (int32_t)vt_column_of_key(t); }
+      col = round_up(ql, 64);
+    }
     for (int i = ch.c0; i < ch.c1; ++i) {
       int32_t *pos = h + mo.pos + p.row0[i], *vc = h + mo.vtcol + p.row0[i];
-      for (int t = 0; t < p.len[i]; ++t) { pos[t] = t; vc[t] = (int32_t)(col + vt_column_of_key(t)); }
+      for (int t = ql; t < p.len[i]; ++t) { pos[t - ql] = t; vc[t - ql] = (int32_t)(col + vt_column_of_key(t)); }
+      h[mo.seqcol + i] = (int32_t)col;
       col += round_up(p.len[i], 64);
     }
   }
-  for (int i = 0; i < n; ++i) h[mo.lastrow + i] = (int32_t)(p.row0[i] + p.len[i] - 1);
+  for (int i = 0; i < n; ++i) h[mo.lastrow + i] = (int32_t)(p.row0[i] + p.own(i) - 1);
   if (!p.tiles.empty()) memcpy(h + mo.tiles, p.tiles.data(), p.tiles.size() * sizeof(AttnTile));
   if (!p.last_tiles.empty()) memcpy(h + mo.ltiles, p.last_tiles.data(), p.last_tiles.size() * sizeof(AttnTile));
   // one copy for [pos .. tiles], a second for the tokens (first upload only)
@@ -790,7 +819,10 @@ static int run_layer(prism_ctx *c, const Plan &p, const MetaOff &mo, float *X, c
     }
     const int32_t *pos = c->d_meta + mo.pos + ch.r0;
     double attn_flops = 0.0;
-    for (int i = ch.c0; i < ch.c1; ++i) attn_flops += 2.0 * m.n_q_heads * m.head_dim * (double)p.len[i] * (p.len[i] + 1.0);
+    // causal triangle of every sequence; with a shared query its own triangle is computed once per chunk
+    const double tri_q = (double)p.ql * (p.ql + 1.0);
+    for (int i = ch.c0; i < ch.c1; ++i) attn_flops += 2.0 * m.n_q_heads * m.head_dim * ((double)p.len[i] * (p.len[i] + 1.0) - tri_q);
+    attn_flops += 2.0 * m.n_q_heads * m.head_dim * tri_q;
     const double tk = 2.0 * Tc;
     // ---- attention block: X += Attn(RMSNorm(X)) Wo^T
     PRISM_TRY(timed_span(c, 5, 0.0, [&] { return launch_rmsnorm(Xc, wbuf + L.attn_norm, Tc, H, m.rms_eps, c->op, c->Xn, s); }));
@@ -816,6 +848,10 @@ static int run_layer(prism_ctx *c, const Plan &p, const MetaOff &mo, float *X, c
                                   c->d_meta + mo.vtcol + ch.r0, c->vt_cap, s));
       return (int)PRISM_OK;
     }));
+    if (p.ql > 0)   // every sequence's V^T columns cover all its positions: the query's part is copied in (a few MB)
+      PRISM_TRY(timed_span(c, 5, 0.0, [&] {
+        return launch_vt_prefix_broadcast(c->Vt, c->vt_cap, Dkv, p.ql, c->d_meta + mo.seqcol + ch.c0, ch.c1 - ch.c0, s);
+      }));
     if (last_only) {
       const int nc = ch.c1 - ch.c0;
       const size_t e = dtype_size(m.dtype);
@@ -924,6 +960,10 @@ static int select_impl(prism_ctx *c, const int32_t *query_tokens, int32_t query_
   }
   const int Kc = std::min(K, n_cands);
   const int mode = K >= n_cands ? PRISM_MODE_NO_PRUNING : c->opt.mode;
+  // the query is held and computed once per chunk where the path supports it: the matrix-core attention kernel (the
+  // fp32 kernel finds sequences by their positions) and a device-resident residual stream
+  p.ql = (!c->opt.no_query_sharing && is16(c->op) && !c->offload && n_cands > 1 &&
+          attention_16_supported(m.n_q_heads, m.n_kv_heads, m.head_dim)) ? query_len : 0;
   build_plan(c, p);
   PRISM_REQUIRE(p.T < (int64_t)1 << 30, PRISM_EINVAL, "prism_select: pool of %lld tokens is too large", (long long)p.T);
   const bool may_prune = mode != PRISM_MODE_NO_PRUNING && !c->checkpoints.empty();
@@ -932,12 +972,14 @@ static int select_impl(prism_ctx *c, const int32_t *query_tokens, int32_t query_
   const MetaOff mo = meta_offsets(p.T, n_cands, max_tiles);
   hipStream_t s = c->stream;
 
-  // tokens, packed: sequence i = query ++ candidate i
+  // tokens, packed: sequence i = query ++ candidate i; with a shared query the query's tokens once per chunk
   {
     int32_t *tok = c->h_meta + mo.tokens;
+    if (p.ql > 0)
+      for (const Chunk &ch : p.chunks) memcpy(tok + ch.r0, query_tokens, (size_t)query_len * 4);
     for (int i = 0; i < n_cands; ++i) {
-      memcpy(tok + p.row0[i], query_tokens, (size_t)query_len * 4);
-      memcpy(tok + p.row0[i] + query_len, cand_tokens[i], (size_t)cand_lens[i] * 4);
+      if (p.ql == 0) memcpy(tok + p.row0[i], query_tokens, (size_t)query_len * 4);
+      memcpy(tok + p.row0[i] + (p.ql == 0 ? query_len : 0), cand_tokens[i], (size_t)cand_lens[i] * 4);
     }
   }
   const bool timed = rep != nullptr;
@@ -1024,7 +1066,7 @@ static int select_impl(prism_ctx *c, const int32_t *query_tokens, int32_t query_
     PRISM_TRY(run_layer(c, p, mo, c->X[cur], c->layer_buf[slot], check_after || last_layer, !last_layer,
                         !last_layer && !check_after, last_layer));
     if (timed) PRISM_HIP(hipEventRecord(c->ev_layer[2 * l + 1], s));
-    token_layers += p.T;
+    token_layers += p.seq_tokens;
     layers_run = l + 1;
     if (c->two_slot && l + c->ring < m.n_layers) {
       PRISM_HIP(hipEventRecord(c->ev_free[slot], s));
@@ -1088,20 +1130,27 @@ static int select_impl(prism_ctx *c, const int32_t *query_tokens, int32_t query_
       // ---- compaction: kept sequences move to the other X buffer, order preserved; metadata is rebuilt
       int32_t *h = c->h_meta;
       Plan q;
-      int64_t dst = 0;
-      int k = 0;
+      q.ql = p.ql;
+      std::vector<int> from;
       for (int i = 0; i < n_live; ++i) {
         if (!keep[i]) continue;
-        h[mo.src + k] = (int32_t)p.row0[i]; h[mo.dst + k] = (int32_t)dst; h[mo.len + k] = p.len[i];
-        q.live.push_back(p.live[i]); q.len.push_back(p.len[i]);
-        dst += p.len[i]; ++k;
+        q.live.push_back(p.live[i]); q.len.push_back(p.len[i]); from.push_back(i);
       }
       build_plan(c, q);
+      int n_moves = 0;
+      for (int k = 0; k < n_keep; ++k, ++n_moves) {
+        h[mo.src + n_moves] = (int32_t)p.row0[from[k]]; h[mo.dst + n_moves] = (int32_t)q.row0[k]; h[mo.len + n_moves] = q.own(k);
+      }
+      if (q.ql > 0)      // every new chunk gets the query's rows (all copies are identical: take the first chunk's)
+        for (const Chunk &ch : q.chunks) {
+          h[mo.src + n_moves] = (int32_t)p.chunks[0].r0; h[mo.dst + n_moves] = (int32_t)ch.r0; h[mo.len + n_moves] = q.ql;
+          ++n_moves;
+        }
       // regrouping the survivors can produce a chunk with more tokens than any chunk before it
       PRISM_TRY(ensure_scratch(c, q, may_prune, n_cands, max_tiles));
       PRISM_TRY(upload_meta(c, q, mo, false));   // also carries src/dst/len, which sit between lastrow and tiles
       if (!c->offload) {   // offload mode: the host copy keeps its layout, dropped candidates are simply never fetched again
-        PRISM_TRY(launch_compact(c->X[cur], c->X[cur ^ 1], c->d_meta + mo.src, c->d_meta + mo.dst, c->d_meta + mo.len, n_keep,
+        PRISM_TRY(launch_compact(c->X[cur], c->X[cur ^ 1], c->d_meta + mo.src, c->d_meta + mo.dst, c->d_meta + mo.len, n_moves,
                                  m.hidden, s));
         cur ^= 1;
       }

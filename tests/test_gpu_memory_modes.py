@@ -67,7 +67,9 @@ def test_offload_bounds_the_device_footprint():
     q, cands = W.make_tokens(w)
     peaks = {}
     for off in (False, True):
-        p = B.Prism(w.model, wt, **_opts(w, chunk_cands=2, offload_hidden=off))
+        # (every sequence with its own copy of the query in both runs: the offloaded layout always has it, and the
+        # bound below counts whole sequences)
+        p = B.Prism(w.model, wt, **_opts(w, chunk_cands=2, offload_hidden=off, share_query=False))
         peaks[off] = p.select(q, cands, w.K)[2].peak_hbm_bytes
         p.destroy()
     lens = sorted((len(q) + len(c) for c in cands), reverse=True)
@@ -104,9 +106,18 @@ def test_embedding_cache_equals_resident_table_and_oracle_lru(name, rows, offloa
     p = B.Prism(w.model, _HostEmbedWeights(wt), **_opts(w, chunk_cands=chunk, embed_on_host=True, embed_cache_rows=rows,
                                                          offload_hidden=offload))
     lru = O.LruRowCache(rows if rows else max(w.model.vocab // 10, 1))
-    stream = np.concatenate([np.concatenate([q, c]) for c in cands])
+
+    def looked_up(q, cands):
+        """The token stream in the order the library gathers embedding rows: sequence by sequence, or, where the query's
+        rows are shared (16-bit path, residual stream on the device), per chunk the query once and then the documents."""
+        if w.model.dtype == "fp32" or offload or len(cands) < 2:
+            return np.concatenate([np.concatenate([q, c]) for c in cands])
+        step = chunk if chunk else len(cands)
+        return np.concatenate([np.concatenate([q] + list(cands[i:i + step])) for i in range(0, len(cands), step)])
+
+    stream = looked_up(q, cands)
     q2, cands2 = q[::-1].copy(), [c[::-1].copy() for c in cands[:5]]      # a second, different request on the warm cache
-    stream2 = np.concatenate([np.concatenate([q2, c]) for c in cands2])
+    stream2 = looked_up(q2, cands2)
     out = p.select(q, cands, w.K)
     _same(out, ref)
     assert (out[2].embed_rows_hit, out[2].embed_rows_missed) == lru.run(stream)

@@ -187,3 +187,24 @@ def test_checkpoint_after_every_layer(name, tol, tau):
     ref = oracle_select(w)
     check_against_oracle(w, idx, scores, rep, ref, tol)
     assert len(rep.layer) >= 2
+
+
+@pytest.mark.parametrize("name,kw", [("mini_bf16", {}), ("mini_bf16", {"chunk_cands": 3}), ("mini_bf16", {"mode": B.MODE_THREE_WAY}),
+                                     ("mini_bf16", {"operand": "bf16", "chunk_cands": 5}), ("cfg2_0p6b", {}),
+                                     ("cfg2_0p6b", {"chunk_cands": 8})])
+def test_sharing_the_query_rows_changes_nothing(name, kw):
+    """Every (query, candidate) sequence begins with the same query (Sec. 3.3) and, under the causal mask, the query
+    tokens' states do not depend on the candidate: holding and computing them once per chunk (the default) gives the
+    scores of the computation in which every sequence carries its own copy, bit for bit, at every check, through pruning
+    and compaction.  mini_bf16 has a 24-token query (not a multiple of the 16-key column groups of the transposed V
+    buffer), cfg2_0p6b a 32-token one.  (The cases are chosen so that both runs launch the same kernel variants: the row
+    count of a launch decides between the fused and the unfused q/k/v finishing and between two GEMM tilings, which
+    round differently in the last bit.)"""
+    w = W.WORKLOADS[name]
+    wt = W.make_weights(w, "cuda")
+    shared = run(w, wt, **kw)
+    own = run(w, wt, share_query=False, **kw)
+    assert shared[0].tolist() == own[0].tolist() and np.array_equal(shared[1], own[1])
+    assert np.array_equal(shared[2].scores, own[2].scores, equal_nan=True)
+    assert np.array_equal(shared[2].fate, own[2].fate) and shared[2].layer.tolist() == own[2].layer.tolist()
+    assert shared[2].token_layers == own[2].token_layers            # counted in sequence tokens either way
