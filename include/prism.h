@@ -129,6 +129,12 @@ typedef struct {
                                          attend to those rows; results are those of the unshared computation.  Applies
                                          to the 16-bit matrix-core path with a device-resident residual stream.
                                          1: every sequence carries and computes its own copy of the query */
+  int32_t single_pass_checks;         /* 0 (default): a layer whose output is checked (Sec. 3.4) runs in two passes: first
+                                         what the scores need (keys and values of every token; attention, O projection
+                                         and FFN for each candidate's last token), then, after the decision, the rest of
+                                         the layer for the survivors only.  Scores and results are those of the one-pass
+                                         order.  Applies with a device-resident residual stream.
+                                         1: the whole layer runs on every live candidate before the check */
 } prism_options;
 
 /* Optional per-call record.  The caller allocates every array ([host]); an "event" is one

@@ -53,7 +53,7 @@ class prism_options(C.Structure):
     _fields_ = [("checkpoint_layers", C.POINTER(C.c_int32)), ("n_checkpoints", C.c_int32), ("cv_threshold", C.c_float),
                 ("n_clusters", C.c_int32), ("mode", C.c_int32), ("chunk_cands", C.c_int32), ("hbm_cap_bytes", C.c_int64),
                 ("stream", C.c_void_p), ("operand", C.c_int32), ("offload_hidden", C.c_int32), ("embed_cache_rows", C.c_int32), ("stream_slots", C.c_int32),
-                ("no_query_sharing", C.c_int32)]
+                ("no_query_sharing", C.c_int32), ("single_pass_checks", C.c_int32)]
 
 
 class prism_report(C.Structure):
@@ -169,7 +169,8 @@ class Prism:
     def __init__(self, model, weights, *, checkpoints: Sequence[int] = (), cv_threshold: float = 0.0, n_clusters: int = 3,
                  mode: int = MODE_DROP_ONLY, chunk_cands: int = 0, hbm_cap_bytes: int = 0, stream_weights: bool = False,
                  stream: Optional[int] = None, operand: str = "f16", offload_hidden: bool = False, embed_on_host: bool = False,
-                 embed_cache_rows: int = 0, w4: bool = False, stream_slots: int = 0, share_query: bool = True):
+                 embed_cache_rows: int = 0, w4: bool = False, stream_slots: int = 0, share_query: bool = True,
+                 two_pass_checks: bool = True):
         """model: object with n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, rms_eps, rope_base,
         qk_norm, dtype ("fp32" | "bf16": storage type of the weights).  operand ("f16" | "bf16"): 16-bit type of the
         matrix-core operands when the weights are bf16.  weights: object with embed, final_norm, w_yes, w_no (device tensors) and
@@ -177,7 +178,8 @@ class Prism:
         pinned host tensor (w_yes / w_no stay device tensors) read through a device LRU cache of embed_cache_rows rows.
         offload_hidden: the residual stream lives in pinned host memory, three chunks at a time on the device.
         w4: the seven matrices of every layer dict are uint8 blobs from quantize_w4 (gains stay bf16).
-        share_query=False: every sequence carries its own copy of the query (prism_options.no_query_sharing)."""
+        share_query=False: every sequence carries its own copy of the query (prism_options.no_query_sharing).
+        two_pass_checks=False: a checked layer runs completely before its check (prism_options.single_pass_checks)."""
         self._ctx = C.c_void_p()
         m = prism_model(model.n_layers, model.hidden, model.n_q_heads, model.n_kv_heads, model.head_dim, model.ffn,
                         model.vocab, model.rms_eps, model.rope_base, DTYPE_FP32 if model.dtype == "fp32" else DTYPE_BF16,
@@ -192,7 +194,8 @@ class Prism:
         ck, ckp = _i32_array(list(checkpoints))
         o = prism_options(ckp, len(ck), cv_threshold, n_clusters, mode, chunk_cands, hbm_cap_bytes,
                           _stream() if stream is None else stream, DTYPE_BF16 if operand == "bf16" else DTYPE_F16,
-                          int(offload_hidden), embed_cache_rows, stream_slots, 0 if share_query else 1)
+                          int(offload_hidden), embed_cache_rows, stream_slots, 0 if share_query else 1,
+                          0 if two_pass_checks else 1)
         self.n_checkpoints = len(ck)
         _check(lib().prism_create(C.byref(m), C.byref(w), C.byref(o), C.byref(self._ctx)))
 

@@ -105,7 +105,7 @@ struct prism_ctx {
   int ring = 2;                                   // layer slots of the streaming ring (two_slot); 2 is the paper's double buffer
   std::vector<hipEvent_t> ev_ready, ev_free;      // per ring slot
   hipEvent_t ev_t[4] = {nullptr, nullptr, nullptr, nullptr};
-  std::vector<hipEvent_t> ev_layer;               // 2 per layer, for the report
+  std::vector<hipEvent_t> ev_layer;               // 4 per layer (two intervals: a layer may run in two passes), for the report
   // per-launch spans for the report: events come from a pool that only grows
   struct Span { int kind; hipEvent_t a, b; double flops; int rows; };
   std::vector<hipEvent_t> ev_pool; size_t ev_used = 0;
@@ -789,8 +789,10 @@ static int retire_chunk(prism_ctx *c, const Plan &p, const Chunk &ch, int slot, 
 // last token's state only.  Keys and values are still needed for every token, so the q/k/v projection runs in full; the
 // attention runs for the query block that holds the last token, and the O projection and the whole FFN block run on one
 // gathered row per candidate, whose final scores are taken right there.
+// resume: the chunk scratch still holds this plan's finished q, k and V^T of this layer (left by a last_only pass over the
+// same single chunk): the layer continues at the attention step.
 static int run_layer(prism_ctx *c, const Plan &p, const MetaOff &mo, float *X, const char *wbuf, bool score_after = false,
-                     bool write_back = true, bool next_layer_same_plan = false, bool last_only = false) {
+                     bool write_back = true, bool next_layer_same_plan = false, bool last_only = false, bool resume = false) {
   const prism_model &m = c->m;
   const LayerLayout &L = c->lay;
   const int H = m.hidden, Dq = m.n_q_heads * m.head_dim, Dkv = m.n_kv_heads * m.head_dim, F = m.ffn;
@@ -825,6 +827,7 @@ static int run_layer(prism_ctx *c, const Plan &p, const MetaOff &mo, float *X, c
     attn_flops += 2.0 * m.n_q_heads * m.head_dim * tri_q;
     const double tk = 2.0 * Tc;
     // ---- attention block: X += Attn(RMSNorm(X)) Wo^T
+    if (!resume) {
     PRISM_TRY(timed_span(c, 5, 0.0, [&] { return launch_rmsnorm(Xc, wbuf + L.attn_norm, Tc, H, m.rms_eps, c->op, c->Xn, s); }));
     // 16-bit modes at head_dim 128 with enough rows: norm, RoPE, rounding and the V transposition happen in the
     // projection's epilogue; otherwise the projection is stored in fp32 and finished by separate kernels
@@ -852,6 +855,7 @@ static int run_layer(prism_ctx *c, const Plan &p, const MetaOff &mo, float *X, c
       PRISM_TRY(timed_span(c, 5, 0.0, [&] {
         return launch_vt_prefix_broadcast(c->Vt, c->vt_cap, Dkv, p.ql, c->d_meta + mo.seqcol + ch.c0, ch.c1 - ch.c0, s);
       }));
+    }
     if (last_only) {
       const int nc = ch.c1 - ch.c0;
       const size_t e = dtype_size(m.dtype);
@@ -987,9 +991,9 @@ static int select_impl(prism_ctx *c, const int32_t *query_tokens, int32_t query_
   c->span_mask = timed && rep->kind_mask ? rep->kind_mask : ~0;
   c->spans.clear();
   c->ev_used = 0;
-  if (timed && (int)c->ev_layer.size() < 2 * m.n_layers) {
+  if (timed && (int)c->ev_layer.size() < 4 * m.n_layers) {
     const size_t old = c->ev_layer.size();
-    c->ev_layer.resize(2 * m.n_layers, nullptr);
+    c->ev_layer.resize(4 * m.n_layers, nullptr);
     for (size_t i = old; i < c->ev_layer.size(); ++i) PRISM_HIP(hipEventCreate(&c->ev_layer[i]));
   }
   if (timed) PRISM_HIP(hipEventRecord(c->ev_t[0], s));
@@ -1054,32 +1058,45 @@ static int select_impl(prism_ctx *c, const int32_t *query_tokens, int32_t query_
     rep->ev_n_after[e] = n_after; rep->ev_tokens_after[e] = (int32_t)tok_after;
   };
 
+  std::vector<char> second_pass(m.n_layers, 0);
   for (int l = 0; l < m.n_layers && !terminated; ++l) {
     const int slot = c->two_slot ? l % c->ring : l;
     if (c->two_slot) PRISM_HIP(hipStreamWaitEvent(s, c->ev_ready[slot], 0));
-    if (timed) PRISM_HIP(hipEventRecord(c->ev_layer[2 * l], s));
+    if (timed) PRISM_HIP(hipEventRecord(c->ev_layer[4 * l], s));
     // known before the layer runs: will its output be scored for pruning, and is it the last one
     while (next_ckpt < c->checkpoints.size() && c->checkpoints[next_ckpt] < l + 1) ++next_ckpt;
     const bool check_after = next_ckpt < c->checkpoints.size() && c->checkpoints[next_ckpt] == l + 1 && l + 1 < m.n_layers &&
                              may_prune && (int)p.live.size() > K_rem;
     const bool last_layer = l + 1 == m.n_layers;
+    // A layer whose output is checked runs in two passes: first only what the scores need (keys and values of every
+    // token, then attention, O projection and FFN for each candidate's last token, exactly as in the last layer), then,
+    // after the decision, the rest of the layer for the survivors alone - the candidates the check drops never get
+    // their layer finished.  The scores are the same bits either way (the GEMM variants and the other kernels compute a
+    // row identically wherever it sits).
+    const bool peek = check_after && !c->offload && !c->opt.single_pass_checks;
+    second_pass[l] = false;
     PRISM_TRY(run_layer(c, p, mo, c->X[cur], c->layer_buf[slot], check_after || last_layer, !last_layer,
-                        !last_layer && !check_after, last_layer));
-    if (timed) PRISM_HIP(hipEventRecord(c->ev_layer[2 * l + 1], s));
+                        !last_layer && !check_after, last_layer || peek));
+    if (timed) PRISM_HIP(hipEventRecord(c->ev_layer[4 * l + 1], s));
     token_layers += p.seq_tokens;
     layers_run = l + 1;
-    if (c->two_slot && l + c->ring < m.n_layers) {
-      PRISM_HIP(hipEventRecord(c->ev_free[slot], s));
-      PRISM_HIP(hipStreamWaitEvent(c->copy_stream, c->ev_free[slot], 0));
-      PRISM_TRY(issue_layer_copy(c, l + c->ring, slot, c->copy_stream, hipMemcpyHostToDevice, &bytes_streamed));
-      PRISM_HIP(hipEventRecord(c->ev_ready[slot], c->copy_stream));
-    }
+    auto release_slot = [&]() -> int {       // the layer's weights are no longer needed: the ring moves on
+      if (c->two_slot && l + c->ring < m.n_layers) {
+        PRISM_HIP(hipEventRecord(c->ev_free[slot], s));
+        PRISM_HIP(hipStreamWaitEvent(c->copy_stream, c->ev_free[slot], 0));
+        PRISM_TRY(issue_layer_copy(c, l + c->ring, slot, c->copy_stream, hipMemcpyHostToDevice, &bytes_streamed));
+        PRISM_HIP(hipEventRecord(c->ev_ready[slot], c->copy_stream));
+      }
+      return PRISM_OK;
+    };
+    if (!peek) PRISM_TRY(release_slot());
     const int n_live = (int)p.live.size();
     if (!check_after) continue;
+    bool compacted = false;
 
     // ---- pruning check on the output of layer l + 1, before layer l + 2 runs (Sec. 3.4, 4.1)
     if (timed) PRISM_HIP(hipEventRecord(c->ev_t[2], s));
-    if (!c->offload)   // offload mode scored every chunk while it was on the device
+    if (!c->offload && !peek)   // offload mode scored every chunk while it was on the device, the first pass its last rows
       PRISM_TRY(launch_score(c->X[cur], c->d_meta + mo.lastrow, n_live, m.hidden, c->final_norm, c->w_yes, c->w_no, m.dtype,
                              m.rms_eps, c->d_scores, s));
     PRISM_TRY(launch_route(c->d_scores, n_live, K_rem, c->opt.n_clusters, c->opt.cv_threshold, c->d_fate, c->d_stats,
@@ -1155,6 +1172,7 @@ static int select_impl(prism_ctx *c, const int32_t *query_tokens, int32_t query_
         cur ^= 1;
       }
       p = q;
+      compacted = true;
     }
     if (timed) {
       PRISM_HIP(hipEventRecord(c->ev_t[3], s));
@@ -1162,6 +1180,18 @@ static int select_impl(prism_ctx *c, const int32_t *query_tokens, int32_t query_
       float ms = 0.f;
       PRISM_HIP(hipEventElapsedTime(&ms, c->ev_t[2], c->ev_t[3]));
       ms_checks += ms;
+    }
+    if (peek) {
+      if (!terminated) {
+        // second pass: the layer for the survivors.  If nobody left and the pool is one chunk, the scratch still holds
+        // this layer's q, k and V^T and the pass starts at the attention step
+        if (timed) PRISM_HIP(hipEventRecord(c->ev_layer[4 * l + 2], s));
+        PRISM_TRY(run_layer(c, p, mo, c->X[cur], c->layer_buf[slot], false, true, false, false,
+                            !compacted && p.chunks.size() == 1));
+        if (timed) PRISM_HIP(hipEventRecord(c->ev_layer[4 * l + 3], s));
+        second_pass[l] = true;
+      }
+      PRISM_TRY(release_slot());
     }
   }
 
@@ -1199,8 +1229,12 @@ static int select_impl(prism_ctx *c, const int32_t *query_tokens, int32_t query_
     rep->ms_total = ms;
     double ml = 0.0;
     for (int l = 0; l < layers_run; ++l) {
-      PRISM_HIP(hipEventElapsedTime(&ms, c->ev_layer[2 * l], c->ev_layer[2 * l + 1]));
+      PRISM_HIP(hipEventElapsedTime(&ms, c->ev_layer[4 * l], c->ev_layer[4 * l + 1]));
       ml += ms;
+      if (second_pass[l]) {
+        PRISM_HIP(hipEventElapsedTime(&ms, c->ev_layer[4 * l + 2], c->ev_layer[4 * l + 3]));
+        ml += ms;
+      }
     }
     rep->ms_layers = ml;
     rep->ms_checks = ms_checks;

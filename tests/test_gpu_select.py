@@ -208,3 +208,30 @@ def test_sharing_the_query_rows_changes_nothing(name, kw):
     assert np.array_equal(shared[2].scores, own[2].scores, equal_nan=True)
     assert np.array_equal(shared[2].fate, own[2].fate) and shared[2].layer.tolist() == own[2].layer.tolist()
     assert shared[2].token_layers == own[2].token_layers            # counted in sequence tokens either way
+
+
+@pytest.mark.parametrize("name,kw", [("cfg1_tiny", {}), ("mini_fp32", {"chunk_cands": 4}), ("mini_bf16", {}), ("mini_bf16", {"chunk_cands": 3}),
+                                     ("mini_bf16", {"mode": B.MODE_THREE_WAY}), ("cfg2_0p6b", {}), ("cfg2_0p6b", {"mode": B.MODE_THREE_WAY})])
+def test_two_pass_checked_layers_change_nothing(name, kw):
+    """A layer whose output is checked (Sec. 3.4) first computes only what the scores need, then, after the decision, the
+    rest of the layer for the survivors: same scores at every check, same decisions, same output as running the whole
+    layer on every live candidate before the check, bit for bit - as long as both orders launch the same kernel variants.
+    cfg2_0p6b is the exception that shows the limit: after its last prune the second pass covers 10 candidates, about
+    3300 rows, below the row count from which the q/k/v projection fuses its finishing steps into the GEMM epilogue,
+    while the one-pass order still runs that layer on 19 candidates; the two finishing paths round differently in the
+    last bit, so the scores agree exactly up to the first such launch and to 1e-3 after it (decisions and output are the
+    same)."""
+    w = W.WORKLOADS[name]
+    wt = W.make_weights(w, "cuda")
+    two = run(w, wt, **kw)
+    one = run(w, wt, two_pass_checks=False, **kw)
+    exact = name != "cfg2_0p6b"
+    assert two[0].tolist() == one[0].tolist()
+    assert np.array_equal(two[2].fate, one[2].fate) and two[2].layer.tolist() == one[2].layer.tolist()
+    assert two[2].token_layers == one[2].token_layers and two[2].layers_run == one[2].layers_run
+    if exact:
+        assert np.array_equal(two[1], one[1]) and np.array_equal(two[2].scores, one[2].scores, equal_nan=True)
+    else:
+        assert np.array_equal(two[2].scores[0], one[2].scores[0], equal_nan=True)      # the first check sees the full pool either way
+        np.testing.assert_allclose(two[2].scores, one[2].scores, rtol=0, atol=1e-3, equal_nan=True)
+        np.testing.assert_allclose(two[1], one[1], rtol=0, atol=1e-3)
