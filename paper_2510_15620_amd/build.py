@@ -15,6 +15,7 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 SOURCES = ["prism_api.hip", "elementwise.hip", "prune.hip", "gemm_fp32.hip", "gemm_16.hip", "attn_fp32.hip",
            "attn_16.hip", "quant.hip"]
+# PRISM_EXTRA_FLAGS: extra hipcc flags for experiments (e.g. -D switches of timing builds); empty in normal use
 COMMON = ["--offload-arch=gfx950", "-O3", *os.environ.get("PRISM_EXTRA_FLAGS", "").split(), "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
           # hipcc -O3 may otherwise form packed-fp32 instructions from ordinary float code
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -154,24 +154,24 @@ def _every(n_layers, stride):
 
 
 WORKLOADS: Dict[str, Workload] = {
-    # BASELINE configs[0]: tiny fp32 model
+    # benchmark configuration 1: tiny fp32 model
     "cfg1_tiny": Workload("cfg1_tiny", ModelShape(2, 256, 4, 2, 64, 688, 1000, "fp32"),
                           16, 8, ("uniform", 16, 48), 3, [1]),
-    # BASELINE configs[1]: 0.6B-shaped
+    # benchmark configuration 2: 0.6B-shaped
     "cfg2_0p6b": Workload("cfg2_0p6b", ModelShape(28, 1024, 16, 8, 128, 3072, 151936),
                           32, 40, ("uniform", 128, 480), 10, _every(28, 4)),
-    # BASELINE configs[2]: 4B-shaped
+    # benchmark configuration 3: 4B-shaped
     "cfg3_4b": Workload("cfg3_4b", ModelShape(36, 2560, 32, 8, 128, 9728, 151936),
                         32, 100, ("uniform", 256, 992), 10, _every(36, 4)),
-    # BASELINE configs[3]: 8B-shaped headline, every sequence exactly 1024 tokens (64 + 960)
+    # benchmark configuration 4: 8B-shaped headline, every sequence exactly 1024 tokens (64 + 960)
     "cfg4_8b": Workload("cfg4_8b", ModelShape(36, 4096, 32, 8, 128, 12288, 151936),
                         64, 100, ("const", 960), 10, _every(36, 4)),
-    # BASELINE configs[4]: 8B-shaped, weights streamed from pinned host memory, chunks of 64
+    # benchmark configuration 5: 8B-shaped, weights streamed from pinned host memory, chunks of 64
     "cfg5_8b_stream": Workload("cfg5_8b_stream", ModelShape(36, 4096, 32, 8, 128, 12288, 151936),
                                64, 500, ("lognormal", 400.0, 0.6, 32, 2048), 20, _every(36, 4),
                                chunk_cands=64, stream_weights=True, hbm_cap_bytes=24 * 10**9,
                                weights_name="cfg4_8b"),       # "8B-shaped reranker as in the previous config"
-    # small cases for element-by-element parity (not BASELINE configs)
+    # small cases for element-by-element parity (not benchmark configurations)
     "mini_bf16": Workload("mini_bf16", ModelShape(4, 512, 8, 2, 128, 1408, 2048),
                           24, 13, ("uniform", 20, 300), 4, [1, 2, 3]),
     "mini_fp32": Workload("mini_fp32", ModelShape(3, 192, 6, 3, 32, 400, 500, "fp32"),
