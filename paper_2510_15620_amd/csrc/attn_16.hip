@@ -212,7 +212,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   if (qi < L) {
     const float inv = 1.0f / l_tot;
-    OT *op = out + (int64_t)(it.row_base + qi) * nq * HD + (int64_t)hq * HD + (lane >> 5) * 4;
+    OT *op = out + (int64_t)(it.out_base + qi) * nq * HD + (int64_t)hq * HD + (lane >> 5) * 4;
 #pragma unroll
     for (int t = 0; t < HD / 32; ++t)
 #pragma unroll

@@ -138,7 +138,9 @@ int launch_attention_fp32(const float *QKV, const int32_t *pos, int T, int nq, i
 // sequences (Sec. 3.3 batches (query, candidate) pairs that all begin with the same query; under a causal mask the
 // query tokens' states do not depend on the candidate); position p >= pre_len has row row_base + p.  Without a prefix
 // pre_len = 0 and row_base is the sequence's first row.  V^T columns are per sequence for ALL its positions.
-struct AttnTile { int32_t row_base, seq_len, q0, vt_col0, pre_len, pre_row0, reserved0, reserved1; };
+// out_base: the tile's output for position p goes to row out_base + p (normally row_base; it differs when the layout the
+// q/k rows were projected in is not the one the layer continues in).
+struct AttnTile { int32_t row_base, seq_len, q0, vt_col0, pre_len, pre_row0, out_base, reserved; };
 int launch_attention_16(int dtype, const void *QK, const void *Vt, int64_t vt_stride, const AttnTile *tiles, int n_tiles,
                         int T, int nq, int nkv, int hd, void *out, hipStream_t s);
 bool attention_16_supported(int nq, int nkv, int hd);

@@ -474,6 +474,10 @@ struct Plan {
   std::vector<Chunk> chunks;
   std::vector<AttnTile> tiles;
   std::vector<AttnTile> last_tiles;   // per live candidate: the query block that holds its last token
+  std::vector<int64_t> col0;          // per live candidate: first V^T column of its sequence (within its chunk)
+  // second pass of a checked layer after a prune (single chunk): attention work items that read q, k and V^T where the
+  // first pass projected them (the layout before the prune) and write their output in this plan's layout
+  std::vector<AttnTile> xtiles;
   int64_t max_chunk_tokens = 0, max_vt_cols = 0;
 };
 
@@ -483,6 +487,8 @@ static void build_plan(const prism_ctx *c, Plan &p) {
   p.chunks.clear();
   p.tiles.clear();
   p.last_tiles.assign(n, AttnTile{0, 0, 0, 0, 0, 0, 0, 0});
+  p.col0.assign(n, 0);
+  p.xtiles.clear();
   p.max_chunk_tokens = p.max_vt_cols = 0;
   p.seq_tokens = 0;
   const int step = c->opt.chunk_cands > 0 ? c->opt.chunk_cands : std::max(n, 1);
@@ -498,7 +504,7 @@ static void build_plan(const prism_ctx *c, Plan &p) {
     int64_t col = 0;
     if (ql > 0) {
       // the shared query: an ordinary sequence of its own (rows [0, ql) of the chunk, columns [0, round_up(ql, 64)))
-      for (int q0 = (ql - 1) / bq * bq; q0 >= 0; q0 -= bq) p.tiles.push_back({0, ql, q0, 0, 0, 0, 0, 0});
+      for (int q0 = (ql - 1) / bq * bq; q0 >= 0; q0 -= bq) p.tiles.push_back({0, ql, q0, 0, 0, 0, 0, 0});   // row_base = out_base = 0
       col = round_up(ql, 64);
       r += ql;
     }
@@ -512,8 +518,9 @@ static void build_plan(const prism_ctx *c, Plan &p) {
         // a sequence's query blocks stay together (they share its K/V in one XCD's L2), the late ones, which loop
         // over the most keys, first
         for (int q0 = p.own(i) > 0 ? ql + (p.own(i) - 1) / bq * bq : -1; q0 >= ql; q0 -= bq)
-          p.tiles.push_back({row_base, p.len[i], q0, (int32_t)col, ql, 0, 0, 0});
-        p.last_tiles[i] = {row_base, p.len[i], ql + (p.own(i) - 1) / bq * bq, (int32_t)col, ql, 0, 0, 0};
+          p.tiles.push_back({row_base, p.len[i], q0, (int32_t)col, ql, 0, row_base, 0});
+        p.last_tiles[i] = {row_base, p.len[i], ql + (p.own(i) - 1) / bq * bq, (int32_t)col, ql, 0, row_base, 0};
+        p.col0[i] = col;
         col += round_up(p.len[i], 64);
       }
     }
@@ -527,9 +534,9 @@ static void build_plan(const prism_ctx *c, Plan &p) {
   p.T = r;
 }
 
-// meta buffer (int32 words): [pos T][vtcol T][lastrow n][seqcol n][src 2n][dst 2n][len 2n][tiles][last tiles][tokens T]
+// meta buffer (int32 words): [pos T][vtcol T][lastrow n][seqcol n][src 2n][dst 2n][len 2n][tiles][last tiles][xtiles][tokens T]
 // (src/dst/len: one compaction entry per kept candidate plus one per chunk for the shared query's rows)
-struct MetaOff { int64_t pos, vtcol, lastrow, seqcol, src, dst, len, tiles, ltiles, tokens, words; };
+struct MetaOff { int64_t pos, vtcol, lastrow, seqcol, src, dst, len, tiles, ltiles, xtiles, tokens, words; };
 
 static MetaOff meta_offsets(int64_t T, int n, int64_t n_tiles) {
   MetaOff o;
@@ -538,7 +545,7 @@ static MetaOff meta_offsets(int64_t T, int n, int64_t n_tiles) {
   constexpr int64_t tw = sizeof(AttnTile) / 4;
   o.pos = take(T); o.vtcol = take(T); o.lastrow = take(n); o.seqcol = take(n);
   o.src = take(2 * (int64_t)n); o.dst = take(2 * (int64_t)n); o.len = take(2 * (int64_t)n);
-  o.tiles = take(tw * n_tiles); o.ltiles = take(tw * (int64_t)n); o.tokens = take(T);
+  o.tiles = take(tw * n_tiles); o.ltiles = take(tw * (int64_t)n); o.xtiles = take(tw * n_tiles); o.tokens = take(T);
   o.words = w;
   return o;
 }
@@ -641,6 +648,7 @@ static int upload_meta(prism_ctx *c, const Plan &p, const MetaOff &mo, bool with
   for (int i = 0; i < n; ++i) h[mo.lastrow + i] = (int32_t)(p.row0[i] + p.own(i) - 1);
   if (!p.tiles.empty()) memcpy(h + mo.tiles, p.tiles.data(), p.tiles.size() * sizeof(AttnTile));
   if (!p.last_tiles.empty()) memcpy(h + mo.ltiles, p.last_tiles.data(), p.last_tiles.size() * sizeof(AttnTile));
+  if (!p.xtiles.empty()) memcpy(h + mo.xtiles, p.xtiles.data(), p.xtiles.size() * sizeof(AttnTile));
   // one copy for [pos .. tiles], a second for the tokens (first upload only)
   PRISM_HIP(hipMemcpyAsync(c->d_meta, h, (size_t)mo.tokens * 4, hipMemcpyHostToDevice, c->stream));
   if (with_tokens)
@@ -887,9 +895,13 @@ static int run_layer(prism_ctx *c, const Plan &p, const MetaOff &mo, float *X, c
                              c->d_scores + ch.c0, s));
     } else {
     PRISM_TRY(timed_span(c, 4, attn_flops, [&] {
-      if (bf)
+      if (bf) {
+        if (resume && !p.xtiles.empty())      // q, k and V^T sit where the first pass left them
+          return launch_attention_16(c->op, c->QK, c->Vt, c->vt_cap, (const AttnTile *)(c->d_meta + mo.xtiles),
+                                     (int)p.xtiles.size(), Tc, m.n_q_heads, m.n_kv_heads, m.head_dim, c->AO, s);
         return launch_attention_16(c->op, c->QK, c->Vt, c->vt_cap, (const AttnTile *)(c->d_meta + mo.tiles) + ch.tile0,
                                    ch.n_tiles, Tc, m.n_q_heads, m.n_kv_heads, m.head_dim, c->AO, s);
+      }
       return launch_attention_fp32((const float *)c->QKV, pos, Tc, m.n_q_heads, m.n_kv_heads, m.head_dim, (float *)c->AO, s);
     }, Tc));
     PRISM_TRY(timed_span(c, 1, tk * H * Dq, [&] { return gemm(PRISM_EPI_RESIDUAL, c->AO, wbuf + L.wo, Xc, Tc, H, Dq); }, Tc));
@@ -1154,6 +1166,18 @@ static int select_impl(prism_ctx *c, const int32_t *query_tokens, int32_t query_
         q.live.push_back(p.live[i]); q.len.push_back(p.len[i]); from.push_back(i);
       }
       build_plan(c, q);
+      if (peek && is16(c->op) && p.chunks.size() == 1 && q.chunks.size() == 1) {
+        const int bq = attention_16_block_queries(m.n_q_heads, m.n_kv_heads);
+        const int ql = q.ql;
+        if (ql > 0)
+          for (int q0 = (ql - 1) / bq * bq; q0 >= 0; q0 -= bq) q.xtiles.push_back({0, ql, q0, 0, 0, 0, 0, 0});
+        for (int k = 0; k < n_keep; ++k) {
+          const int i = from[k];
+          const int32_t old_base = (int32_t)p.row0[i] - ql, new_base = (int32_t)q.row0[k] - ql;
+          for (int q0 = ql + (q.own(k) - 1) / bq * bq; q0 >= ql; q0 -= bq)
+            q.xtiles.push_back({old_base, q.len[k], q0, (int32_t)p.col0[i], ql, 0, new_base, 0});
+        }
+      }
       int n_moves = 0;
       for (int k = 0; k < n_keep; ++k, ++n_moves) {
         h[mo.src + n_moves] = (int32_t)p.row0[from[k]]; h[mo.dst + n_moves] = (int32_t)q.row0[k]; h[mo.len + n_moves] = q.own(k);
@@ -1183,11 +1207,13 @@ static int select_impl(prism_ctx *c, const int32_t *query_tokens, int32_t query_
     }
     if (peek) {
       if (!terminated) {
-        // second pass: the layer for the survivors.  If nobody left and the pool is one chunk, the scratch still holds
-        // this layer's q, k and V^T and the pass starts at the attention step
+        // second pass: the layer for the survivors.  If the pool is one chunk, the scratch still holds this layer's q, k
+        // and V^T (in the layout before the prune) and the pass starts at the attention step, which writes its output
+        // in the survivors' layout
         if (timed) PRISM_HIP(hipEventRecord(c->ev_layer[4 * l + 2], s));
         PRISM_TRY(run_layer(c, p, mo, c->X[cur], c->layer_buf[slot], false, true, false, false,
-                            !compacted && p.chunks.size() == 1));
+                            p.chunks.size() == 1 && (!compacted || !p.xtiles.empty())));
+        p.xtiles.clear();
         if (timed) PRISM_HIP(hipEventRecord(c->ev_layer[4 * l + 3], s));
         second_pass[l] = true;
       }
@@ -1372,7 +1398,7 @@ extern "C" int prism_op_attention(int32_t dtype, const void *QK, const void *Vt,
     const int L = cu[i + 1] - cu[i];
     PRISM_REQUIRE(vt_col0[i] >= 0 && vt_col0[i] % 64 == 0 && vt_col0[i] + round_up(L, 64) <= vt_stride, PRISM_EINVAL,
                   "attention bf16: sequence %d: V^T columns must start at a multiple of 64 and fit the row stride", i);
-    for (int q0 = L > 0 ? (L - 1) / bq * bq : -1; q0 >= 0; q0 -= bq) tiles.push_back({cu[i], L, q0, vt_col0[i]});
+    for (int q0 = L > 0 ? (L - 1) / bq * bq : -1; q0 >= 0; q0 -= bq) tiles.push_back({cu[i], L, q0, vt_col0[i], 0, 0, cu[i], 0});
   }
   TmpDev d_tiles;
   PRISM_TRY(d_tiles.alloc(tiles.size() * sizeof(AttnTile)));
