@@ -22,6 +22,11 @@
 // second contraction runs on the f16 MFMA in both modes so that the probabilities keep 11
 // significand bits.  A sequence's columns
 // start at a multiple of 64 so every 16-byte chunk is aligned.
+// Shared prefix (paper Sec. 3.3: every (query, candidate) sequence begins with the same query): positions below
+// pre_len of a work item's sequence have their q/k rows stored once, at pre_row0 + position, for all sequences of the
+// launch; the K staging picks the row per key.  V^T needs no such case: every sequence's columns cover all its
+// positions.  The output row base is a field of its own (out_base), so that a launch can read q and k in one row layout
+// and write its output in another.
 #include <type_traits>
 
 #include "common.h"
@@ -34,9 +39,9 @@ static constexpr int BKV = 64;           // keys per staged tile
 #define PRISM_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
 template <typename OT, int G, int NW>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attention_16_kernel(const OT *__restrict__ QK, const f16 *__restrict__ Vt,
-                                                           int64_t vt_stride, const AttnTile *__restrict__ tiles,
-                                                           int nq, int nkv, OT *__restrict__ out) {
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void attention_16_kernel(const OT *__restrict__ QK, const f16 *__restrict__ Vt, int64_t vt_stride,
+                         const AttnTile *__restrict__ tiles, int nq, int nkv, OT *__restrict__ out) {
   typedef typename Mfma<OT>::vec8 vec8;
   typedef typename Mfma<OT>::vec4 vec4;
   constexpr int QB = NW / G;             // 32-query blocks per item
