@@ -292,9 +292,12 @@ def main():
         torch.cuda.synchronize()
         t5 = time.perf_counter()
         reps5 = []
+        step_ms5 = []
         for _ in range(2):
+            ts = time.perf_counter()
             idx5, scores5, rep5 = p5.select(q5, cands5, w5.K, report=True)
             reps5.append(rep5)
+            step_ms5.append(round((time.perf_counter() - ts) * 1e3, 1))
         torch.cuda.synchronize()
         ms5 = (time.perf_counter() - t5) / 2 * 1e3
         p5.destroy()
@@ -302,7 +305,7 @@ def main():
         cfg5_rec = {"workload": f"cfg5_8b_stream: {w5.n_cands} candidates, {int(sum(len(c) + len(q5) for c in cands5))} tokens, "
                                 f"layers streamed from pinned host memory ({'2' if not args.stream_slots else args.stream_slots} "
                                 f"buffers), chunks of {w5.chunk_cands} candidates, K={w5.K}",
-                    "topk_latency_ms": round(ms5, 3), "candidates_per_s": round(w5.n_cands / (ms5 / 1e3), 2), "steps": 2,
+                    "topk_latency_ms": round(ms5, 3), "candidates_per_s": round(w5.n_cands / (ms5 / 1e3), 2), "steps": 2, "step_ms": step_ms5,
                     "stream_GBps": round(rep5.bytes_streamed / rep5.ms_total / 1e6, 1), "bytes_streamed": int(rep5.bytes_streamed),
                     "peak_hbm_bytes_library": int(rep5.peak_hbm_bytes), "caller_device_bytes": caller,
                     "hbm_cap_bytes": int(w5.hbm_cap_bytes), "under_cap": bool(rep5.peak_hbm_bytes + caller <= w5.hbm_cap_bytes),

@@ -38,6 +38,18 @@ static constexpr int BKV = 64;           // keys per staged tile
 #define PRISM_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define PRISM_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
+// A lane's value and the value of lane l ^ 32, as an unordered pair: one register swap between the two half-waves (no
+// LDS round trip, nothing to wait for).  v_permlane32_swap exchanges the upper half of its first operand with the lower
+// half of its second; with the same value in both, the two results hold the lower half-wave's and the upper half-wave's
+// value in every lane.
+__device__ __forceinline__ void half_wave_pair(float x, float &lo, float &hi) {
+  typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+  const unsigned u = __float_as_uint(x);
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  lo = __uint_as_float(r[0]);
+  hi = __uint_as_float(r[1]);
+}
+
 template <typename OT, int G, int NW>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void attention_16_kernel(const OT *__restrict__ QK, const f16 *__restrict__ Vt, int64_t vt_stride,
@@ -81,30 +93,43 @@ void attention_16_kernel(const OT *__restrict__ QK, const f16 *__restrict__ Vt, 
   // touch all 64 banks.
   constexpr int NI = 16 / NW;
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-  const OT *gK[NI];                                   // + (seq_row0 + key) * row_elems
-  const f16 *gV[NI];                                  // + kt * BKV
+  // Byte offsets of this lane's chunks from the tile's first K row and first V^T column: fixed for the whole item, so
+  // a tile costs one wave-uniform base address per operand and no per-lane address arithmetic.
+  uint32_t oK[NI], oV[NI];
 #pragma unroll
   for (int j = 0; j < NI; ++j) {
     const int kr = (wave * NI + j) * 4 + (lane >> 4);
-    gK[j] = QK + (int64_t)(nq + kvh) * HD + (((lane & 15) ^ (kr & 15)) * 8);
+    oK[j] = ((uint32_t)kr * (uint32_t)row_elems + (uint32_t)(((lane & 15) ^ (kr & 15)) * 8)) * 2u;
     const int vr = (wave * NI + j) * 8 + (lane >> 3);
-    gV[j] = Vt + ((int64_t)kvh * HD + vr) * vt_stride + it.vt_col0 + (((lane & 7) ^ ((vr >> 1) & 7)) * 8);
+    oV[j] = ((uint32_t)vr * (uint32_t)vt_stride + (uint32_t)(((lane & 7) ^ ((vr >> 1) & 7)) * 8)) * 2u;   // < 4 GiB: checked by the launcher
   }
+  const char *const kcol = reinterpret_cast<const char *>(QK + (int64_t)(nq + kvh) * HD);
+  const char *const vrow = reinterpret_cast<const char *>(Vt + (int64_t)kvh * HD * vt_stride + it.vt_col0);
   auto stage_tile = [&](int kt, auto buf_tag) {
     constexpr int BUF = decltype(buf_tag)::value;
     OT *const lK = BUF ? lK1 : lK0;
     f16 *const lV = BUF ? lV1 : lV0;
+    const int k0 = kt * BKV;
+    if (k0 + BKV <= L && (k0 >= it.pre_len || k0 + BKV <= it.pre_len)) {
+      // all 64 keys exist and sit in one row range (the shared prefix or the sequence's own rows)
+      const char *kb = kcol + (int64_t)((k0 < it.pre_len ? it.pre_row0 : it.row_base) + k0) * row_elems * 2;
 #pragma unroll
-    for (int j = 0; j < NI; ++j) {
-      int key = kt * BKV + (wave * NI + j) * 4 + (lane >> 4);
-      key = key < L ? key : L - 1;
-      __builtin_amdgcn_global_load_lds(PRISM_GLOBAL_PTR(gK[j] + (int64_t)((key < it.pre_len ? it.pre_row0 : it.row_base) + key) * row_elems),
-                                       PRISM_LDS_PTR(&lK[(wave_u * NI + j) * 4 * HD]), 16, 0, 0);
+      for (int j = 0; j < NI; ++j)
+        __builtin_amdgcn_global_load_lds(PRISM_GLOBAL_PTR(kb + oK[j]), PRISM_LDS_PTR(&lK[(wave_u * NI + j) * 4 * HD]), 16, 0, 0);
+    } else {
+#pragma unroll
+      for (int j = 0; j < NI; ++j) {
+        const int kr = (wave * NI + j) * 4 + (lane >> 4);
+        int key = k0 + kr;
+        key = key < L ? key : L - 1;
+        const char *src = kcol + ((int64_t)((key < it.pre_len ? it.pre_row0 : it.row_base) + key) * row_elems + (((lane & 15) ^ (kr & 15)) * 8)) * 2;
+        __builtin_amdgcn_global_load_lds(PRISM_GLOBAL_PTR(src), PRISM_LDS_PTR(&lK[(wave_u * NI + j) * 4 * HD]), 16, 0, 0);
+      }
     }
+    const char *vb = vrow + (int64_t)k0 * 2;
 #pragma unroll
     for (int j = 0; j < NI; ++j)
-      __builtin_amdgcn_global_load_lds(PRISM_GLOBAL_PTR(gV[j] + kt * BKV),
-                                       PRISM_LDS_PTR(&lV[(wave_u * NI + j) * 8 * BKV]), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(PRISM_GLOBAL_PTR(vb + oV[j]), PRISM_LDS_PTR(&lV[(wave_u * NI + j) * 8 * BKV]), 16, 0, 0);
   };
 
   f32x16 o[HD / 32];
@@ -158,7 +183,11 @@ void attention_16_kernel(const OT *__restrict__ QK, const f16 *__restrict__ Vt, 
           }
           mx = fmaxf(mx, s[kb][e]);
         }
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      {
+        float lo, hi;
+        half_wave_pair(mx, lo, hi);
+        mx = fmaxf(lo, hi);
+      }
       const float m_new = fmaxf(m_run, mx);
       const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c_exp);
       const float mb = m_new * c_exp;
@@ -214,7 +243,9 @@ void attention_16_kernel(const OT *__restrict__ QK, const f16 *__restrict__ Vt, 
   }
 
   // ---- normalise and store: lane holds d = t*32 + (e/4)*8 + (lane/32)*4 + e%4 of query qi
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  float l_lo, l_hi;
+  half_wave_pair(l_run, l_lo, l_hi);
+  const float l_tot = l_lo + l_hi;
   if (qi < L) {
     const float inv = 1.0f / l_tot;
     OT *op = out + (int64_t)(it.out_base + qi) * nq * HD + (int64_t)hq * HD + (lane >> 5) * 4;
@@ -269,6 +300,9 @@ int launch_attention_16(int dtype, const void *QK, const void *Vt, int64_t vt_st
   PRISM_REQUIRE(attention_16_supported(nq, nkv, hd), PRISM_EUNSUPPORTED,
                 "attention: 16-bit modes need head_dim 128 and 1, 2, 4 or 8 query heads per KV head (got hd %d, %d/%d)", hd, nq, nkv);
   PRISM_REQUIRE(vt_stride % 8 == 0, PRISM_EINVAL, "attention: V^T row stride must be a multiple of 8");
+  // the kernel addresses the 128 V^T rows of a KV head with 32-bit byte offsets
+  PRISM_REQUIRE(vt_stride > 0 && (int64_t)HD * vt_stride * 2 < ((int64_t)1 << 32), PRISM_EUNSUPPORTED,
+                "attention: V^T row stride %lld too large (128 rows must stay below 4 GiB)", (long long)vt_stride);
   PRISM_REQUIRE((int64_t)n_tiles * nkv < (int64_t)1 << 31, PRISM_EINVAL, "attention: too many work items (%d x %d)", n_tiles, nkv);
   if (n_tiles == 0) return PRISM_OK;
   const int n_groups = n_tiles * nkv;

@@ -219,11 +219,12 @@ static size_t packed_layer_bytes(const prism_model &m, const LayerLayout &L, con
   return b;
 }
 
-// Fills layer slot `slot` with layer `layer` on stream s.  Plain weights: a handful of copies (device to device at
-// create, pinned host to device when streamed), then bf16 -> half in place if the operands are half.  4-bit weights:
-// the blobs (copied to the device first when they live on the host) are expanded into the slot, the norm gains
-// converted beside them.
-static int issue_layer_copy(prism_ctx *c, int layer, int slot, hipStream_t s, hipMemcpyKind kind, int64_t *bytes) {
+// Fills layer slot `slot` with layer `layer` on stream s, in two parts that can be issued apart.  kLayerTransfer: what
+// crosses the host link (pinned host to device when streamed; device to device at create; nothing for resident 4-bit
+// blobs).  kLayerFinish: the kernels that turn what arrived into operands - bf16 -> half in place if the operands are
+// half; 4-bit blobs expanded into the slot, the norm gains converted beside them.
+enum { kLayerTransfer = 1, kLayerFinish = 2, kLayerBoth = 3 };
+static int issue_layer_copy(prism_ctx *c, int layer, int slot, hipStream_t s, hipMemcpyKind kind, int64_t *bytes, int parts = kLayerBoth) {
   std::vector<CopyItem> items;
   layer_copy_items(c->m, c->lay, c->host_layers[layer], items);
   if (c->w4) {
@@ -233,22 +234,26 @@ static int issue_layer_copy(prism_ctx *c, int layer, int slot, hipStream_t s, hi
       const void *src = it.src;
       if (c->streamed) {
         char *land = c->packed_buf[slot] + poff;
-        PRISM_HIP(hipMemcpyAsync(land, it.src, sb, hipMemcpyHostToDevice, s));
+        if (parts & kLayerTransfer) {
+          PRISM_HIP(hipMemcpyAsync(land, it.src, sb, hipMemcpyHostToDevice, s));
+          if (bytes) *bytes += (int64_t)sb;
+        }
         src = land;
         poff += (size_t)round_up(sb, 256);
-        if (bytes) *bytes += (int64_t)sb;
       }
+      if (!(parts & kLayerFinish)) continue;
       if (it.K) PRISM_TRY(launch_dequantize_w4(src, (int)it.N, (int)it.K, c->op, c->layer_buf[slot] + it.dst_off, s));
       else PRISM_TRY(launch_convert_bf16(src, it.N, c->op, c->layer_buf[slot] + it.dst_off, s));
     }
     return PRISM_OK;
   }
-  for (const CopyItem &it : items) {
-    PRISM_HIP(hipMemcpyAsync(c->layer_buf[slot] + it.dst_off, it.src, it.bytes, kind, s));
-    if (bytes) *bytes += (int64_t)it.bytes;
-  }
+  if (parts & kLayerTransfer)
+    for (const CopyItem &it : items) {
+      PRISM_HIP(hipMemcpyAsync(c->layer_buf[slot] + it.dst_off, it.src, it.bytes, kind, s));
+      if (bytes) *bytes += (int64_t)it.bytes;
+    }
   // half operands: the bf16 weights become the same numbers in IEEE half, in place, on the same stream
-  if (c->op == PRISM_DTYPE_F16) PRISM_TRY(launch_bf16_to_f16(c->layer_buf[slot], c->lay.bytes / 2, s));
+  if ((parts & kLayerFinish) && c->op == PRISM_DTYPE_F16) PRISM_TRY(launch_bf16_to_f16(c->layer_buf[slot], c->lay.bytes / 2, s));
   return PRISM_OK;
 }
 
@@ -1029,13 +1034,25 @@ static int select_impl(prism_ctx *c, const int32_t *query_tokens, int32_t query_
   }
 
   int64_t bytes_streamed = 0, token_layers = 0;
+  // A layer's transfers and its finishing kernels (conversion or expansion, then the slot's ready event) are issued at
+  // different times: whatever waits for a transfer to complete is queued only after a full layer of compute kernels
+  // has been queued behind the transfer.  The side stream and the compute stream may be served by one hardware queue
+  // (the runtime maps streams onto a few of them, and which share one depends on what else the process has created); a
+  // queue is consumed in order, so a wait for the copy queued right behind it would hold back the compute kernels that
+  // follow, and the copy would not overlap anything.  With the wait a layer later the order in the shared queue is
+  // transfer, a layer of compute, wait: the overlap no longer depends on the mapping.
+  auto finish_layer = [&](int layer) -> int {
+    const int slot = layer % c->ring;
+    PRISM_TRY(issue_layer_copy(c, layer, slot, c->copy_stream, hipMemcpyHostToDevice, nullptr, kLayerFinish));
+    PRISM_HIP(hipEventRecord(c->ev_ready[slot], c->copy_stream));
+    return PRISM_OK;
+  };
   if (c->two_slot) {
     // Sec. 4.2: a ring of layer buffers (two in the paper); layer l computes from slot l % ring while the layers
     // after it arrive (or are expanded) in the others
-    for (int l = 0; l < std::min(c->ring, m.n_layers); ++l) {
-      PRISM_TRY(issue_layer_copy(c, l, l, c->copy_stream, hipMemcpyHostToDevice, &bytes_streamed));
-      PRISM_HIP(hipEventRecord(c->ev_ready[l], c->copy_stream));
-    }
+    for (int l = 0; l < std::min(c->ring, m.n_layers); ++l)
+      PRISM_TRY(issue_layer_copy(c, l, l, c->copy_stream, hipMemcpyHostToDevice, &bytes_streamed, kLayerTransfer));
+    for (int l = 0; l < std::min(c->ring - 1, m.n_layers); ++l) PRISM_TRY(finish_layer(l));
   }
 
   std::vector<int> early_idx;          // three-way mode: candidates selected before the end, in output order
@@ -1092,12 +1109,13 @@ static int select_impl(prism_ctx *c, const int32_t *query_tokens, int32_t query_
     if (timed) PRISM_HIP(hipEventRecord(c->ev_layer[4 * l + 1], s));
     token_layers += p.seq_tokens;
     layers_run = l + 1;
+    // this layer's kernels are queued: the layer that arrived last (the one the ring's newest slot holds) can be finished
+    if (c->two_slot && l + c->ring - 1 < m.n_layers) PRISM_TRY(finish_layer(l + c->ring - 1));
     auto release_slot = [&]() -> int {       // the layer's weights are no longer needed: the ring moves on
       if (c->two_slot && l + c->ring < m.n_layers) {
         PRISM_HIP(hipEventRecord(c->ev_free[slot], s));
         PRISM_HIP(hipStreamWaitEvent(c->copy_stream, c->ev_free[slot], 0));
-        PRISM_TRY(issue_layer_copy(c, l + c->ring, slot, c->copy_stream, hipMemcpyHostToDevice, &bytes_streamed));
-        PRISM_HIP(hipEventRecord(c->ev_ready[slot], c->copy_stream));
+        PRISM_TRY(issue_layer_copy(c, l + c->ring, slot, c->copy_stream, hipMemcpyHostToDevice, &bytes_streamed, kLayerTransfer));
       }
       return PRISM_OK;
     };
