@@ -223,10 +223,12 @@ def main():
     # the compute stream; with all kinds on that is about 1 % of the call).  The per-kind breakdown comes from extra,
     # untimed selects right after.
     DOM = 2        # the gate/up GEMM with the SwiGLU epilogue carries more than half of all flops
-    dom_reps = []
+    dom_reps, step_ms = [], []
     t0 = time.perf_counter()
     for _ in range(args.steps):
+        ts = time.perf_counter()
         idx, scores, rep = p.select(q, cands, w.K, report=True, kinds=[DOM])      # synchronous: results are on the host
+        step_ms.append((time.perf_counter() - ts) * 1e3)
         dom_reps.append(rep)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -327,7 +329,8 @@ def main():
                                f"weights {'4-bit (groups of 128) expanded to ' + op_t if args.w4 else m.dtype}, matrix-core operands {op_t}, "
                                f"fp32 accumulation and residual",
                    "n_cands": w.n_cands, "K": w.K, "seed": w.seed, "chunk_cands": w.chunk_cands, "stream_weights": w.stream_weights},
-        "topk_latency_ms": round(ms_per_step, 3),
+        "topk_latency_ms": round(ms_per_step, 3), "topk_latency_ms_median": round(float(np.median(step_ms)), 3),
+        "topk_latency_ms_min": round(min(step_ms), 3),
         "unpruned_latency_ms": None if unpruned_ms is None else round(unpruned_ms, 3),
         "gpu_ms": {"total": round(rep.ms_total, 3), "layers": round(rep.ms_layers, 3), "checks": round(rep.ms_checks, 3)},
         "survivors": {"layer": rep.layer.tolist(), "n_before": rep.n_before.tolist(), "n_after": rep.n_after.tolist()},

@@ -290,6 +290,18 @@ def test_attention(dtype, nq, nkv, hd, lens):
     np.testing.assert_allclose(_f64(out), ref, **tol)
 
 
+def test_attention_refuses_a_transposed_v_stride_beyond_its_32_bit_offsets():
+    """The 16-bit kernel addresses the 128 rows of a KV head's V^T with 32-bit byte offsets: a row stride of 2^24 columns
+    (128 rows x 2 bytes = 4 GiB) is refused before anything is launched (the buffers here are tiny and never touched)."""
+    nq, nkv, hd = 8, 2, 128
+    QK = torch.zeros(4, (nq + nkv) * hd, dtype=torch.float16, device=DEV)
+    Vt = torch.zeros(nkv, hd, 64, dtype=torch.float16, device=DEV)
+    out = torch.zeros(4, nq * hd, dtype=torch.float16, device=DEV)
+    with pytest.raises(B.PrismError) as e:
+        B.op_attention(B.DTYPE_F16, QK, Vt, 1 << 24, np.array([0, 4], np.int32), np.array([0], np.int32), nq, nkv, hd, out)
+    assert e.value.code == B.EUNSUPPORTED
+
+
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_score(dtype):
     H, T = 1024, 500

@@ -113,6 +113,35 @@ def test_chunked_execution_and_streamed_weights_change_nothing(name):
         assert deep[2].bytes_streamed == streamed[2].bytes_streamed
 
 
+@pytest.mark.parametrize("name", ["mini_fp32", "mini_bf16"])
+def test_streamed_context_beside_a_resident_one(name):
+    """Two live contexts on one stream, one with resident layers and one streaming them (a ring of 2 and of 3 buffers):
+    calls alternate between them and every call gives the resident context's results.  (Side streams of several contexts
+    may be served by one hardware queue; the order in which a layer's transfers and its finishing kernels are queued
+    must not depend on that.)"""
+    w = W.WORKLOADS[name]
+    q, cands = W.make_tokens(w)
+    wt = W.make_weights(w, "cuda")
+    host = W.make_weights(w, "cpu")
+    for l in host.layers:
+        for k in l:
+            l[k] = l[k].pin_memory()
+    mixed = W.Weights(wt.embed, host.layers, wt.final_norm)
+    opts = dict(checkpoints=w.checkpoints, cv_threshold=w.cv_threshold, n_clusters=w.n_clusters)
+    resident = B.Prism(w.model, wt, **opts)
+    streamed = [B.Prism(w.model, mixed, stream_weights=True, stream_slots=s, **opts) for s in (0, 3)]
+    base = resident.select(q, cands, w.K)
+    for _ in range(2):
+        for p in streamed:
+            got = p.select(q, cands, w.K)
+            assert got[0].tolist() == base[0].tolist() and np.array_equal(got[1], base[1])
+            assert np.array_equal(got[2].scores, base[2].scores, equal_nan=True)
+        again = resident.select(q, cands, w.K)
+        assert again[0].tolist() == base[0].tolist() and np.array_equal(again[1], base[1])
+    for p in streamed + [resident]:
+        p.destroy()
+
+
 def test_three_way_mode_matches_oracle():
     w = W.WORKLOADS["mini_fp32"]
     q, cands = W.make_tokens(w)
