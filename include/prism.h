@@ -190,7 +190,9 @@ typedef struct {
 } prism_report;
 
 /* Build a context.  Device-resident layer weights are repacked once into library-owned HBM
- * (fused [wq;wk;wv] and [w_gate;w_up] operands); pinned-host layer weights are borrowed and
+ * (fused [wq;wk;wv] and [w_gate;w_up] operands): plain (not 4-bit) device-resident layer tensors are
+ * not read again after prism_create returns, so a caller short of memory may release its own copies
+ * then instead of holding the layers twice; pinned-host layer weights are borrowed and
  * read asynchronously by every prism_select, so they must stay mapped and unmodified until
  * prism_destroy.  embed, final_norm, w_yes, w_no are borrowed in place.  The option arrays
  * are copied. */

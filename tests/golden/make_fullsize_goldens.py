@@ -2,6 +2,7 @@
 4B- and 8B-shaped benchmark workloads.  CPU only; calls nothing but oracle/ and the seeded input generator.
 
     python tests/golden/make_fullsize_goldens.py cfg3_4b drop_only
+    python tests/golden/make_fullsize_goldens.py cfg3_4b three_way
     python tests/golden/make_fullsize_goldens.py cfg4_8b drop_only
     python tests/golden/make_fullsize_goldens.py cfg4_8b three_way
     python tests/golden/make_fullsize_goldens.py cfg5_8b_stream drop_only

@@ -271,6 +271,17 @@ def test_cfg4_three_way_against_the_complete_oracle_run(weights_8b):
     _progress(f"cfg4 three-way: stops after layer {rep.layers_run}, worst |gpu - oracle| {worst:.3e}, top-K {idx.tolist()}")
 
 
+def test_cfg3_three_way_against_the_complete_oracle_run():
+    """The same comparison on the 4B shape (ragged lengths, hidden 2560: other tile counts and tails on the
+    hand-scheduled GEMM path)."""
+    w = W.WORKLOADS["cfg3_4b"]
+    gold = _need(w.name, "three_way")
+    idx, scores, rep = _run_gpu(w, W.make_weights(w, "cuda"), mode=B.MODE_THREE_WAY)
+    assert rep.layers_run == gold.layers_run
+    worst = _three_way_fates_and_output(w, idx, scores, rep, gold)
+    _progress(f"cfg3 three-way: stops after layer {rep.layers_run}, worst |gpu - oracle| {worst:.3e}, top-K {idx.tolist()}")
+
+
 def test_cfg5_streamed_chunked_under_the_hbm_cap(weights_8b):
     """500 candidates, log-normal lengths, weights streamed from pinned host memory one layer ahead,
     chunks of 64 candidates, 24 GB cap on library-owned device memory."""

@@ -128,6 +128,32 @@ def test_gemm_16_big_tile_with_a_ragged_last_column_tile(dtype, epi):
 
 
 @pytest.mark.parametrize("dtype", SIXTEEN)
+@pytest.mark.parametrize("epi", [B.EPI_STORE, B.EPI_RESIDUAL, B.EPI_SWIGLU])
+def test_gemm_16_rows_beyond_whole_rounds_go_to_small_tiles_with_the_same_bits(dtype, epi):
+    """2900 x 6144 outputs are 12 x 24 = 288 tiles of 256 x 256: one round of 256 compute units and a few tiles more.  The
+    launcher gives the first 10 row tiles (240 tiles, one round) to the big tile and the last 340 rows to a second launch
+    with 128 x 128 tiles.  Checked against the oracle, and bit for bit against the same rows computed by the small tile
+    alone (2560 rows are 240 big tiles, too few for the big tile: that launch takes the small one)."""
+    M, N, K, cut = 2900, 6144, 320, 2560
+    _gemm_16_case(dtype, epi, M, N, K)
+    A = _rand((M, K), dtype, 10 + M + K, 1.0).to(DEV)
+    Wt = _rand((N, K), dtype, 20 + N + K, 1.0 / math.sqrt(K)).to(DEV)
+    cols = N // 2 if epi == B.EPI_SWIGLU else N
+
+    def fresh(rows):
+        if epi == B.EPI_RESIDUAL:
+            return _rand((M, N), torch.float32, 30, 1.0)[rows].to(DEV).clone()
+        return torch.zeros(len(range(M)[rows]), cols, dtype=dtype, device=DEV)
+    whole = fresh(slice(0, M))
+    B.op_gemm(epi, A, Wt, whole)
+    top, bottom = fresh(slice(0, cut)), fresh(slice(cut, M))
+    B.op_gemm(epi, A[:cut].contiguous(), Wt, top)
+    B.op_gemm(epi, A[cut:].contiguous(), Wt, bottom)
+    torch.cuda.synchronize()
+    assert torch.equal(whole[:cut], top) and torch.equal(whole[cut:], bottom)
+
+
+@pytest.mark.parametrize("dtype", SIXTEEN)
 def test_gemm_16_fp32_output(dtype):
     M, N, K = 700, 6144, 1024
     A, Wt = _rand((M, K), dtype, 5), _rand((N, K), dtype, 6, 1.0 / math.sqrt(K))

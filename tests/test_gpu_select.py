@@ -142,6 +142,25 @@ def test_streamed_context_beside_a_resident_one(name):
         p.destroy()
 
 
+@pytest.mark.parametrize("name", ["mini_fp32", "mini_bf16"])
+def test_resident_layers_are_not_read_after_create(name):
+    """Plain device-resident layer tensors are repacked into library-owned memory by prism_create: the caller's copies can
+    be overwritten (or released) afterwards without changing any result."""
+    w = W.WORKLOADS[name]
+    q, cands = W.make_tokens(w)
+    base = run(w)
+    wt = W.make_weights(w, "cuda")
+    p = B.Prism(w.model, wt, checkpoints=w.checkpoints, cv_threshold=w.cv_threshold, n_clusters=w.n_clusters)
+    for l in wt.layers:
+        for t in l.values():
+            t.fill_(float("nan"))
+    torch.cuda.synchronize()
+    got = p.select(q, cands, w.K)
+    p.destroy()
+    assert got[0].tolist() == base[0].tolist() and np.array_equal(got[1], base[1])
+    assert np.array_equal(got[2].scores, base[2].scores, equal_nan=True)
+
+
 def test_three_way_mode_matches_oracle():
     w = W.WORKLOADS["mini_fp32"]
     q, cands = W.make_tokens(w)
