@@ -509,35 +509,37 @@ static int launch_cfg(const OT *A, const OT *W, void *out, int M, int N, int K, 
   return PRISM_OK;
 }
 
-// Cost of the small tile relative to the big one, per tile: a quarter of the work at about two thirds of the rate
-// (the 128 x 128 loop is compiler-scheduled).  Only used to decide where a launch is split, never for results.
-static constexpr double kSmallTileCost = 0.4;
+// Cost of a round of small tiles relative to a round of big ones: a quarter of the work at about two thirds of the rate
+// (the 128 x 128 loop is compiler-scheduled).  Only used to decide how a launch is tiled, never for results.
+#ifndef PRISM_SMALL_TILE_COST
+#define PRISM_SMALL_TILE_COST 0.4
+#endif
 
 template <typename OT, int EPI>
 static int launch_epi(const OT *A, const OT *W, void *out, int M, int N, int K, hipStream_t s) {
-  // big tile when there is enough work to fill 256 CUs with it, else a 128x128 tile
-  const int ncols = EPI == PRISM_EPI_SWIGLU ? N / 2 : N;
-  const int nN = cdiv(ncols, EPI == PRISM_EPI_SWIGLU ? 128 : 256), nM = cdiv(M, 256);
-  const int64_t big_tiles = (int64_t)nM * nN;
-  if (big_tiles < 256) return launch_cfg<OT, 128, 128, 2, 2, EPI>(A, W, out, M, N, K, s);
   // A launch runs its tiles in rounds of one per compute unit, and a last round that fills only a few of them costs a
-  // whole tile's time.  Rows are independent and both tile sizes give a row the same bits, so when it pays the bottom
-  // rows go to a second launch with small tiles: the big tiles then fill whole rounds and the remainder is spread over
-  // all compute units in quarter-size pieces.
+  // whole tile's time.  Rows are independent and both tile sizes give a row the same bits, so the launcher compares three
+  // ways of tiling by their rounds: small tiles only, big tiles only, or the row tiles that fill whole rounds with big
+  // tiles and the remaining rows in a second launch with small ones.
   constexpr int kCus = 256;
+  constexpr bool kGlu = EPI == PRISM_EPI_SWIGLU;
+  const int ncols = kGlu ? N / 2 : N;
+  const int nN = cdiv(ncols, kGlu ? 128 : 256), nM = cdiv(M, 256), nN_small = cdiv(ncols, kGlu ? 64 : 128);
+  const int64_t big_tiles = (int64_t)nM * nN;
+  const double cost_small = PRISM_SMALL_TILE_COST * (double)cdiv((int64_t)cdiv(M, 128) * nN_small, kCus);
+  const double cost_big = (double)cdiv(big_tiles, kCus);
   const int full_rounds = (int)(big_tiles / kCus);
   const int rows_big = (int)std::min<int64_t>(nM, (int64_t)full_rounds * kCus / nN);      // row tiles that fit whole rounds
   const int rest_rows = M - rows_big * 256;
-  if (full_rounds >= 1 && rows_big >= 1 && rest_rows > 0) {
-    const int64_t small_tiles = (int64_t)cdiv(rest_rows, 128) * cdiv(ncols, EPI == PRISM_EPI_SWIGLU ? 64 : 128);
-    const double whole = (double)cdiv(big_tiles, kCus);
-    const double split = (double)cdiv((int64_t)rows_big * nN, kCus) + kSmallTileCost * (double)cdiv(small_tiles, kCus);
-    if (split < whole - 0.05) {
-      const size_t out_elem = EPI == PRISM_EPI_RESIDUAL || EPI == PRISM_EPI_STORE_F32 ? 4 : 2;
-      PRISM_TRY((launch_cfg<OT, 256, 256, 2, 2, EPI>(A, W, out, rows_big * 256, N, K, s)));
-      return launch_cfg<OT, 128, 128, 2, 2, EPI>(A + (size_t)rows_big * 256 * K, W,
-                                                  reinterpret_cast<char *>(out) + (size_t)rows_big * 256 * ncols * out_elem, rest_rows, N, K, s);
-    }
+  double cost_split = 1e30;
+  if (rows_big >= 1 && rest_rows > 0)
+    cost_split = (double)cdiv((int64_t)rows_big * nN, kCus) + PRISM_SMALL_TILE_COST * (double)cdiv((int64_t)cdiv(rest_rows, 128) * nN_small, kCus);
+  if (cost_small <= cost_big && cost_small <= cost_split) return launch_cfg<OT, 128, 128, 2, 2, EPI>(A, W, out, M, N, K, s);
+  if (cost_split < cost_big - 0.05) {
+    const size_t out_elem = EPI == PRISM_EPI_RESIDUAL || EPI == PRISM_EPI_STORE_F32 ? 4 : 2;
+    PRISM_TRY((launch_cfg<OT, 256, 256, 2, 2, EPI>(A, W, out, rows_big * 256, N, K, s)));
+    return launch_cfg<OT, 128, 128, 2, 2, EPI>(A + (size_t)rows_big * 256 * K, W,
+                                                reinterpret_cast<char *>(out) + (size_t)rows_big * 256 * ncols * out_elem, rest_rows, N, K, s);
   }
   return launch_cfg<OT, 256, 256, 2, 2, EPI>(A, W, out, M, N, K, s);
 }
