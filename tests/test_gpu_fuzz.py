@@ -1,6 +1,7 @@
 """Seeded differential test of prism_select against the oracle over the option space: pool size, ragged lengths, K,
-routing mode, number of clusters, dispersion threshold, checkpoint subset, chunk size, and the memory modes (which must
-not change any number).  Small models so that the oracle finishes in a fraction of a second per case."""
+routing mode, number of clusters, dispersion threshold, checkpoint subset, chunk size, and the memory modes (hidden-state
+offload, embedding cache, layers streamed from pinned host memory through a ring of 2 to 5 buffers), which must not change
+any number.  Small models so that the oracle finishes in a fraction of a second per case."""
 import dataclasses
 
 import numpy as np
@@ -17,13 +18,19 @@ pytestmark = pytest.mark.gpu
 
 
 class _HostEmbed:
-    def __init__(self, wt):
+    def __init__(self, wt, layers):
         self.embed = wt.embed.cpu().pin_memory()
-        self.layers, self.final_norm = wt.layers, wt.final_norm
+        self.layers, self.final_norm = layers, wt.final_norm
         self.w_yes, self.w_no = wt.w_yes.clone(), wt.w_no.clone()
 
 
-_WEIGHTS = {}
+_WEIGHTS, _HOST_LAYERS = {}, {}
+
+
+def _host_layers(name):
+    if name not in _HOST_LAYERS:
+        _HOST_LAYERS[name] = [{k: v.cpu().pin_memory() for k, v in l.items()} for l in _weights(name).layers]
+    return _HOST_LAYERS[name]
 
 
 def _weights(name):
@@ -54,12 +61,17 @@ def test_random_options_match_the_oracle(seed):
     cache = bool(rng.integers(0, 2))
     w = dataclasses.replace(base, K=K, checkpoints=ck, cv_threshold=tau, n_clusters=k)
     wt = _weights(name)
-    p = B.Prism(m, _HostEmbed(wt) if cache else wt, checkpoints=ck, cv_threshold=tau, n_clusters=k, mode=mode,
-                chunk_cands=chunk, offload_hidden=offload, embed_on_host=cache, embed_cache_rows=int(rng.integers(1, 40)) if cache else 0)
+    cache_rows = int(rng.integers(1, 40)) if cache else 0
+    stream = bool(rng.integers(0, 2))                     # (drawn last: the cases above keep their earlier options)
+    slots = int(rng.choice([0, 3, 5]))
+    layers_arg = _host_layers(name) if stream else wt.layers
+    weights = _HostEmbed(wt, layers_arg) if cache else (W.Weights(wt.embed, layers_arg, wt.final_norm) if stream else wt)
+    p = B.Prism(m, weights, checkpoints=ck, cv_threshold=tau, n_clusters=k, mode=mode, chunk_cands=chunk, offload_hidden=offload,
+                embed_on_host=cache, embed_cache_rows=cache_rows, stream_weights=stream, stream_slots=slots)
     idx, scores, rep = p.select(q, cands, K)
     p.destroy()
     ref = oracle_select(w, wt, (q, cands), mode=mode)
-    desc = dict(n=n, K=K, mode=mode, ck=ck, tau=tau, k=k, chunk=chunk, offload=offload, cache=cache)
+    desc = dict(n=n, K=K, mode=mode, ck=ck, tau=tau, k=k, chunk=chunk, offload=offload, cache=cache, stream=stream, slots=slots)
     assert len(idx) == min(K, n), desc
     if mode == B.MODE_THREE_WAY:
         assert sorted(idx.tolist()) == sorted(ref.idx.tolist()), desc
