@@ -6,6 +6,7 @@
     python tests/golden/make_fullsize_goldens.py cfg4_8b drop_only
     python tests/golden/make_fullsize_goldens.py cfg4_8b three_way
     python tests/golden/make_fullsize_goldens.py cfg5_8b_stream drop_only
+    python tests/golden/make_fullsize_goldens.py cfg5_8b_stream three_way
 
 Each takes 10 to 60 minutes on eight host cores.  What is stored, per scoring event (every evaluated pruning
 check of Sec. 4.1, plus the final scoring): the layer, the live candidates, their fp64 scores, the fates

@@ -294,6 +294,18 @@ def test_cfg5_streamed_chunked_under_the_hbm_cap(weights_8b):
     assert rep.bytes_streamed >= w.model.n_layers * per_layer
 
 
+def test_cfg5_three_way_streamed_chunked_against_the_complete_oracle_run(weights_8b):
+    """Three-way routing with early termination on the 500-candidate pool: layers streamed, chunks of 64 that are regrouped
+    as candidates leave in both directions (selected upwards, dropped downwards)."""
+    w = W.WORKLOADS["cfg5_8b_stream"]
+    gold = _need(w.name, "three_way")
+    idx, scores, rep = _run_gpu(w, weights_8b, mode=B.MODE_THREE_WAY)
+    assert rep.layers_run == gold.layers_run
+    worst = _three_way_fates_and_output(w, idx, scores, rep, gold)
+    _progress(f"cfg5 three-way: stops after layer {rep.layers_run}, worst |gpu - oracle| {worst:.3e}, "
+              f"{rep.bytes_streamed / 1e9:.1f} GB streamed, top-K {idx.tolist()}")
+
+
 def test_cfg5_offload_and_embedding_cache_are_bit_identical_and_leaner(weights_8b):
     """The 500-candidate pool again with the residual stream in pinned host memory (three chunks on the device) and the
     embedding table behind a device cache of a tenth of its rows: same numbers as the run the previous test compares
