@@ -161,6 +161,38 @@ def test_resident_layers_are_not_read_after_create(name):
     assert np.array_equal(got[2].scores, base[2].scores, equal_nan=True)
 
 
+def test_contexts_on_different_streams_run_concurrently_from_two_threads():
+    """A context is single-caller, but different contexts may run at the same time: two host threads, each with its own
+    context on its own stream (one fp32, one 16-bit; the binding releases the interpreter lock during a call), repeat
+    their selections side by side and get what they get alone."""
+    import threading
+    jobs = []
+    for name in ("mini_fp32", "mini_bf16"):
+        w = W.WORKLOADS[name]
+        jobs.append((w, W.make_weights(w, "cuda"), W.make_tokens(w), run(w)))
+    torch.cuda.synchronize()
+    errors = []
+
+    def worker(w, wt, toks, base):
+        try:
+            st = torch.cuda.Stream()
+            p = B.Prism(w.model, wt, checkpoints=w.checkpoints, cv_threshold=w.cv_threshold, n_clusters=w.n_clusters,
+                        stream=st.cuda_stream)
+            for _ in range(12):
+                got = p.select(toks[0], toks[1], w.K)
+                assert got[0].tolist() == base[0].tolist() and np.array_equal(got[1], base[1])
+                assert np.array_equal(got[2].scores, base[2].scores, equal_nan=True)
+            p.destroy()
+        except Exception as e:           # noqa: BLE001 - reported by the main thread
+            errors.append((w.name, repr(e)))
+    threads = [threading.Thread(target=worker, args=j) for j in jobs]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+
+
 def test_three_way_mode_matches_oracle():
     w = W.WORKLOADS["mini_fp32"]
     q, cands = W.make_tokens(w)
