@@ -302,6 +302,8 @@ def main():
             step_ms5.append(round((time.perf_counter() - ts) * 1e3, 1))
         torch.cuda.synchronize()
         ms5 = (time.perf_counter() - t5) / 2 * 1e3
+        # one more select, not timed, with the copies of the streamed layers bracketed by events on the side stream
+        rep5x = p5.select(q5, cands5, w5.K, report=True, kinds=[B.KIND_TRANSFERS])[2]
         p5.destroy()
         caller = int(wt_for_oracle.embed.numel() * 2 + wt_for_oracle.final_norm.numel() * 2)
         cfg5_rec = {"workload": f"cfg5_8b_stream: {w5.n_cands} candidates, {int(sum(len(c) + len(q5) for c in cands5))} tokens, "
@@ -309,6 +311,11 @@ def main():
                                 f"buffers), chunks of {w5.chunk_cands} candidates, K={w5.K}",
                     "topk_latency_ms": round(ms5, 3), "candidates_per_s": round(w5.n_cands / (ms5 / 1e3), 2), "steps": 2, "step_ms": step_ms5,
                     "stream_GBps": round(rep5.bytes_streamed / rep5.ms_total / 1e6, 1), "bytes_streamed": int(rep5.bytes_streamed),
+                    # the host link while it is in use (HIP events on the side stream around each layer's copies), next to
+                    # PCIe Gen5 x16's 64 GB/s; stream_GBps above is the same bytes over the whole call
+                    "host_link": {"GBps_while_copying": round(rep5x.bytes_streamed / max(rep5x.ms_transfers, 1e-9) / 1e6, 1),
+                                  "peak_GBps": 64.0, "ms_copying": round(rep5x.ms_transfers, 1),
+                                  "measured_on": "one more select after the timed ones"},
                     "peak_hbm_bytes_library": int(rep5.peak_hbm_bytes), "caller_device_bytes": caller,
                     "hbm_cap_bytes": int(w5.hbm_cap_bytes), "under_cap": bool(rep5.peak_hbm_bytes + caller <= w5.hbm_cap_bytes),
                     "survivors": rep5.n_after.tolist(), "kernels": kind_table(reps5), "mfma_utilisation": utilisation(reps5),

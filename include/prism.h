@@ -187,7 +187,14 @@ typedef struct {
    * compute stream (about 3 ms per call at 36 layers with all kinds on), so a caller that times the call as a whole
    * can restrict the spans to the kinds it reads; the other kinds' totals then stay 0. */
   int32_t  kind_mask;
+  /* out, only when kind_mask has PRISM_KIND_MASK_TRANSFERS set (it is not part of "0 means all"): time the side stream
+   * spent moving streamed layer weights over the host link, summed over the layers, first copy start to last copy end
+   * (HIP events on that stream); bytes_streamed / ms_transfers is the rate of the link while it is in use.  The records
+   * behind the copies can delay compute kernels that share the side stream's hardware queue, so a call timed this way
+   * is not the call to take the latency from.  0 otherwise. */
+  double   ms_transfers;
 } prism_report;
+#define PRISM_KIND_MASK_TRANSFERS (1 << 8)
 
 /* Build a context.  Device-resident layer weights are repacked once into library-owned HBM
  * (fused [wq;wk;wv] and [w_gate;w_up] operands): plain (not 4-bit) device-resident layer tensors are

@@ -19,6 +19,7 @@ DTYPE_FP32, DTYPE_BF16, DTYPE_F16 = 0, 1, 2
 MODE_DROP_ONLY, MODE_THREE_WAY, MODE_NO_PRUNING = 0, 1, 2
 EPI_STORE, EPI_RESIDUAL, EPI_SWIGLU, EPI_STORE_F32 = 0, 1, 2, 3
 FATE_NOT_LIVE, FATE_DROPPED, FATE_DEFERRED, FATE_SELECTED = -1, 0, 1, 2
+KIND_TRANSFERS = 8          # bit of prism_report.kind_mask that asks for ms_transfers (PRISM_KIND_MASK_TRANSFERS)
 MAX_CANDS, MAX_CLUSTERS, MAX_SEQ = 4096, 8, 8192
 
 EXPORTS = ["prism_create", "prism_select", "prism_set_forced_keep", "prism_destroy", "prism_strerror",
@@ -69,7 +70,7 @@ class prism_report(C.Structure):
                 ("kind_flops", C.c_double * 6), ("bytes_hidden_moved", C.c_int64), ("embed_rows_hit", C.c_int64),
                 ("embed_rows_missed", C.c_int64), ("span_cap", C.c_int32), ("n_spans", C.c_int32),
                 ("span_kind", C.POINTER(C.c_int32)), ("span_rows", C.POINTER(C.c_int32)), ("span_ms", C.POINTER(C.c_float)),
-                ("span_flops", C.POINTER(C.c_double)), ("kind_mask", C.c_int32)]
+                ("span_flops", C.POINTER(C.c_double)), ("kind_mask", C.c_int32), ("ms_transfers", C.c_double)]
 
 
 _lib = None
@@ -160,6 +161,7 @@ class Report:
     bytes_hidden_moved: int = 0
     embed_rows_hit: int = 0
     embed_rows_missed: int = 0
+    ms_transfers: float = 0.0   # side-stream time spent copying streamed layer weights
     spans: Optional[np.ndarray] = None   # per launch, in order: structured array (kind, rows, ms, flops); None unless asked for
 
 
@@ -201,7 +203,7 @@ class Prism:
 
     def select(self, query_tokens, cand_tokens: Sequence, K: int, report: bool = True, spans: int = 0, kinds=None):
         """spans: capacity of the per-launch detail of the report (0 = none).  kinds: the kernel kinds that get event spans
-        (iterable of kind numbers; None = all)."""
+        (iterable of kind numbers; None = all); KIND_TRANSFERS in it additionally times the streamed layers' copies."""
         q, qp = _i32_array(query_tokens)
         cands = [np.ascontiguousarray(c, dtype=np.int32) for c in cand_tokens]
         n = len(cands)
@@ -243,7 +245,7 @@ class Prism:
                        arrs["scores"][:e], arrs["fate"][:e], rep.ms_total, rep.ms_layers, rep.ms_checks,
                        rep.token_layers, rep.peak_hbm_bytes, rep.bytes_streamed, rep.layers_run,
                        list(rep.kind_launches), list(rep.kind_ms), list(rep.kind_flops), rep.bytes_hidden_moved,
-                       rep.embed_rows_hit, rep.embed_rows_missed)
+                       rep.embed_rows_hit, rep.embed_rows_missed, rep.ms_transfers)
             if spans > 0:
                 n = rep.n_spans
                 r.spans = np.rec.fromarrays([sp["kind"][:n], sp["rows"][:n], sp["ms"][:n], sp["flops"][:n]],

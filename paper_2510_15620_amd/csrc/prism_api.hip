@@ -106,6 +106,7 @@ struct prism_ctx {
   std::vector<hipEvent_t> ev_ready, ev_free;      // per ring slot
   hipEvent_t ev_t[4] = {nullptr, nullptr, nullptr, nullptr};
   std::vector<hipEvent_t> ev_layer;               // 4 per layer (two intervals: a layer may run in two passes), for the report
+  std::vector<hipEvent_t> ev_xfer;                // 2 per layer on the side stream around a streamed layer's transfers, for the report
   // per-launch spans for the report: events come from a pool that only grows
   struct Span { int kind; hipEvent_t a, b; double flops; int rows; };
   std::vector<hipEvent_t> ev_pool; size_t ev_used = 0;
@@ -429,6 +430,7 @@ extern "C" void prism_destroy(prism_ctx *c) {
   for (hipEvent_t e : c->ev_free) if (e) (void)hipEventDestroy(e);
   for (int i = 0; i < 4; ++i) if (c->ev_t[i]) (void)hipEventDestroy(c->ev_t[i]);
   for (hipEvent_t e : c->ev_layer) if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : c->ev_xfer) if (e) (void)hipEventDestroy(e);
   for (hipEvent_t e : c->ev_pool) if (e) (void)hipEventDestroy(e);
   if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
   if (c->own_stream && c->stream) (void)hipStreamDestroy(c->stream);
@@ -1008,6 +1010,15 @@ static int select_impl(prism_ctx *c, const int32_t *query_tokens, int32_t query_
   c->span_mask = timed && rep->kind_mask ? rep->kind_mask : ~0;
   c->spans.clear();
   c->ev_used = 0;
+  // opt-in: the end-of-transfer records wait for the copies in the side stream's hardware queue, which holds back compute
+  // kernels behind them if the compute stream shares that queue
+  const bool timed_xfer = timed && c->streamed && (rep->kind_mask & PRISM_KIND_MASK_TRANSFERS) != 0;
+  if (timed_xfer && (int)c->ev_xfer.size() < 2 * m.n_layers) {
+    const size_t old = c->ev_xfer.size();
+    c->ev_xfer.resize(2 * m.n_layers, nullptr);
+    for (size_t i = old; i < c->ev_xfer.size(); ++i) PRISM_HIP(hipEventCreate(&c->ev_xfer[i]));
+  }
+  int n_xfer_timed = 0;
   if (timed && (int)c->ev_layer.size() < 4 * m.n_layers) {
     const size_t old = c->ev_layer.size();
     c->ev_layer.resize(4 * m.n_layers, nullptr);
@@ -1041,6 +1052,12 @@ static int select_impl(prism_ctx *c, const int32_t *query_tokens, int32_t query_
   // queue is consumed in order, so a wait for the copy queued right behind it would hold back the compute kernels that
   // follow, and the copy would not overlap anything.  With the wait a layer later the order in the shared queue is
   // transfer, a layer of compute, wait: the overlap no longer depends on the mapping.
+  auto transfer_layer = [&](int layer, int slot) -> int {
+    if (timed_xfer) PRISM_HIP(hipEventRecord(c->ev_xfer[2 * layer], c->copy_stream));
+    PRISM_TRY(issue_layer_copy(c, layer, slot, c->copy_stream, hipMemcpyHostToDevice, &bytes_streamed, kLayerTransfer));
+    if (timed_xfer) { PRISM_HIP(hipEventRecord(c->ev_xfer[2 * layer + 1], c->copy_stream)); n_xfer_timed = layer + 1; }
+    return PRISM_OK;
+  };
   auto finish_layer = [&](int layer) -> int {
     const int slot = layer % c->ring;
     PRISM_TRY(issue_layer_copy(c, layer, slot, c->copy_stream, hipMemcpyHostToDevice, nullptr, kLayerFinish));
@@ -1050,8 +1067,7 @@ static int select_impl(prism_ctx *c, const int32_t *query_tokens, int32_t query_
   if (c->two_slot) {
     // Sec. 4.2: a ring of layer buffers (two in the paper); layer l computes from slot l % ring while the layers
     // after it arrive (or are expanded) in the others
-    for (int l = 0; l < std::min(c->ring, m.n_layers); ++l)
-      PRISM_TRY(issue_layer_copy(c, l, l, c->copy_stream, hipMemcpyHostToDevice, &bytes_streamed, kLayerTransfer));
+    for (int l = 0; l < std::min(c->ring, m.n_layers); ++l) PRISM_TRY(transfer_layer(l, l));
     for (int l = 0; l < std::min(c->ring - 1, m.n_layers); ++l) PRISM_TRY(finish_layer(l));
   }
 
@@ -1115,7 +1131,7 @@ static int select_impl(prism_ctx *c, const int32_t *query_tokens, int32_t query_
       if (c->two_slot && l + c->ring < m.n_layers) {
         PRISM_HIP(hipEventRecord(c->ev_free[slot], s));
         PRISM_HIP(hipStreamWaitEvent(c->copy_stream, c->ev_free[slot], 0));
-        PRISM_TRY(issue_layer_copy(c, l + c->ring, slot, c->copy_stream, hipMemcpyHostToDevice, &bytes_streamed, kLayerTransfer));
+        PRISM_TRY(transfer_layer(l + c->ring, slot));
       }
       return PRISM_OK;
     };
@@ -1281,6 +1297,12 @@ static int select_impl(prism_ctx *c, const int32_t *query_tokens, int32_t query_
       }
     }
     rep->ms_layers = ml;
+    double mx = 0.0;
+    for (int l = 0; l < n_xfer_timed; ++l) {
+      PRISM_HIP(hipEventElapsedTime(&ms, c->ev_xfer[2 * l], c->ev_xfer[2 * l + 1]));
+      mx += ms;
+    }
+    rep->ms_transfers = mx;
     rep->ms_checks = ms_checks;
     rep->token_layers = token_layers;
     rep->peak_hbm_bytes = c->bytes_peak;

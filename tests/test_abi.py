@@ -38,7 +38,7 @@ def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(binding.prism_layer_weights) == 11 * 8
     assert ctypes.sizeof(binding.prism_weights) == 7 * 8
     assert ctypes.sizeof(binding.prism_options) == 8 + 4 * 6 + 8 + 8 + 4 * 6     # six trailing int32
-    assert ctypes.sizeof(binding.prism_report) == 3 * 4 + 4 + 10 * 8 + 3 * 8 + 3 * 8 + 4 + 6 * 4 + 4 + 6 * 8 + 6 * 8 + 3 * 8 + 2 * 4 + 4 * 8 + 8   # kind_mask (int32) + tail padding
+    assert ctypes.sizeof(binding.prism_report) == 3 * 4 + 4 + 10 * 8 + 3 * 8 + 3 * 8 + 4 + 6 * 4 + 4 + 6 * 8 + 6 * 8 + 3 * 8 + 2 * 4 + 4 * 8 + 8 + 8   # kind_mask (int32) + padding, ms_transfers
 
 
 def test_strerror_and_argument_errors_without_a_gpu(built):

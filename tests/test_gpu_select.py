@@ -138,6 +138,12 @@ def test_streamed_context_beside_a_resident_one(name):
             assert np.array_equal(got[2].scores, base[2].scores, equal_nan=True)
         again = resident.select(q, cands, w.K)
         assert again[0].tolist() == base[0].tolist() and np.array_equal(again[1], base[1])
+    # the copies of the streamed layers are timed on request only (the records behind them may hold back compute kernels
+    # in a shared hardware queue): same results, a positive copy time, and none reported otherwise
+    timed = streamed[0].select(q, cands, w.K, kinds=[B.KIND_TRANSFERS])
+    assert timed[0].tolist() == base[0].tolist() and np.array_equal(timed[1], base[1])
+    assert timed[2].ms_transfers > 0 and timed[2].bytes_streamed > 0
+    assert streamed[0].select(q, cands, w.K)[2].ms_transfers == 0 and base[2].ms_transfers == 0
     for p in streamed + [resident]:
         p.destroy()
 
