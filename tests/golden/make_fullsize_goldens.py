@@ -7,6 +7,7 @@
     python tests/golden/make_fullsize_goldens.py cfg4_8b three_way
     python tests/golden/make_fullsize_goldens.py cfg5_8b_stream drop_only
     python tests/golden/make_fullsize_goldens.py cfg5_8b_stream three_way
+    python tests/golden/make_fullsize_goldens.py cfg4_8b drop_only_w4
 
 Each takes 10 to 60 minutes on eight host cores.  What is stored, per scoring event (every evaluated pruning
 check of Sec. 4.1, plus the final scoring): the layer, the live candidates, their fp64 scores, the fates
@@ -16,6 +17,10 @@ written with repr(), so they read back bit for bit.
 The oracle walks one layer at a time over every live candidate (Sec. 3.3), so only one layer's fp64 weights
 need to exist at once: the weights handed to it are sequences that draw a layer, or a set of embedding rows,
 when it is asked for.
+
+A mode name ending in _w4 runs the oracle on the weights that the 4-bit layer format stands for: each of a layer's
+seven matrices goes through the oracle's own quantiser and back (Sec. 6 names the quantised variant; the format is this
+build's reading of it), norm gains and the embedding table stay as drawn.
 """
 import json
 import os
@@ -38,8 +43,8 @@ MODES = {"drop_only": O.MODE_DROP_ONLY, "three_way": O.MODE_THREE_WAY}
 class LazyLayers:
     """weights["layers"][l]: the fp64 tensors of layer l, drawn when asked for; the previous layer is released."""
 
-    def __init__(self, w):
-        self.w, self.at, self.cur = w, -1, None
+    def __init__(self, w, w4=False):
+        self.w, self.at, self.cur, self.w4 = w, -1, None, w4
 
     def __len__(self):
         return self.w.model.n_layers
@@ -47,7 +52,11 @@ class LazyLayers:
     def __getitem__(self, l):
         if l != self.at:
             self.cur = None
-            self.cur = {k: v.to(torch.float64).numpy() for k, v in W.make_layer(self.w, l).items()}
+            if self.w4:                                      # matrices (2-D) as code x scale, gains (1-D) as drawn
+                self.cur = {k: (O.dequantize_w4(*O.quantize_w4(v.float().numpy())) if v.ndim == 2
+                                else v.to(torch.float64).numpy()) for k, v in W.make_layer(self.w, l).items()}
+            else:
+                self.cur = {k: v.to(torch.float64).numpy() for k, v in W.make_layer(self.w, l).items()}
             self.at = l
         return self.cur
 
@@ -67,6 +76,8 @@ def golden_path(workload: str, mode: str) -> str:
 
 
 def main(workload: str, mode: str):
+    w4 = mode.endswith("_w4")
+    routing = mode[:-3] if w4 else mode
     w = W.WORKLOADS[workload]
     m = w.model
     t0 = time.time()
@@ -76,13 +87,13 @@ def main(workload: str, mode: str):
     final_norm = W.gaussian(w.seed, w.wname + "/final_norm", (m.hidden,), 1.0, 0.02, dt)
     f64 = lambda t: t.to(torch.float64).numpy()
     weights = {"embed": RowTable(table), "final_norm": f64(final_norm), "w_yes": f64(table[1]), "w_no": f64(table[0]),
-               "layers": LazyLayers(w)}
+               "layers": LazyLayers(w, w4)}
     q, cands = W.make_tokens(w)
     om = O.Model(m.n_layers, m.hidden, m.n_q_heads, m.n_kv_heads, m.head_dim, m.ffn, m.vocab, m.rms_eps, m.rope_base,
                  m.qk_norm, "exact")
     say(f"{workload} {mode}: inputs drawn, {sum(len(q) + len(c) for c in cands)} tokens")
     sel = O.select(q, cands, w.K, weights, om, checkpoints=w.checkpoints, n_clusters=w.n_clusters, tau=w.cv_threshold,
-                   mode=MODES[mode], progress=lambda l, n: say(f"layer {l} done, {n} live"))
+                   mode=MODES[routing], progress=lambda l, n: say(f"layer {l} done, {n} live"))
     events = []
     for ev in sel.events:
         events.append({
