@@ -10,7 +10,7 @@ from paper_2510_15620_amd import workloads as W
 from tests.helpers import checkpoint_margins, load_fullsize_golden
 
 CASES = [("cfg3_4b", "drop_only"), ("cfg3_4b", "three_way"), ("cfg4_8b", "drop_only"), ("cfg4_8b", "three_way"),
-         ("cfg5_8b_stream", "drop_only"), ("cfg5_8b_stream", "three_way")]
+         ("cfg5_8b_stream", "drop_only"), ("cfg5_8b_stream", "three_way"), ("cfg4_8b", "drop_only_w4")]
 
 
 @pytest.mark.parametrize("workload,mode", CASES)
@@ -18,7 +18,7 @@ def test_stored_oracle_run_is_self_consistent(workload, mode):
     g = load_fullsize_golden(workload, mode)
     w = W.WORKLOADS[workload]
     assert (g.K, g.n_cands, g.n_clusters, g.tau, g.checkpoints) == (w.K, w.n_cands, w.n_clusters, w.cv_threshold, list(w.checkpoints))
-    omode = O.MODE_DROP_ONLY if mode == "drop_only" else O.MODE_THREE_WAY
+    omode = O.MODE_DROP_ONLY if mode.startswith("drop_only") else O.MODE_THREE_WAY
     live = np.arange(w.n_cands)
     K_rem, early, early_scores, lens = w.K, [], [], (W.doc_lengths(w) + w.query_len)
     token_layers, prev_layer = 0, 0

@@ -99,20 +99,22 @@ class _HostTable:
         self.w_yes, self.w_no = wt.w_yes.clone(), wt.w_no.clone()
 
 
-def _make_ctx(w, wt, mode=B.MODE_DROP_ONLY, operand="f16", lean=False, hbm_cap_bytes=None, plain_order=False):
+def _make_ctx(w, wt, mode=B.MODE_DROP_ONLY, operand="f16", lean=False, hbm_cap_bytes=None, plain_order=False, w4=False):
     """lean: hidden-state offload and the embedding-table cache on top of the workload's own options.
     plain_order: every sequence with its own copy of the query and checked layers in one pass (the order of work the
-    offloaded mode always has)."""
+    offloaded mode always has).  w4: the layer matrices handed over as 4-bit blobs from the device quantiser."""
     weights = wt
+    layers = B.quantize_layers_w4(wt.layers) if w4 else wt.layers
     if w.stream_weights:
-        host = [{k: v.to("cpu").pin_memory() for k, v in l.items()} for l in wt.layers]
-        weights = W.Weights(wt.embed, host, wt.final_norm)
+        layers = [{k: v.to("cpu").pin_memory() for k, v in l.items()} for l in layers]
+    if w4 or w.stream_weights:
+        weights = W.Weights(wt.embed, layers, wt.final_norm)
     if lean:
         weights = _HostTable(weights)
     return B.Prism(w.model, weights, checkpoints=w.checkpoints, mode=mode, chunk_cands=w.chunk_cands,
                    hbm_cap_bytes=w.hbm_cap_bytes if hbm_cap_bytes is None else hbm_cap_bytes, stream_weights=w.stream_weights,
                    operand=operand, offload_hidden=lean, embed_on_host=lean, share_query=not plain_order,
-                   two_pass_checks=not plain_order)
+                   two_pass_checks=not plain_order, w4=w4)
 
 
 def _run_gpu(w, wt, **kw):
@@ -220,6 +222,17 @@ def test_cfg4_headline_against_the_complete_oracle_run(weights_8b):
     live = ~np.isnan(rep.scores[-1])
     assert np.array_equal(rep.scores[-1][live], rep0.scores[-1][live])
     assert rep.ms_total < rep0.ms_total                                  # pruning cuts the top-K latency
+
+
+def test_cfg4_with_4bit_layers_against_the_complete_oracle_run(weights_8b):
+    """The headline pool with every layer matrix handed over as a 4-bit blob (Sec. 6's quantised variant, in this build's
+    format): the stored oracle run used the oracle's own quantiser and the weights its codes stand for, the device path
+    its own quantiser and expansion, so the same survivor sets, scores and top-K mean that both agree end to end at full
+    size, not only on the small pool of tests/test_gpu_w4.py."""
+    w = W.WORKLOADS["cfg4_8b"]
+    gold = _need(w.name, "drop_only_w4")
+    idx, scores, rep, summary = _drop_only_against_golden(w, weights_8b, gold, w4=True)
+    assert rep.bytes_streamed == 0                                       # resident blobs: expanded on the device
 
 
 def _three_way_fates_and_output(w, idx, scores, rep, gold):
