@@ -8,8 +8,9 @@
     python tests/golden/make_fullsize_goldens.py cfg5_8b_stream drop_only
     python tests/golden/make_fullsize_goldens.py cfg5_8b_stream three_way
     python tests/golden/make_fullsize_goldens.py cfg4_8b drop_only_w4
+    python tests/golden/make_fullsize_goldens.py cfg5_8b_stream drop_only_w4
 
-Each takes 10 to 60 minutes on eight host cores.  What is stored, per scoring event (every evaluated pruning
+Each takes 10 to 70 minutes on eight host cores.  What is stored, per scoring event (every evaluated pruning
 check of Sec. 4.1, plus the final scoring): the layer, the live candidates, their fp64 scores, the fates
 (2 selected / 1 deferred / 0 dropped) and who continues; then the returned top-K with its scores.  Floats are
 written with repr(), so they read back bit for bit.

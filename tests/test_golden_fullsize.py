@@ -10,7 +10,8 @@ from paper_2510_15620_amd import workloads as W
 from tests.helpers import checkpoint_margins, load_fullsize_golden
 
 CASES = [("cfg3_4b", "drop_only"), ("cfg3_4b", "three_way"), ("cfg4_8b", "drop_only"), ("cfg4_8b", "three_way"),
-         ("cfg5_8b_stream", "drop_only"), ("cfg5_8b_stream", "three_way"), ("cfg4_8b", "drop_only_w4")]
+         ("cfg5_8b_stream", "drop_only"), ("cfg5_8b_stream", "three_way"), ("cfg4_8b", "drop_only_w4"),
+         ("cfg5_8b_stream", "drop_only_w4")]
 
 
 @pytest.mark.parametrize("workload,mode", CASES)
