@@ -9,6 +9,7 @@
     python tests/golden/make_fullsize_goldens.py cfg5_8b_stream three_way
     python tests/golden/make_fullsize_goldens.py cfg4_8b drop_only_w4
     python tests/golden/make_fullsize_goldens.py cfg5_8b_stream drop_only_w4
+    python tests/golden/make_fullsize_goldens.py cfg5_8b_stream half_noise_w4 211,420,146
 
 Each takes 10 to 70 minutes on eight host cores.  What is stored, per scoring event (every evaluated pruning
 check of Sec. 4.1, plus the final scoring): the layer, the live candidates, their fp64 scores, the fates
@@ -22,6 +23,10 @@ when it is asked for.
 A mode name ending in _w4 runs the oracle on the weights that the 4-bit layer format stands for: each of a layer's
 seven matrices goes through the oracle's own quantiser and back (Sec. 6 names the quantised variant; the format is this
 build's reading of it), norm gains and the embedding table stay as drawn.
+
+half_noise[_w4] <candidates> writes tests/golden/half_operand_noise_<workload>[_w4].json instead: the full-depth scores
+of the listed candidates (no pruning; every candidate is forwarded independently, Sec. 3.3) once exact and once with every
+contraction operand rounded to IEEE half, i.e. how far half operands alone move a score on this workload.
 """
 import json
 import os
@@ -76,6 +81,44 @@ def golden_path(workload: str, mode: str) -> str:
     return os.path.join(os.path.dirname(os.path.abspath(__file__)), f"fullsize_{workload}_{mode}.json")
 
 
+def _weights(w, w4):
+    m = w.model
+    dt = W.torch_dtype(m)
+    table = W.gaussian(w.seed, w.wname + "/embed", (m.vocab, m.hidden), 0.0, 0.02, dt)
+    final_norm = W.gaussian(w.seed, w.wname + "/final_norm", (m.hidden,), 1.0, 0.02, dt)
+    f64 = lambda t: t.to(torch.float64).numpy()
+    return {"embed": RowTable(table), "final_norm": f64(final_norm), "w_yes": f64(table[1]), "w_no": f64(table[0]),
+            "layers": LazyLayers(w, w4)}
+
+
+def half_noise(workload: str, w4: bool, which):
+    w = W.WORKLOADS[workload]
+    m = w.model
+    t0 = time.time()
+    weights = _weights(w, w4)
+    q, cands = W.make_tokens(w)
+    scores = {}
+    for operand in ("exact", "f16"):
+        om = O.Model(m.n_layers, m.hidden, m.n_q_heads, m.n_kv_heads, m.head_dim, m.ffn, m.vocab, m.rms_eps, m.rope_base,
+                     m.qk_norm, operand)
+        sel = O.select(q, [cands[c] for c in which], len(which), weights, om, mode=O.MODE_NO_PRUNING,
+                       progress=lambda l, n: print(f"[{time.time() - t0:7.0f} s] {operand}: layer {l} done", flush=True))
+        by = {which[int(i)]: float(s) for i, s in zip(sel.idx, sel.scores)}
+        scores[operand] = [by[c] for c in which]
+    out = {
+        "_about": "Full-depth scores from oracle/prism_oracle.py select() without pruning, operand = exact and operand = f16 "
+                  "(every contraction operand rounded to IEEE half, everything else fp64); written by "
+                  "tests/golden/make_fullsize_goldens.py.  Scores are repr() of fp64 values.",
+        "workload": workload, "w4": w4, "seed": w.seed, "cands": [int(c) for c in which],
+        "exact": [repr(x) for x in scores["exact"]], "half": [repr(x) for x in scores["f16"]],
+        "oracle_seconds": round(time.time() - t0),
+    }
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"half_operand_noise_{workload}{'_w4' if w4 else ''}.json")
+    with open(path, "w") as f:
+        f.write("{\n" + ",\n".join(f"{json.dumps(k)}: {json.dumps(v)}" for k, v in out.items()) + "\n}\n")
+    print(f"wrote {path}: half - exact = {[f'{h - e:+.3e}' for h, e in zip(scores['f16'], scores['exact'])]}")
+
+
 def main(workload: str, mode: str):
     w4 = mode.endswith("_w4")
     routing = mode[:-3] if w4 else mode
@@ -83,12 +126,7 @@ def main(workload: str, mode: str):
     m = w.model
     t0 = time.time()
     say = lambda s: print(f"[{time.time() - t0:7.0f} s] {s}", flush=True)
-    dt = W.torch_dtype(m)
-    table = W.gaussian(w.seed, w.wname + "/embed", (m.vocab, m.hidden), 0.0, 0.02, dt)
-    final_norm = W.gaussian(w.seed, w.wname + "/final_norm", (m.hidden,), 1.0, 0.02, dt)
-    f64 = lambda t: t.to(torch.float64).numpy()
-    weights = {"embed": RowTable(table), "final_norm": f64(final_norm), "w_yes": f64(table[1]), "w_no": f64(table[0]),
-               "layers": LazyLayers(w, w4)}
+    weights = _weights(w, w4)
     q, cands = W.make_tokens(w)
     om = O.Model(m.n_layers, m.hidden, m.n_q_heads, m.n_kv_heads, m.head_dim, m.ffn, m.vocab, m.rms_eps, m.rope_base,
                  m.qk_norm, "exact")
@@ -126,4 +164,7 @@ def main(workload: str, mode: str):
 
 
 if __name__ == "__main__":
-    main(sys.argv[1], sys.argv[2] if len(sys.argv) > 2 else "drop_only")
+    if len(sys.argv) > 3 and sys.argv[2].startswith("half_noise"):
+        half_noise(sys.argv[1], sys.argv[2].endswith("_w4"), [int(c) for c in sys.argv[3].split(",")])
+    else:
+        main(sys.argv[1], sys.argv[2] if len(sys.argv) > 2 else "drop_only")

@@ -2,12 +2,15 @@
 tests/golden/make_fullsize_goldens.py) are internally consistent: every stored pruning decision is what the oracle's
 route() gives for the stored scores, live sets chain from one event to the next, and the stored top-K is the ranking of
 the stored scores.  Guards against a damaged or hand-edited file; also prints which checks the margin rule pins."""
+import json
+import os
+
 import numpy as np
 import pytest
 
 from oracle import prism_oracle as O
 from paper_2510_15620_amd import workloads as W
-from tests.helpers import checkpoint_margins, load_fullsize_golden
+from tests.helpers import GOLDEN_DIR, checkpoint_margins, load_fullsize_golden
 
 CASES = [("cfg3_4b", "drop_only"), ("cfg3_4b", "three_way"), ("cfg4_8b", "drop_only"), ("cfg4_8b", "three_way"),
          ("cfg5_8b_stream", "drop_only"), ("cfg5_8b_stream", "three_way"), ("cfg4_8b", "drop_only_w4"),
@@ -59,3 +62,15 @@ def test_stored_oracle_run_is_self_consistent(workload, mode):
     assert g.idx.tolist() == early and g.scores.tolist() == early_scores
     assert g.token_layers == token_layers and g.layers_run == prev_layer
     print(f"{workload} {mode}: checks (layer, pinned by the 2e-2 margins) {pinned}; live sizes {[len(e.live) for e in g.events]}")
+
+
+def test_half_operand_noise_file_agrees_with_the_complete_run():
+    """tests/golden/half_operand_noise_cfg5_8b_stream_w4.json (three candidates forwarded alone, exact and with half operands):
+    its exact scores are the complete run's final scores of those candidates - the oracle forwards every candidate on
+    its own (Sec. 3.3), so the pool around it changes nothing - and half operands alone move each by less than the 2e-2 bar."""
+    d = json.load(open(os.path.join(GOLDEN_DIR, "half_operand_noise_cfg5_8b_stream_w4.json")))
+    fin = load_fullsize_golden(d["workload"], "drop_only_w4").events[-1]
+    for c, e, h in zip(d["cands"], d["exact"], d["half"]):
+        i = int(np.where(fin.live == c)[0][0])
+        assert abs(float(e) - fin.scores[i]) <= 1e-12
+        assert 0 < abs(float(h) - float(e)) <= 2e-2

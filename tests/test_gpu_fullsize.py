@@ -15,6 +15,7 @@ live set, fp64 scores, fates and survivors, and the final top-K.  The comparison
   4. the returned top-K is the oracle's, in the oracle's order wherever adjacent oracle scores differ by more than 4e-2;
      candidates inside such a near-tie may swap places.
 """
+import json
 import os
 import time
 
@@ -353,12 +354,17 @@ def test_cfg5_with_4bit_layers_streams_a_quarter_of_the_bytes(weights_8b):
     scores after layer 36 one does not: candidate 211 (1062 tokens) is off by 2.30e-2, the next ones by 1.84e-2 and
     1.74e-2, with an r.m.s. of 1.0e-2 over the 20 - the error grows smoothly with depth (r.m.s. 2.8e-3 after layer 4),
     as accumulated rounding of half operands does on random weights; the oracle's own forward with half operands differs
-    from its exact one by -6.7e-3, -9.0e-3 and -3.9e-3 on those three candidates (same signs).  The bar on the final
-    scores of this variant is therefore 3e-2, and the ranking rule (same order wherever the oracle's scores differ by
-    more than 4e-2) is unchanged."""
+    from its exact one by -6.7e-3, -9.0e-3 and -3.9e-3 on those three candidates (same signs; stored in
+    tests/golden/half_operand_noise_cfg5_8b_stream_w4.json), and against THAT forward the device is within 2e-2 on all
+    three, which is asserted below.  The bar against the exact run on the final scores of this variant is 3e-2, and the
+    ranking rule (same order wherever the oracle's scores differ by more than 4e-2) is unchanged."""
     w = W.WORKLOADS["cfg5_8b_stream"]
     gold = _need(w.name, "drop_only_w4")
     idx, scores, rep, summary = _drop_only_against_golden(w, weights_8b, gold, tol_final=3e-2, w4=True)
+    # the three worst candidates against the oracle in the device's operand precision (stored beside the complete run)
+    noise = json.load(open(os.path.join(os.path.dirname(golden_path(w.name, "drop_only_w4")), "half_operand_noise_cfg5_8b_stream_w4.json")))
+    for c, h in zip(noise["cands"], noise["half"]):
+        assert abs(float(rep.scores[-1][c]) - float(h)) <= TOL, (c, rep.scores[-1][c], h)
     plain = w.model.n_layers * sum(v.numel() * 2 for v in weights_8b.layers[0].values())
     assert 0.25 * plain < rep.bytes_streamed < 0.27 * plain
     assert rep.peak_hbm_bytes <= w.hbm_cap_bytes
